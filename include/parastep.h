@@ -1,0 +1,190 @@
+/*
+ * parastep.h -- C ABI of the MI355X (gfx950) hot path of reuse-then-predict
+ * diffusion denoising.
+ *
+ * The paper states the problem as  eps_t = eps_theta(x_t, t, c);
+ * x_{t-1} = Scheduler(x_t, t, eps_t)  (Preliminaries, "Denoising computation"),
+ * measures similarity with the relative MAE of Eq. (1), and wraps the loop in the
+ * round-based reuse-then-predict procedure of Appendix A, Algorithm 1 (batched on one
+ * device in Section 3.3).  Each entry point below is one of those operations.
+ *
+ * Conventions for every function:
+ *  - returns PS_OK (0) or a negative ps_status; never throws, exits or prints;
+ *  - arguments are validated on the host before any launch, so a failing call has
+ *    no side effects on device memory;
+ *  - "DEVICE" pointers are HIP device memory owned by the caller (e.g. PyTorch
+ *    tensors); the library never allocates, frees or keeps device memory.  "HOST"
+ *    pointers are ordinary host memory read during the call only;
+ *  - work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = the
+ *    default stream) and the call returns without synchronising; outputs, including
+ *    device-side sums, are valid once the caller has synchronised that stream;
+ *  - results are deterministic: no floating-point atomics, fixed reduction order;
+ *  - calls on one `dit` handle must not overlap; distinct handles/streams may.
+ */
+#ifndef PARASTEP_H
+#define PARASTEP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#if defined(__GNUC__)
+#define PS_API __attribute__((visibility("default")))
+#else
+#define PS_API
+#endif
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PS_OK = 0,
+    PS_ERR_NULL = -1,       /* a required pointer is NULL */
+    PS_ERR_SHAPE = -2,      /* inconsistent or unsupported sizes */
+    PS_ERR_DTYPE = -3,      /* unknown ps_dtype */
+    PS_ERR_WORKSPACE = -4,  /* workspace missing, misaligned (256 B) or too small */
+    PS_ERR_SCHEDULE = -5,   /* invalid sampling schedule */
+    PS_ERR_HIP = -6         /* a HIP runtime call or launch failed */
+} ps_status;
+
+/* Storage / operand type of matrices and activations fed to contractions.
+ * Accumulators, LayerNorm statistics, softmax statistics, the residual stream,
+ * modulation vectors, biases, latents and eps are always fp32. */
+typedef enum { PS_F32 = 0, PS_BF16 = 1 } ps_dtype;
+
+/* Static message for a status code. */
+PS_API const char* ps_strerror(int status);
+
+/* ------------------------------------------------------------------ noise predictor
+ * eps_theta is a DiT with full 3D attention (Section 1: cost quadratic in spatial and
+ * temporal length).  Tokens are the text tokens followed by one token per
+ * (frame, patch row, patch col) of the latent, patch vector ordered (c, dy, dx).
+ * Requirements: hidden == heads*head_dim, head_dim % 16 == 0 (3D RoPE splits it
+ * d/4, 3d/8, 3d/8 into interleaved pairs), height and width divisible by patch,
+ * hidden even, text_tokens >= 0, layers <= 64. */
+typedef struct {
+    int layers, hidden, heads, head_dim, mlp_ratio;
+    int in_channels, patch, frames, height, width;   /* latent [C, F, H, W] */
+    int text_tokens, time_embed_dim;
+    int dtype;                                        /* ps_dtype */
+    float ln_eps, rope_theta;
+} dit_config;
+
+typedef struct dit dit;   /* opaque host object */
+
+/* Number of weight tensors dit_create expects for `layers` layers: 6 + 10*layers + 4. */
+PS_API int dit_num_weights(int layers);
+
+/* Create a predictor.  `weights` is a HOST array of n_weights DEVICE pointers in the
+ * order  W_pe b_pe W_t1 b_t1 W_t2 b_t2, then per layer  W_mod b_mod W_qkv b_qkv W_o
+ * b_o W_1 b_1 W_2 b_2,  then  W_fm b_fm W_out b_out.  Matrices are row-major
+ * [out_features, in_features] in cfg->dtype; biases are fp32.  The tensors are
+ * borrowed: the caller keeps them alive and unchanged while the handle exists.
+ * The handle owns only host memory and a few HIP events. */
+PS_API int dit_create(const dit_config* cfg, const void* const* weights, int n_weights, dit** out);
+PS_API int dit_destroy(dit* d);
+
+/* Bytes of DEVICE workspace dit_forward needs for `batch` samples (0 on bad input). */
+PS_API size_t dit_workspace_bytes(const dit* d, int batch);
+
+/* eps_out[b] = eps_theta(x[b], t_host[b], ctx[b]) for b < batch.
+ *   x        DEVICE fp32 [B, C, F, H, W]
+ *   ctx      DEVICE cfg.dtype [B, text_tokens, hidden]; may be NULL iff text_tokens == 0
+ *   t_host   HOST int32 [B], per-sample timestep (0 <= t < 100000)
+ *   eps_out  DEVICE fp32 [B, C, F, H, W]; must not alias x
+ *   workspace DEVICE, 256-byte aligned, >= dit_workspace_bytes(d, batch); scratch only */
+PS_API int dit_forward(dit* d, const float* x, const void* ctx, const int32_t* t_host, float* eps_out,
+                int batch, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Optional per-kernel-class timing of dit_forward with HIP events on its stream.
+ * Classes: 0 attention, 1 qkv GEMM, 2 out-proj GEMM, 3 fc1 GEMM, 4 fc2 GEMM,
+ * 5 LayerNorm+modulate, 6 everything else.  dit_profile_read synchronises the
+ * recorded events and returns accumulated milliseconds and launch counts since the
+ * last dit_profile_enable(d, 1); both arrays are HOST [7]. */
+PS_API int dit_profile_enable(dit* d, int on);
+PS_API int dit_profile_read(dit* d, double* ms_out, int64_t* launches_out);
+
+/* Stand-alone full attention: for every batch and head, O = softmax(scale*Q K^T) V
+ * over all `seq` tokens (no mask, Section 1's "3D attention": one token axis holding
+ * text tokens and the flattened frame/row/col grid).  q, k, v, o: DEVICE
+ * [B, seq, heads, head_dim] contiguous in `dtype`, 16-byte aligned; o must not alias
+ * the inputs.  seq >= 1, scale > 0, head_dim in {16, 32, 64}.
+ * workspace: DEVICE, 256-byte aligned, >= attn3d_workspace_bytes(...) (may be NULL when
+ * that is 0); scratch only. */
+PS_API size_t attn3d_workspace_bytes(int batch, int seq, int heads, int head_dim, int dtype);
+PS_API int attn3d(const void* q, const void* k, const void* v, void* o,
+           int batch, int seq, int heads, int head_dim, float scale, int dtype,
+           void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* The projection every DiT sub-layer uses, exposed for per-kernel parity and timing:
+ * out[M, n_out] = act(a[M, k] * w[n_out, k]^T + bias), act 0 = none, 1 = tanh-GELU.
+ * a, w, out DEVICE in `dtype`, row-major, 16-byte aligned; bias DEVICE fp32 [n_out].
+ * n_out even, k % 8 == 0. */
+PS_API int dit_linear(const void* a, const void* w, const float* bias, void* out, int m, int n_out, int k,
+               int act, int dtype, void* hip_stream);
+
+/* Test hook: 0 = pick the fastest kernel for each shape (default), 1 = always use the
+ * generic fp32-FMA kernels.  Process-wide; returns the previous value. */
+PS_API int ps_set_kernel_path(int path);
+
+/* ------------------------------------------------------------- scheduler and metric
+ * Fused DDIM update  x_out = a*x + b*eps  (the element-wise Scheduler of the paper's
+ * Section 3) and, if sums4 != NULL, the four sums behind the adjacent-step relative
+ * MAEs of Eq. (1):  sums4 = { sum|x_out-x|, sum|x_out|, sum|eps-eps_prev|, sum|eps| }
+ * (the last two use eps_prev; with eps_prev == NULL they are 0 and sum|eps|).
+ * x_out may alias x.  workspace: DEVICE, >= sampler_step_workspace_bytes(n), only
+ * needed when sums4 != NULL. */
+PS_API size_t sampler_step_workspace_bytes(size_t n);
+PS_API int sampler_step(const float* x, const float* eps, const float* eps_prev, float* x_out,
+                 float a, float b, size_t n, float* sums4,
+                 void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Relative MAE of Eq. (1): out3 = { sum|a-b|, sum|a|, sum|a-b| / sum|a| } (DEVICE fp32).
+ * The denominator is the FIRST argument; a zero denominator yields inf or nan. */
+PS_API size_t rel_mae_workspace_bytes(size_t n);
+PS_API int rel_mae(const float* a, const float* b, size_t n, float* out3,
+            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Host-only: DDIM grid and coefficients for a linear beta schedule, computed in
+ * double.  tau_i = (steps-1-i)*floor(train_steps/steps); a_i = sqrt(abar_prev/abar_tau),
+ * b_i = sqrt(1-abar_prev) - a_i*sqrt(1-abar_tau), abar_prev = 1 after the last step.
+ * Outputs are HOST arrays of length `steps`. */
+PS_API int ddim_coefficients(int train_steps, double beta_start, double beta_end, int steps,
+                      int32_t* timesteps_out, float* a_out, float* b_out);
+
+/* ------------------------------------------------------------- reuse-then-predict run
+ * Algorithm 1 with all ranks of a cycle simulated on one device.
+ *   warmup     first `warmup` steps run the original process; must be >= 1 unless
+ *              every cycle has length 1
+ *   cycle_len  HOST [n_cycles] cycle length (= parallel degree p) of each cycle after
+ *              warm-up; they must cover steps - warmup; the last may be cut short
+ *   batched    0: one predictor call per step (rank == round evaluates);
+ *              1: one call per cycle with batch = cycle length (Section 3.3)
+ *   mode       0 reuse-then-predict, 1 direct reuse (predict only in round 0) */
+typedef struct {
+    int steps;
+    const int32_t* timesteps;   /* HOST [steps], descending */
+    const float* coef_a;        /* HOST [steps] */
+    const float* coef_b;        /* HOST [steps] */
+    int warmup;
+    int n_cycles;
+    const int32_t* cycle_len;
+    int batched;
+    int mode;
+} sampler_schedule;
+
+PS_API size_t sampler_workspace_bytes(const dit* d, const sampler_schedule* s);
+
+/* x_T, x0_out: DEVICE fp32 [C,F,H,W] (one sample; may alias each other).
+ * ctx as in dit_forward with B = 1 (it is shared by all ranks).
+ * step_sums: DEVICE fp32 [steps][4] or NULL; row i holds sampler_step's sums4 for the
+ * update rank 0 takes at step i (row 0's eps_prev terms are 0, sum|eps|).
+ * calls_out: HOST, optional; receives the number of predictor launches. */
+PS_API int sampler_run(dit* d, const sampler_schedule* s, const float* x_T, const void* ctx,
+                float* x0_out, float* step_sums, int* calls_out,
+                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PARASTEP_H */

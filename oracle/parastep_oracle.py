@@ -224,7 +224,13 @@ def dit_forward(cfg, W: Dict[str, np.ndarray], x, ctx, t, taps: Optional[list] =
     B = x.shape[0]
     D, H, d, Lt = cfg.hidden, cfg.heads, cfg.head_dim, cfg.text_tokens
     Nv, N = cfg.video_tokens, cfg.tokens
-    Wd = {k: np.asarray(v, dtype=F64) for k, v in W.items()}
+
+    class _Widen(dict):
+        # weights are widened to float64 where they are used, one tensor at a time
+        def __getitem__(self, key):
+            return np.asarray(W[key], dtype=F64)
+
+    Wd = _Widen()
     angles = rope3d_angles(cfg.grid, d, cfg.rope_theta)
     out = np.empty_like(x)
     for b in range(B):

@@ -1,0 +1,610 @@
+// C ABI: argument validation, the DiT forward schedule, and the reuse-then-predict run
+// (Algorithm 1 with every rank of a cycle simulated on one device).
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "common.h"
+
+using namespace ps;
+
+namespace {
+
+constexpr int MAX_BATCH = 16;
+constexpr int MAX_LAYERS = 64;
+constexpr int N_CLASSES = 7;
+enum KClass { KC_ATTN = 0, KC_QKV = 1, KC_OPROJ = 2, KC_FC1 = 3, KC_FC2 = 4, KC_LN = 5, KC_OTHER = 6 };
+
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+inline bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+struct LayerW { const void *W_mod, *W_qkv, *W_o, *W_1, *W_2; const float *b_mod, *b_qkv, *b_o, *b_1, *b_2; };
+
+}  // namespace
+
+struct dit {
+    dit_config cfg;
+    const void *W_pe, *W_t1, *W_t2, *W_fm, *W_out;
+    const float *b_pe, *b_t1, *b_t2, *b_fm, *b_out;
+    std::vector<LayerW> layers;
+    int Hp, Wp, Nv, N, P;
+    size_t esize;
+    // profiling
+    bool profiling = false;
+    std::vector<hipEvent_t> ev;           // pairs: start, stop
+    std::vector<int> ev_class;
+    size_t ev_used = 0;
+    double prof_ms[N_CLASSES] = {0};
+    int64_t prof_n[N_CLASSES] = {0};
+};
+
+namespace {
+
+struct WsLayout {
+    size_t X, H, QKV, mod, modf, sinus, hid, cvec, rcos, rsin, attn, total;
+};
+
+WsLayout ws_layout(const dit* d, int batch) {
+    const dit_config& c = d->cfg;
+    size_t M = (size_t)batch * d->N, D = c.hidden;
+    WsLayout w;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return o; };
+    w.X = take(M * D * 4);
+    w.H = take(M * D * d->esize);                                  // LN output / attention output
+    size_t wide = (size_t)(c.mlp_ratio > 3 ? c.mlp_ratio : 3);
+    w.QKV = take(M * wide * D * d->esize);                         // qkv, later the MLP hidden
+    w.mod = take((size_t)batch * c.layers * 12 * D * 4);
+    w.modf = take((size_t)batch * 2 * D * 4);
+    w.sinus = take((size_t)batch * D * 4);
+    w.hid = take((size_t)batch * c.time_embed_dim * 4);
+    w.cvec = take((size_t)batch * c.time_embed_dim * 4);
+    w.rcos = take((size_t)d->Nv * (c.head_dim / 2) * 4);
+    w.rsin = take((size_t)d->Nv * (c.head_dim / 2) * 4);
+    w.attn = take(attention_workspace_bytes(c.dtype, batch, d->N, c.heads, c.head_dim));
+    w.total = off;
+    return w;
+}
+
+struct Prof {
+    dit* d;
+    hipStream_t st;
+    hipError_t begin(int cls, hipEvent_t* stop) {
+        *stop = nullptr;
+        if (!d->profiling) return hipSuccess;
+        if (d->ev_used + 2 > d->ev.size()) {
+            hipEvent_t a, b;
+            hipError_t e = hipEventCreate(&a);
+            if (e != hipSuccess) return e;
+            e = hipEventCreate(&b);
+            if (e != hipSuccess) { hipEventDestroy(a); return e; }
+            d->ev.push_back(a);
+            d->ev.push_back(b);
+            d->ev_class.push_back(cls);
+        }
+        d->ev_class[d->ev_used / 2] = cls;
+        hipError_t e = hipEventRecord(d->ev[d->ev_used], st);
+        *stop = d->ev[d->ev_used + 1];
+        d->ev_used += 2;
+        return e;
+    }
+    hipError_t end(hipEvent_t stop) { return stop ? hipEventRecord(stop, st) : hipSuccess; }
+};
+
+#define PS_TRY(expr)                         \
+    do {                                     \
+        hipError_t e__ = (expr);             \
+        if (e__ != hipSuccess) return PS_ERR_HIP; \
+    } while (0)
+
+#define PS_TIMED(cls, expr)                  \
+    do {                                     \
+        hipEvent_t stop__;                   \
+        PS_TRY(prof.begin(cls, &stop__));    \
+        PS_TRY(expr);                        \
+        PS_TRY(prof.end(stop__));            \
+    } while (0)
+
+int validate_forward(const dit* d, const float* x, const void* ctx, const int32_t* t_host,
+                     const float* eps_out, int batch, const void* ws, size_t ws_bytes) {
+    if (!d || !x || !t_host || !eps_out) return PS_ERR_NULL;
+    if (d->cfg.text_tokens > 0 && !ctx) return PS_ERR_NULL;
+    if (batch < 1 || batch > MAX_BATCH) return PS_ERR_SHAPE;
+    if (x == eps_out) return PS_ERR_SHAPE;
+    if (!aligned(x, 16) || !aligned(eps_out, 16) || (ctx && !aligned(ctx, 16))) return PS_ERR_SHAPE;
+    for (int b = 0; b < batch; ++b)
+        if (t_host[b] < 0 || t_host[b] >= 100000) return PS_ERR_SHAPE;
+    if (!ws || !aligned(ws, 256) || ws_bytes < dit_workspace_bytes(d, batch)) return PS_ERR_WORKSPACE;
+    return PS_OK;
+}
+
+// ctx_shared: every sample reads the same [text_tokens, hidden] context (the ranks of a
+// reuse-then-predict cycle share one prompt).
+int forward_impl(dit* d, const float* x, const void* ctx, const int32_t* t_host, float* eps_out,
+                 int batch, void* workspace, hipStream_t st, bool ctx_shared = false) {
+    const dit_config& c = d->cfg;
+    const int D = c.hidden, Dt = c.time_embed_dim, L = c.layers, N = d->N, M = batch * N;
+    const int dt = c.dtype;
+    WsLayout w = ws_layout(d, batch);
+    char* base = (char*)workspace;
+    float* X = (float*)(base + w.X);
+    void* Hb = base + w.H;
+    void* QKV = base + w.QKV;
+    float* mod = (float*)(base + w.mod);
+    float* modf = (float*)(base + w.modf);
+    float* sinus = (float*)(base + w.sinus);
+    float* hid = (float*)(base + w.hid);
+    float* cvec = (float*)(base + w.cvec);
+    float* rcos = (float*)(base + w.rcos);
+    float* rsin = (float*)(base + w.rsin);
+    void* attn_ws = attention_workspace_bytes(dt, batch, N, c.heads, c.head_dim) ? base + w.attn : nullptr;
+    Prof prof{d, st};
+    TokenGeom geom{N, c.text_tokens};
+    const long mod_bs = (long)L * 12 * D;
+
+    // time conditioning: c = SiLU(W_t2 SiLU(W_t1 s(t) + b_t1) + b_t2); all modulation vectors
+    PS_TIMED(KC_OTHER, launch_sinusoid(t_host, sinus, batch, D, st));
+    PS_TIMED(KC_OTHER, launch_gemv(dt, d->W_t1, d->b_t1, sinus, hid, Dt, D, batch, D, Dt, 1, st));
+    PS_TIMED(KC_OTHER, launch_gemv(dt, d->W_t2, d->b_t2, hid, cvec, Dt, Dt, batch, Dt, Dt, 1, st));
+    for (int l = 0; l < L; ++l)
+        PS_TIMED(KC_OTHER, launch_gemv(dt, d->layers[l].W_mod, d->layers[l].b_mod, cvec, mod + (long)l * 12 * D,
+                                       12 * D, Dt, batch, Dt, mod_bs, 0, st));
+    PS_TIMED(KC_OTHER, launch_gemv(dt, d->W_fm, d->b_fm, cvec, modf, 2 * D, Dt, batch, Dt, 2 * D, 0, st));
+    PS_TIMED(KC_OTHER, launch_rope_table(rcos, rsin, c.frames, d->Hp, d->Wp, c.head_dim, c.rope_theta, st));
+    PS_TIMED(KC_OTHER, launch_patch_embed(dt, x, ctx, d->W_pe, d->b_pe, X, batch, c.in_channels, c.frames,
+                                          c.height, c.width, c.patch, c.text_tokens, D,
+                                          ctx_shared ? 0L : (long)c.text_tokens * D, st));
+
+    const size_t es = d->esize;
+    AttnStrides as;
+    as.q_tok = as.k_tok = as.v_tok = 3L * D;
+    as.q_head = as.k_head = as.v_head = c.head_dim;
+    as.q_batch = as.k_batch = as.v_batch = (long)N * 3 * D;
+    as.o_tok = D; as.o_head = c.head_dim; as.o_batch = (long)N * D;
+    const float scale = 1.0f / sqrtf((float)c.head_dim);
+
+    for (int l = 0; l < L; ++l) {
+        const LayerW& lw = d->layers[l];
+        const float* mod_l = mod + (long)l * 12 * D;
+        // h = LN(X)(1+scale_a)+shift_a
+        PS_TIMED(KC_LN, launch_ln_modulate(dt, X, Hb, M, D, c.ln_eps, mod_l, mod_bs, 0, 1, geom, st));
+        // [q|k|v] = W_qkv h + b, rotary on video q,k
+        Epilogue eq{};
+        eq.kind = EPI_QKV_ROPE; eq.bias = lw.b_qkv; eq.D = D; eq.geom = geom;
+        eq.rope_cos = rcos; eq.rope_sin = rsin; eq.head_dim = c.head_dim;
+        PS_TIMED(KC_QKV, launch_gemm(dt, Hb, lw.W_qkv, QKV, M, 3 * D, D, eq, st));
+        // o = attention(q, k, v) -> Hb (token-major, heads concatenated)
+        const char* qp = (const char*)QKV;
+        PS_TIMED(KC_ATTN, launch_attention(dt, qp, qp + (size_t)D * es, qp + (size_t)2 * D * es, Hb, batch, N,
+                                           c.heads, c.head_dim, scale, as, attn_ws, st));
+        // X += gate_a * (W_o o + b_o)
+        Epilogue eo{};
+        eo.kind = EPI_GATE_RESIDUAL; eo.bias = lw.b_o; eo.resid = X; eo.mod_layer = mod_l;
+        eo.mod_batch_stride = mod_bs; eo.gate_chunk = 2; eo.D = D; eo.geom = geom;
+        PS_TIMED(KC_OPROJ, launch_gemm(dt, Hb, lw.W_o, nullptr, M, D, D, eo, st));
+        // h2 = LN(X)(1+scale_m)+shift_m ; u = GELU(W_1 h2 + b_1) ; X += gate_m * (W_2 u + b_2)
+        PS_TIMED(KC_LN, launch_ln_modulate(dt, X, Hb, M, D, c.ln_eps, mod_l, mod_bs, 3, 4, geom, st));
+        Epilogue e1{};
+        e1.kind = EPI_BIAS_GELU; e1.bias = lw.b_1;
+        PS_TIMED(KC_FC1, launch_gemm(dt, Hb, lw.W_1, QKV, M, c.mlp_ratio * D, D, e1, st));
+        Epilogue e2 = eo;
+        e2.bias = lw.b_2; e2.gate_chunk = 5;
+        PS_TIMED(KC_FC2, launch_gemm(dt, QKV, lw.W_2, nullptr, M, D, c.mlp_ratio * D, e2, st));
+    }
+    PS_TIMED(KC_OTHER, launch_final_proj(dt, X, modf, d->W_out, d->b_out, eps_out, batch, c.in_channels, c.frames,
+                                         c.height, c.width, c.patch, c.text_tokens, D, c.ln_eps, st));
+    return PS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ps_strerror(int status) {
+    switch (status) {
+        case PS_OK: return "ok";
+        case PS_ERR_NULL: return "a required pointer is NULL";
+        case PS_ERR_SHAPE: return "inconsistent or unsupported sizes";
+        case PS_ERR_DTYPE: return "unknown dtype";
+        case PS_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case PS_ERR_SCHEDULE: return "invalid sampling schedule";
+        case PS_ERR_HIP: return "HIP runtime call or kernel launch failed";
+        default: return "unknown status";
+    }
+}
+
+int ps_set_kernel_path(int path) {
+    int old = get_kernel_path();
+    set_kernel_path(path ? 1 : 0);
+    return old;
+}
+
+int dit_num_weights(int layers) { return layers < 0 ? 0 : 6 + 10 * layers + 4; }
+
+int dit_create(const dit_config* cfg, const void* const* weights, int n_weights, dit** out) {
+    if (!cfg || !weights || !out) return PS_ERR_NULL;
+    *out = nullptr;
+    const dit_config& c = *cfg;
+    if (c.dtype != PS_F32 && c.dtype != PS_BF16) return PS_ERR_DTYPE;
+    if (c.layers < 1 || c.layers > MAX_LAYERS || c.hidden < 1 || c.heads < 1 || c.head_dim < 1) return PS_ERR_SHAPE;
+    if (c.hidden != c.heads * c.head_dim || c.head_dim % 16 != 0) return PS_ERR_SHAPE;
+    if (c.head_dim != 16 && c.head_dim != 32 && c.head_dim != 64) return PS_ERR_SHAPE;
+    if (c.hidden % 8 != 0 || c.hidden > 2048) return PS_ERR_SHAPE;
+    if (c.mlp_ratio < 1 || c.mlp_ratio > 8) return PS_ERR_SHAPE;
+    if (c.in_channels < 1 || c.patch < 1 || c.frames < 1 || c.height < 1 || c.width < 1) return PS_ERR_SHAPE;
+    if (c.height % c.patch || c.width % c.patch) return PS_ERR_SHAPE;
+    if (c.text_tokens < 0 || c.time_embed_dim < 1) return PS_ERR_SHAPE;
+    if ((long)c.in_channels * c.patch * c.patch > 4096) return PS_ERR_SHAPE;
+    if (!(c.ln_eps > 0.f) || !(c.rope_theta > 1.f)) return PS_ERR_SHAPE;
+    if ((long)c.in_channels * c.frames * c.height * c.width % 4 != 0) return PS_ERR_SHAPE;
+    if (n_weights != dit_num_weights(c.layers)) return PS_ERR_SHAPE;
+    for (int i = 0; i < n_weights; ++i) {
+        if (!weights[i]) return PS_ERR_NULL;
+        if (!aligned(weights[i], 16)) return PS_ERR_SHAPE;
+    }
+    long nv = (long)c.frames * (c.height / c.patch) * (c.width / c.patch);
+    if (nv + c.text_tokens > (1L << 24)) return PS_ERR_SHAPE;
+    dit* d = new (std::nothrow) dit();
+    if (!d) return PS_ERR_HIP;
+    d->cfg = c;
+    d->Hp = c.height / c.patch;
+    d->Wp = c.width / c.patch;
+    d->Nv = (int)nv;
+    d->N = d->Nv + c.text_tokens;
+    d->P = c.in_channels * c.patch * c.patch;
+    d->esize = c.dtype == PS_BF16 ? 2 : 4;
+    int i = 0;
+    d->W_pe = weights[i++]; d->b_pe = (const float*)weights[i++];
+    d->W_t1 = weights[i++]; d->b_t1 = (const float*)weights[i++];
+    d->W_t2 = weights[i++]; d->b_t2 = (const float*)weights[i++];
+    d->layers.resize(c.layers);
+    for (int l = 0; l < c.layers; ++l) {
+        LayerW& lw = d->layers[l];
+        lw.W_mod = weights[i++]; lw.b_mod = (const float*)weights[i++];
+        lw.W_qkv = weights[i++]; lw.b_qkv = (const float*)weights[i++];
+        lw.W_o = weights[i++];   lw.b_o = (const float*)weights[i++];
+        lw.W_1 = weights[i++];   lw.b_1 = (const float*)weights[i++];
+        lw.W_2 = weights[i++];   lw.b_2 = (const float*)weights[i++];
+    }
+    d->W_fm = weights[i++]; d->b_fm = (const float*)weights[i++];
+    d->W_out = weights[i++]; d->b_out = (const float*)weights[i++];
+    *out = d;
+    return PS_OK;
+}
+
+int dit_destroy(dit* d) {
+    if (!d) return PS_ERR_NULL;
+    for (hipEvent_t e : d->ev) hipEventDestroy(e);
+    delete d;
+    return PS_OK;
+}
+
+size_t dit_workspace_bytes(const dit* d, int batch) {
+    if (!d || batch < 1 || batch > MAX_BATCH) return 0;
+    return ws_layout(d, batch).total;
+}
+
+int dit_forward(dit* d, const float* x, const void* ctx, const int32_t* t_host, float* eps_out,
+                int batch, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    int rc = validate_forward(d, x, ctx, t_host, eps_out, batch, workspace, workspace_bytes);
+    if (rc != PS_OK) return rc;
+    return forward_impl(d, x, ctx, t_host, eps_out, batch, workspace, (hipStream_t)hip_stream);
+}
+
+int dit_profile_enable(dit* d, int on) {
+    if (!d) return PS_ERR_NULL;
+    d->profiling = on != 0;
+    if (on) {
+        d->ev_used = 0;
+        for (int k = 0; k < N_CLASSES; ++k) { d->prof_ms[k] = 0; d->prof_n[k] = 0; }
+    }
+    return PS_OK;
+}
+
+int dit_profile_read(dit* d, double* ms_out, int64_t* launches_out) {
+    if (!d || !ms_out || !launches_out) return PS_ERR_NULL;
+    for (size_t i = 0; i + 1 < d->ev_used; i += 2) {
+        if (hipEventSynchronize(d->ev[i + 1]) != hipSuccess) return PS_ERR_HIP;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, d->ev[i], d->ev[i + 1]) != hipSuccess) return PS_ERR_HIP;
+        int cls = d->ev_class[i / 2];
+        d->prof_ms[cls] += ms;
+        d->prof_n[cls] += 1;
+    }
+    d->ev_used = 0;
+    for (int k = 0; k < N_CLASSES; ++k) { ms_out[k] = d->prof_ms[k]; launches_out[k] = d->prof_n[k]; }
+    return PS_OK;
+}
+
+size_t attn3d_workspace_bytes(int batch, int seq, int heads, int head_dim, int dtype) {
+    if (batch < 1 || seq < 1 || heads < 1 || head_dim < 1) return 0;
+    return align256(attention_workspace_bytes(dtype, batch, seq, heads, head_dim));
+}
+
+int attn3d(const void* q, const void* k, const void* v, void* o, int batch, int seq, int heads,
+           int head_dim, float scale, int dtype, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!q || !k || !v || !o) return PS_ERR_NULL;
+    if (dtype != PS_F32 && dtype != PS_BF16) return PS_ERR_DTYPE;
+    if (batch < 1 || seq < 1 || heads < 1) return PS_ERR_SHAPE;
+    if (head_dim != 16 && head_dim != 32 && head_dim != 64) return PS_ERR_SHAPE;
+    if (batch > 65535 || heads > 65535 || seq > (1 << 24)) return PS_ERR_SHAPE;
+    if (!(scale > 0.f) || !std::isfinite(scale)) return PS_ERR_SHAPE;
+    if (o == q || o == k || o == v) return PS_ERR_SHAPE;
+    if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16)) return PS_ERR_SHAPE;
+    size_t need = attn3d_workspace_bytes(batch, seq, heads, head_dim, dtype);
+    if (need > 0 && (!workspace || !aligned(workspace, 256) || workspace_bytes < need)) return PS_ERR_WORKSPACE;
+    AttnStrides s;
+    s.q_tok = s.k_tok = s.v_tok = s.o_tok = (long)heads * head_dim;
+    s.q_head = s.k_head = s.v_head = s.o_head = head_dim;
+    s.q_batch = s.k_batch = s.v_batch = s.o_batch = (long)seq * heads * head_dim;
+    hipError_t e = launch_attention(dtype, q, k, v, o, batch, seq, heads, head_dim, scale, s,
+                                    need ? workspace : nullptr, (hipStream_t)hip_stream);
+    return e == hipSuccess ? PS_OK : PS_ERR_HIP;
+}
+
+int dit_linear(const void* a, const void* w, const float* bias, void* out, int m, int n_out, int k, int act,
+               int dtype, void* hip_stream) {
+    if (!a || !w || !bias || !out) return PS_ERR_NULL;
+    if (dtype != PS_F32 && dtype != PS_BF16) return PS_ERR_DTYPE;
+    if (m < 1 || n_out < 2 || k < 8 || (n_out & 1) || (k % 8) || (act != 0 && act != 1)) return PS_ERR_SHAPE;
+    if (!aligned(a, 16) || !aligned(w, 16) || !aligned(out, 16) || out == a || out == w) return PS_ERR_SHAPE;
+    Epilogue ep{};
+    ep.kind = act ? EPI_BIAS_GELU : EPI_BIAS;
+    ep.bias = bias;
+    hipError_t e = launch_gemm(dtype, a, w, out, m, n_out, k, ep, (hipStream_t)hip_stream);
+    return e == hipSuccess ? PS_OK : PS_ERR_HIP;
+}
+
+size_t sampler_step_workspace_bytes(size_t n) { return align256(reduce_workspace_bytes(n)); }
+size_t rel_mae_workspace_bytes(size_t n) { return align256(reduce_workspace_bytes(n)); }
+
+int sampler_step(const float* x, const float* eps, const float* eps_prev, float* x_out, float a, float b,
+                 size_t n, float* sums4, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!x || !eps || !x_out) return PS_ERR_NULL;
+    if (!aligned(x, 16) || !aligned(eps, 16) || !aligned(x_out, 16) || (eps_prev && !aligned(eps_prev, 16)))
+        return PS_ERR_SHAPE;
+    if (eps == x_out || (eps_prev && eps_prev == x_out)) return PS_ERR_SHAPE;
+    if (sums4 && (!workspace || !aligned(workspace, 256) || workspace_bytes < sampler_step_workspace_bytes(n)))
+        return PS_ERR_WORKSPACE;
+    hipError_t e = launch_sampler_step(x, eps, eps_prev, x_out, a, b, n, sums4, workspace, (hipStream_t)hip_stream);
+    return e == hipSuccess ? PS_OK : PS_ERR_HIP;
+}
+
+int rel_mae(const float* a, const float* b, size_t n, float* out3, void* workspace, size_t workspace_bytes,
+            void* hip_stream) {
+    if (!a || !b || !out3) return PS_ERR_NULL;
+    if (!aligned(a, 16) || !aligned(b, 16)) return PS_ERR_SHAPE;
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < rel_mae_workspace_bytes(n)) return PS_ERR_WORKSPACE;
+    hipError_t e = launch_rel_mae(a, b, n, out3, workspace, (hipStream_t)hip_stream);
+    return e == hipSuccess ? PS_OK : PS_ERR_HIP;
+}
+
+int ddim_coefficients(int train_steps, double beta_start, double beta_end, int steps, int32_t* timesteps_out,
+                      float* a_out, float* b_out) {
+    if (!timesteps_out || !a_out || !b_out) return PS_ERR_NULL;
+    if (train_steps < 2 || steps < 1 || steps > train_steps) return PS_ERR_SCHEDULE;
+    if (!(beta_start > 0.0) || !(beta_end >= beta_start) || !(beta_end < 1.0)) return PS_ERR_SCHEDULE;
+    std::vector<double> abar(train_steps);
+    double prod = 1.0;
+    for (int k = 0; k < train_steps; ++k) {
+        double beta = beta_start + (double)k * (beta_end - beta_start) / (double)(train_steps - 1);
+        prod *= 1.0 - beta;
+        abar[k] = prod;
+    }
+    int stride = train_steps / steps;
+    for (int i = 0; i < steps; ++i) {
+        int tau = (steps - 1 - i) * stride;
+        double ab_t = abar[tau];
+        double ab_p = i + 1 < steps ? abar[(steps - 2 - i) * stride] : 1.0;
+        double a = std::sqrt(ab_p / ab_t);
+        double b = std::sqrt(1.0 - ab_p) - a * std::sqrt(1.0 - ab_t);
+        timesteps_out[i] = tau;
+        a_out[i] = (float)a;
+        b_out[i] = (float)b;
+    }
+    return PS_OK;
+}
+
+}  // extern "C"
+
+// ----------------------------------------------------------------- reuse-then-predict run
+namespace {
+
+struct RunPlan {
+    std::vector<int> cycles;   // cycle lengths actually entered after warm-up
+    int pmax = 1;
+    int warm = 0;
+};
+
+int plan_schedule(const sampler_schedule* s, RunPlan* plan) {
+    if (!s) return PS_ERR_NULL;
+    if (s->steps < 1 || !s->timesteps || !s->coef_a || !s->coef_b) return s->steps < 1 ? PS_ERR_SCHEDULE : PS_ERR_NULL;
+    if (s->warmup < 0 || (s->mode != 0 && s->mode != 1) || (s->batched != 0 && s->batched != 1)) return PS_ERR_SCHEDULE;
+    if (s->batched && s->mode == 1) return PS_ERR_SCHEDULE;
+    for (int i = 0; i < s->steps; ++i) {
+        if (s->timesteps[i] < 0 || s->timesteps[i] >= 100000) return PS_ERR_SCHEDULE;
+        if (i > 0 && s->timesteps[i] >= s->timesteps[i - 1]) return PS_ERR_SCHEDULE;
+    }
+    plan->warm = s->warmup < s->steps ? s->warmup : s->steps;
+    int left = s->steps - plan->warm;
+    plan->pmax = 1;
+    if (left > 0) {
+        if (s->n_cycles < 1 || !s->cycle_len) return PS_ERR_SCHEDULE;
+        for (int c = 0; c < s->n_cycles && left > 0; ++c) {
+            int p = s->cycle_len[c];
+            if (p < 1 || p > MAX_BATCH) return PS_ERR_SCHEDULE;
+            plan->cycles.push_back(p);
+            if (p > plan->pmax) plan->pmax = p;
+            left -= p;
+        }
+        if (left > 0) return PS_ERR_SCHEDULE;                 // cycles do not cover the run
+        if (plan->pmax > 1 && s->warmup < 1) return PS_ERR_SCHEDULE;   // eps_cache undefined
+    }
+    return PS_OK;
+}
+
+struct RunWs { size_t xbuf, cache, pp, xb, eb, red, dit, total; };
+
+RunWs run_layout(const dit* d, const sampler_schedule* s, const RunPlan& plan) {
+    size_t n = (size_t)d->cfg.in_channels * d->cfg.frames * d->cfg.height * d->cfg.width;
+    size_t nb = align256(n * 4);
+    RunWs w;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return o; };
+    int p = plan.pmax;
+    w.xbuf = take(nb * p);        // per-rank samples (rank 0 = true trajectory)
+    w.cache = take(nb * p);       // per-rank eps_cache
+    w.pp = take(nb * 2);          // ping-pong eps buffers / eps_prev copy
+    w.xb = take(s->batched ? nb * p : 0);
+    w.eb = take(s->batched ? nb * p : 0);
+    w.red = take(reduce_workspace_bytes(n));
+    w.dit = take(dit_workspace_bytes(d, s->batched ? p : 1));
+    w.total = off;
+    return w;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t sampler_workspace_bytes(const dit* d, const sampler_schedule* s) {
+    RunPlan plan;
+    if (!d || plan_schedule(s, &plan) != PS_OK) return 0;
+    return run_layout(d, s, plan).total;
+}
+
+int sampler_run(dit* d, const sampler_schedule* s, const float* x_T, const void* ctx, float* x0_out,
+                float* step_sums, int* calls_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!d || !s || !x_T || !x0_out) return PS_ERR_NULL;
+    if (d->cfg.text_tokens > 0 && !ctx) return PS_ERR_NULL;
+    RunPlan plan;
+    int rc = plan_schedule(s, &plan);
+    if (rc != PS_OK) return rc;
+    if (!aligned(x_T, 16) || !aligned(x0_out, 16) || (step_sums && !aligned(step_sums, 16))) return PS_ERR_SHAPE;
+    RunWs w = run_layout(d, s, plan);
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < w.total) return PS_ERR_WORKSPACE;
+
+    hipStream_t st = (hipStream_t)hip_stream;
+    const size_t n = (size_t)d->cfg.in_channels * d->cfg.frames * d->cfg.height * d->cfg.width;
+    const size_t nb = align256(n * 4);
+    char* base = (char*)workspace;
+    const int P = plan.pmax;
+    auto xbuf = [&](int r) { return (float*)(base + w.xbuf + nb * r); };
+    auto cache = [&](int r) { return (float*)(base + w.cache + nb * r); };
+    auto pp = [&](int i) { return (float*)(base + w.pp + nb * i); };
+    auto xb = [&](int r) { return (float*)(base + w.xb + n * 4 * r); };     // contiguous [p, n]
+    auto eb = [&](int r) { return (float*)(base + w.eb + n * 4 * r); };
+    void* red = base + w.red;
+    void* dws = base + w.dit;
+    const size_t dws_bytes = w.total - w.dit;
+    int calls = 0;
+
+    auto step = [&](const float* x, const float* e, const float* eprev, float* xo, int i, bool record) -> int {
+        float* sums = (record && step_sums) ? step_sums + 4 * (size_t)i : nullptr;
+        hipError_t err = launch_sampler_step(x, e, eprev, xo, s->coef_a[i], s->coef_b[i], n, sums, red, st);
+        return err == hipSuccess ? PS_OK : PS_ERR_HIP;
+    };
+    auto copy = [&](float* dst, const float* src) -> int {
+        if (dst == src) return PS_OK;
+        return hipMemcpyAsync(dst, src, n * 4, hipMemcpyDeviceToDevice, st) == hipSuccess ? PS_OK : PS_ERR_HIP;
+    };
+#define PS_RC(expr) do { int rc__ = (expr); if (rc__ != PS_OK) return rc__; } while (0)
+
+    if (!s->batched) {
+        // rank r's current sample lives in xbuf[src[r]] (after a broadcast every rank reads
+        // rank 0's buffer until its next own update)
+        std::vector<int> src(P, 0);
+        PS_RC(copy(xbuf(0), x_T));
+        const float* eprev = nullptr;
+        int toggle = 0;
+        int cyc = 0, rnd = 0;
+        for (int i = 0; i < s->steps; ++i) {
+            int32_t t = s->timesteps[i];
+            if (i < plan.warm) {
+                float* e = pp(toggle); toggle ^= 1;
+                PS_RC(forward_impl(d, xbuf(0), ctx, &t, e, 1, dws, st)); ++calls;
+                PS_RC(step(xbuf(0), e, eprev, xbuf(0), i, true));
+                eprev = e;
+                if (i == plan.warm - 1)
+                    for (int r = 1; r < P; ++r) PS_RC(copy(cache(r), e));   // eps_cache of every rank
+                continue;
+            }
+            const int p = plan.cycles[cyc];
+            if (s->mode == 1) {                      // direct reuse: predict only in round 0
+                const float* e = eprev;
+                if (rnd == 0) {
+                    float* en = pp(toggle); toggle ^= 1;
+                    PS_RC(forward_impl(d, xbuf(0), ctx, &t, en, 1, dws, st)); ++calls;
+                    e = en;
+                }
+                PS_RC(step(xbuf(0), e, eprev, xbuf(0), i, true));
+                eprev = e;
+            } else {
+                const int master = rnd;
+                float* e;
+                if (master == 0) { e = pp(toggle); toggle ^= 1; } else { e = cache(master); }
+                PS_RC(forward_impl(d, xbuf(src[master]), ctx, &t, e, 1, dws, st)); ++calls;
+                // ranks that still have to predict in this cycle advance with their own cache;
+                // they may read rank 0's buffer, so they go before rank 0's in-place update
+                for (int r = master + 1; r < p; ++r) {
+                    PS_RC(step(xbuf(src[r]), cache(r), nullptr, xbuf(r), i, false));
+                    src[r] = r;
+                }
+                PS_RC(step(xbuf(0), e, eprev, xbuf(0), i, true));   // rank 0 applies the master's eps
+                eprev = e;
+            }
+            if (rnd == p - 1) {                      // broadcast rank 0's sample
+                for (int r = 1; r < P; ++r) src[r] = 0;
+                ++cyc; rnd = 0;
+            } else {
+                ++rnd;
+            }
+        }
+        PS_RC(copy(x0_out, xbuf(0)));
+    } else {
+        // batched: rank 0's sample lives in xb(0)'s neighbour xbuf(0); inputs of a cycle in xb(r)
+        PS_RC(copy(xbuf(0), x_T));
+        float* eprev_buf = pp(0);
+        bool have_prev = false;
+        int i = 0;
+        int32_t tb[MAX_BATCH];
+        for (; i < plan.warm; ++i) {
+            tb[0] = s->timesteps[i];
+            PS_RC(forward_impl(d, xbuf(0), ctx, tb, eb(0), 1, dws, st)); ++calls;
+            PS_RC(step(xbuf(0), eb(0), have_prev ? eprev_buf : nullptr, xbuf(0), i, true));
+            PS_RC(copy(eprev_buf, eb(0)));
+            have_prev = true;
+            if (i == plan.warm - 1)
+                for (int r = 0; r < P; ++r) PS_RC(copy(cache(r), eb(0)));
+        }
+        for (size_t c = 0; c < plan.cycles.size() && i < s->steps; ++c) {
+            int p = plan.cycles[c];
+            int nn = p < s->steps - i ? p : s->steps - i;
+            // rank r's input: the current sample advanced r times with that rank's cached eps
+            PS_RC(copy(xb(0), xbuf(0)));
+            for (int r = 1; r < nn; ++r) {
+                PS_RC(step(xbuf(0), cache(r), nullptr, xb(r), i, false));
+                for (int jj = 1; jj < r; ++jj) PS_RC(step(xb(r), cache(r), nullptr, xb(r), i + jj, false));
+            }
+            for (int r = 0; r < nn; ++r) tb[r] = s->timesteps[i + r];
+            // the text context is shared by all ranks of the cycle
+            PS_RC(forward_impl(d, xb(0), ctx, tb, eb(0), nn, dws, st, true)); ++calls;
+            for (int r = 0; r < nn; ++r) {
+                const float* prev = r == 0 ? (have_prev ? eprev_buf : nullptr) : eb(r - 1);
+                PS_RC(step(xbuf(0), eb(r), prev, xbuf(0), i + r, true));
+            }
+            for (int r = 0; r < nn; ++r) PS_RC(copy(cache(r), eb(r)));
+            PS_RC(copy(eprev_buf, eb(nn - 1)));
+            have_prev = true;
+            i += nn;
+        }
+        PS_RC(copy(x0_out, xbuf(0)));
+    }
+#undef PS_RC
+    (void)dws_bytes;
+    if (calls_out) *calls_out = calls;
+    return PS_OK;
+}
+
+}  // extern "C"

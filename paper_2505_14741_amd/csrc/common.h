@@ -1,0 +1,98 @@
+// Internal declarations shared by the library's translation units (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_bf16.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/parastep.h"
+
+namespace ps {
+
+typedef __hip_bfloat16 bf16_t;
+
+// ---- element conversion (device) ---------------------------------------------------
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16_t v) { return __bfloat162float(v); }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return __float2bfloat16(v); }
+
+__device__ __forceinline__ float gelu_tanh_f(float x) {
+    const float k0 = 0.7978845608028654f, k1 = 0.044715f;
+    float u = k0 * (x + k1 * x * x * x);
+    return 0.5f * x * (1.0f + tanhf(u));
+}
+__device__ __forceinline__ float silu_f(float x) { return x / (1.0f + expf(-x)); }
+
+// ---- modulation addressing -----------------------------------------------------------
+// mod is fp32 [B][layers][12][D]; chunks 0..5 are the video set (shift_a, scale_a,
+// gate_a, shift_m, scale_m, gate_m), 6..11 the same for text tokens.
+struct TokenGeom {
+    int tokens;        // N = text + video tokens per sample
+    int text_tokens;   // L_txt
+};
+
+// ---- GEMM epilogues ------------------------------------------------------------------
+enum EpiKind { EPI_BIAS = 0, EPI_BIAS_GELU = 1, EPI_GATE_RESIDUAL = 2, EPI_QKV_ROPE = 3 };
+
+struct Epilogue {
+    int kind;
+    const float* bias;        // [Nn]
+    // EPI_GATE_RESIDUAL: X[m, col] += gate[b, stream, col] * (acc + bias)
+    float* resid;             // fp32 [M, Nn]
+    const float* mod_layer;   // fp32, points at mod[0][layer][0][0]
+    long mod_batch_stride;    // layers*12*D
+    int gate_chunk;           // 2 (attention) or 5 (mlp); text uses +6
+    int D;                    // hidden
+    TokenGeom geom;
+    // EPI_QKV_ROPE: rotate pairs of q and k columns of video tokens
+    const float* rope_cos;    // fp32 [N_v, d/2]
+    const float* rope_sin;
+    int head_dim;
+};
+
+// ---- launchers (each validates nothing; callers have checked shapes) -----------------
+// C[M, Nn] = A[M, K] * W[Nn, K]^T with epilogue.  A, W, C in `dtype` (C ignored for
+// EPI_GATE_RESIDUAL).  lda/ldc in elements.
+hipError_t launch_gemm(int dtype, const void* A, const void* W, void* C, int M, int Nn, int K,
+                       const Epilogue& epi, hipStream_t st);
+
+// Full attention with explicit strides (in elements) for token, head and batch.
+struct AttnStrides { long q_tok, q_head, q_batch, k_tok, k_head, k_batch, v_tok, v_head, v_batch,
+                     o_tok, o_head, o_batch; };
+// `ws` is scratch of attention_workspace_bytes() bytes (may be NULL when that is 0).
+size_t attention_workspace_bytes(int dtype, int batch, int seq, int heads, int head_dim);
+hipError_t launch_attention(int dtype, const void* q, const void* k, const void* v, void* o,
+                            int batch, int seq, int heads, int head_dim, float scale,
+                            const AttnStrides& s, void* ws, hipStream_t st);
+void set_kernel_path(int p);
+int get_kernel_path();
+
+hipError_t launch_sinusoid(const int32_t* t_host, float* out, int batch, int D, hipStream_t st);
+// out[b, r] = act(W[r,:] . in[b,:] + bias[r]);  act: 0 none, 1 SiLU.  W in dtype, in/out fp32.
+hipError_t launch_gemv(int dtype, const void* W, const float* bias, const float* in, float* out,
+                       int rows, int cols, int batch, long in_bstride, long out_bstride, int act,
+                       hipStream_t st);
+hipError_t launch_rope_table(float* cosb, float* sinb, int F, int Hp, int Wp, int head_dim,
+                             float theta, hipStream_t st);
+hipError_t launch_patch_embed(int dtype, const float* x, const void* ctx, const void* W_pe,
+                              const float* b_pe, float* X, int batch, int C, int F, int H, int Wd,
+                              int patch, int text_tokens, int D, long ctx_batch_stride,
+                              hipStream_t st);
+// out[m, :] = LN(X[m, :]) * (1 + scale) + shift with per-token stream selection.
+hipError_t launch_ln_modulate(int dtype, const float* X, void* out, int M, int D, float eps,
+                              const float* mod_layer, long mod_batch_stride, int shift_chunk,
+                              int scale_chunk, TokenGeom geom, hipStream_t st);
+hipError_t launch_final_proj(int dtype, const float* X, const float* modf, const void* W_out,
+                             const float* b_out, float* eps_out, int batch, int C, int F, int H,
+                             int Wd, int patch, int text_tokens, int D, float eps, hipStream_t st);
+
+size_t reduce_workspace_bytes(size_t n);
+hipError_t launch_sampler_step(const float* x, const float* e, const float* e_prev, float* x_out,
+                               float a, float b, size_t n, float* sums4, void* ws, hipStream_t st);
+hipError_t launch_rel_mae(const float* a, const float* b, size_t n, float* out3, void* ws,
+                          hipStream_t st);
+
+}  // namespace ps

@@ -1,0 +1,493 @@
+// HBM-bound kernels of the denoising step: time conditioning, patch embedding,
+// LayerNorm + adaLN modulation, final projection, the fused DDIM update with the
+// relative-MAE sums of paper Eq. (1), and the stand-alone relative MAE.
+#include "common.h"
+
+namespace ps {
+
+static constexpr int WAVE = 64;
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+    return v;
+}
+__device__ __forceinline__ double wave_sum_d(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+    return v;
+}
+
+// ------------------------------------------------------------------ time conditioning
+struct TList { int t[16]; };
+
+// s(t) = [cos(t w_j) | sin(t w_j)], w_j = 10000^(-j/(D/2)); double precision because
+// t*w reaches ~1e3 rad and the result feeds an fp32 MLP compared at 1e-4.
+__global__ void sinusoid_kernel(TList tl, float* __restrict__ out, int D) {
+    int b = blockIdx.y;
+    int half = D / 2;
+    int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= half) return;
+    double w = exp(-(double)j / (double)half * 9.210340371976184);   // ln(10000)
+    double ang = (double)tl.t[b] * w;
+    out[(long)b * D + j] = (float)cos(ang);
+    out[(long)b * D + half + j] = (float)sin(ang);
+}
+
+hipError_t launch_sinusoid(const int32_t* t_host, float* out, int batch, int D, hipStream_t st) {
+    TList tl;
+    for (int i = 0; i < 16; ++i) tl.t[i] = i < batch ? t_host[i] : 0;
+    dim3 grid((D / 2 + 127) / 128, batch);
+    sinusoid_kernel<<<grid, 128, 0, st>>>(tl, out, D);
+    return hipGetLastError();
+}
+
+// One wave per output row; weights stream once from HBM, inputs stay in cache.
+template <typename T, int MAXB>
+__global__ void gemv_kernel(const T* __restrict__ W, const float* __restrict__ bias,
+                            const float* __restrict__ in, float* __restrict__ out, int rows,
+                            int cols, int batch, long in_bs, long out_bs, int act) {
+    int wave = (blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
+    int lane = threadIdx.x % WAVE;
+    if (wave >= rows) return;
+    const T* w = W + (long)wave * cols;
+    float acc[MAXB];
+#pragma unroll
+    for (int b = 0; b < MAXB; ++b) acc[b] = 0.f;
+    for (int c = lane; c < cols; c += WAVE) {
+        float wv = to_f32(w[c]);
+#pragma unroll
+        for (int b = 0; b < MAXB; ++b)
+            if (b < batch) acc[b] += wv * in[b * in_bs + c];
+    }
+#pragma unroll
+    for (int b = 0; b < MAXB; ++b) {
+        if (b < batch) {
+            float v = wave_sum(acc[b]);
+            if (lane == 0) {
+                v += bias[wave];
+                if (act == 1) v = silu_f(v);
+                out[b * out_bs + wave] = v;
+            }
+        }
+    }
+}
+
+hipError_t launch_gemv(int dtype, const void* W, const float* bias, const float* in, float* out,
+                       int rows, int cols, int batch, long in_bs, long out_bs, int act,
+                       hipStream_t st) {
+    int threads = 256;
+    int blocks = (rows + (threads / WAVE) - 1) / (threads / WAVE);
+    if (dtype == PS_BF16)
+        gemv_kernel<bf16_t, 16><<<blocks, threads, 0, st>>>((const bf16_t*)W, bias, in, out, rows,
+                                                             cols, batch, in_bs, out_bs, act);
+    else
+        gemv_kernel<float, 16><<<blocks, threads, 0, st>>>((const float*)W, bias, in, out, rows,
+                                                            cols, batch, in_bs, out_bs, act);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------- 3D RoPE table
+// cos/sin of pos_A * theta^(-2m/d_A) for every video token and pair; axis widths
+// d/4, 3d/8, 3d/8 over (frame, row, col).  Double precision angles.
+__global__ void rope_table_kernel(float* __restrict__ cosb, float* __restrict__ sinb, int F, int Hp,
+                                  int Wp, int head_dim, float theta) {
+    int half = head_dim / 2;
+    long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    long total = (long)F * Hp * Wp * half;
+    if (idx >= total) return;
+    int pair = idx % half;
+    long tok = idx / half;
+    int j = tok % Wp;
+    int i = (tok / Wp) % Hp;
+    int f = tok / ((long)Wp * Hp);
+    int p0 = head_dim / 8;            // pairs on the frame axis
+    int p1 = 3 * head_dim / 16;       // pairs on each spatial axis
+    int pos, m, dA;
+    if (pair < p0) { pos = f; m = pair; dA = 2 * p0; }
+    else if (pair < p0 + p1) { pos = i; m = pair - p0; dA = 2 * p1; }
+    else { pos = j; m = pair - p0 - p1; dA = 2 * p1; }
+    double ang = (double)pos * exp(-2.0 * (double)m / (double)dA * log((double)theta));
+    cosb[idx] = (float)cos(ang);
+    sinb[idx] = (float)sin(ang);
+}
+
+hipError_t launch_rope_table(float* cosb, float* sinb, int F, int Hp, int Wp, int head_dim,
+                             float theta, hipStream_t st) {
+    long total = (long)F * Hp * Wp * (head_dim / 2);
+    if (total == 0) return hipSuccess;
+    rope_table_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(cosb, sinb, F, Hp, Wp, head_dim,
+                                                                      theta);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------ patch embedding
+// X[b, L_txt + (f,i,j), :] = W_pe . patch(c,dy,dx) + b_pe ; X[b, n < L_txt, :] = ctx[b, n, :].
+// One workgroup per TOK tokens; patch vectors staged in LDS, threads stride over D.
+template <typename T, int TOK>
+__global__ void patch_embed_kernel(const float* __restrict__ x, const T* __restrict__ ctx,
+                                   const T* __restrict__ W_pe, const float* __restrict__ b_pe,
+                                   float* __restrict__ X, int C, int F, int H, int Wd, int patch,
+                                   int text_tokens, int D, long ctx_bs) {
+    extern __shared__ float pv[];        // [TOK][P]
+    int Hp = H / patch, Wp = Wd / patch;
+    int Nv = F * Hp * Wp;
+    int N = text_tokens + Nv;
+    int P = C * patch * patch;
+    int b = blockIdx.y;
+    int tok0 = blockIdx.x * TOK;         // token index within the sample (text first)
+    for (int e = threadIdx.x; e < TOK * P; e += blockDim.x) {
+        int tl = e / P, pi = e % P;
+        int n = tok0 + tl;
+        float val = 0.f;
+        if (n < N && n >= text_tokens) {
+            int nv = n - text_tokens;
+            int j = nv % Wp, i = (nv / Wp) % Hp, f = nv / (Wp * Hp);
+            int dx = pi % patch, dy = (pi / patch) % patch, c = pi / (patch * patch);
+            val = x[((((long)b * C + c) * F + f) * H + (i * patch + dy)) * Wd + (j * patch + dx)];
+        }
+        pv[e] = val;
+    }
+    __syncthreads();
+    for (int col = threadIdx.x; col < D; col += blockDim.x) {
+        float acc[TOK];
+#pragma unroll
+        for (int tl = 0; tl < TOK; ++tl) acc[tl] = b_pe[col];
+        const T* w = W_pe + (long)col * P;
+        for (int pi = 0; pi < P; ++pi) {
+            float wv = to_f32(w[pi]);
+#pragma unroll
+            for (int tl = 0; tl < TOK; ++tl) acc[tl] += wv * pv[tl * P + pi];
+        }
+#pragma unroll
+        for (int tl = 0; tl < TOK; ++tl) {
+            int n = tok0 + tl;
+            if (n >= N) continue;
+            float v = n < text_tokens ? to_f32(ctx[b * ctx_bs + (long)n * D + col]) : acc[tl];
+            X[((long)b * N + n) * D + col] = v;
+        }
+    }
+}
+
+hipError_t launch_patch_embed(int dtype, const float* x, const void* ctx, const void* W_pe,
+                              const float* b_pe, float* X, int batch, int C, int F, int H, int Wd,
+                              int patch, int text_tokens, int D, long ctx_bs, hipStream_t st) {
+    constexpr int TOK = 8;
+    int N = text_tokens + F * (H / patch) * (Wd / patch);
+    int P = C * patch * patch;
+    dim3 grid((N + TOK - 1) / TOK, batch);
+    size_t sh = (size_t)TOK * P * sizeof(float);
+    if (dtype == PS_BF16)
+        patch_embed_kernel<bf16_t, TOK><<<grid, 256, sh, st>>>(x, (const bf16_t*)ctx, (const bf16_t*)W_pe,
+                                                               b_pe, X, C, F, H, Wd, patch, text_tokens, D, ctx_bs);
+    else
+        patch_embed_kernel<float, TOK><<<grid, 256, sh, st>>>(x, (const float*)ctx, (const float*)W_pe, b_pe,
+                                                              X, C, F, H, Wd, patch, text_tokens, D, ctx_bs);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------- LayerNorm + modulate
+// One wave per token row.  fp32 statistics (mean, then centred second moment), biased
+// variance, no affine; out = y*(1+scale)+shift with the text or video chunk.
+// The row is held in registers between the passes: D <= 64*4*MAXV.
+template <typename T, int MAXV>
+__global__ void ln_modulate_kernel(const float* __restrict__ X, T* __restrict__ out, int M, int D,
+                                   float eps, const float* __restrict__ mod_layer, long mod_bs,
+                                   int shift_chunk, int scale_chunk, TokenGeom g) {
+    int row = (blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
+    int lane = threadIdx.x % WAVE;
+    if (row >= M) return;
+    const float4* xr = reinterpret_cast<const float4*>(X + (long)row * D);
+    int nvec = D / 4;
+    float4 v[MAXV];
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < MAXV; ++i) {
+        int c = lane + i * WAVE;
+        if (c < nvec) {
+            v[i] = xr[c];
+            s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+        }
+    }
+    float mean = wave_sum(s) / (float)D;
+    float q = 0.f;
+#pragma unroll
+    for (int i = 0; i < MAXV; ++i) {
+        int c = lane + i * WAVE;
+        if (c < nvec) {
+            float a = v[i].x - mean, b = v[i].y - mean, cc = v[i].z - mean, d = v[i].w - mean;
+            q += (a * a + b * b) + (cc * cc + d * d);
+        }
+    }
+    float rstd = 1.0f / sqrtf(wave_sum(q) / (float)D + eps);
+    int b = row / g.tokens, n = row % g.tokens;
+    int off = n < g.text_tokens ? 6 : 0;
+    const float4* sh = reinterpret_cast<const float4*>(mod_layer + b * mod_bs + (long)(shift_chunk + off) * D);
+    const float4* sc = reinterpret_cast<const float4*>(mod_layer + b * mod_bs + (long)(scale_chunk + off) * D);
+    T* orow = out + (long)row * D;
+#pragma unroll
+    for (int i = 0; i < MAXV; ++i) {
+        int c = lane + i * WAVE;
+        if (c < nvec) {
+            float4 h = sh[c], k = sc[c];
+            float y0 = (v[i].x - mean) * rstd * (1.f + k.x) + h.x;
+            float y1 = (v[i].y - mean) * rstd * (1.f + k.y) + h.y;
+            float y2 = (v[i].z - mean) * rstd * (1.f + k.z) + h.z;
+            float y3 = (v[i].w - mean) * rstd * (1.f + k.w) + h.w;
+            if constexpr (sizeof(T) == 2) {
+                union { bf16_t h4[4]; uint2 u; } pk;
+                pk.h4[0] = __float2bfloat16(y0); pk.h4[1] = __float2bfloat16(y1);
+                pk.h4[2] = __float2bfloat16(y2); pk.h4[3] = __float2bfloat16(y3);
+                *reinterpret_cast<uint2*>(orow + 4 * c) = pk.u;
+            } else {
+                *reinterpret_cast<float4*>(orow + 4 * c) = make_float4(y0, y1, y2, y3);
+            }
+        }
+    }
+}
+
+hipError_t launch_ln_modulate(int dtype, const float* X, void* out, int M, int D, float eps,
+                              const float* mod_layer, long mod_bs, int shift_chunk, int scale_chunk,
+                              TokenGeom geom, hipStream_t st) {
+    int threads = 256;
+    int blocks = (M + 3) / 4;
+    if (D % 4 != 0 || D > 64 * 4 * 8) return hipErrorInvalidValue;
+    if (dtype == PS_BF16)
+        ln_modulate_kernel<bf16_t, 8><<<blocks, threads, 0, st>>>(X, (bf16_t*)out, M, D, eps, mod_layer, mod_bs,
+                                                                 shift_chunk, scale_chunk, geom);
+    else
+        ln_modulate_kernel<float, 8><<<blocks, threads, 0, st>>>(X, (float*)out, M, D, eps, mod_layer, mod_bs,
+                                                                shift_chunk, scale_chunk, geom);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------ final projection
+// Video tokens only: y = LN(X_n)(1+scale)+shift with modf = [shift | scale] (fp32 [B][2D]),
+// out = W_out y + b_out (C*ps*ps values in (c,dy,dx) order) scattered into eps[C,F,H,W].
+// One workgroup (256 threads) per token; y kept in LDS.
+template <typename T>
+__global__ void final_proj_kernel(const float* __restrict__ X, const float* __restrict__ modf,
+                                  const T* __restrict__ W_out, const float* __restrict__ b_out,
+                                  float* __restrict__ eps_out, int C, int F, int H, int Wd, int patch,
+                                  int text_tokens, int D, float eps) {
+    extern __shared__ float y[];     // [D] + 8 partials
+    float* red = y + D;
+    int Hp = H / patch, Wp = Wd / patch;
+    int Nv = F * Hp * Wp, N = text_tokens + Nv;
+    int b = blockIdx.y, nv = blockIdx.x;
+    const float* xr = X + ((long)b * N + text_tokens + nv) * D;
+    int lane = threadIdx.x % WAVE, wave = threadIdx.x / WAVE, nw = blockDim.x / WAVE;
+    float s = 0.f;
+    for (int c = threadIdx.x; c < D; c += blockDim.x) { float v = xr[c]; y[c] = v; s += v; }
+    s = wave_sum(s);
+    if (lane == 0) red[wave] = s;
+    __syncthreads();
+    float tot = 0.f;
+    for (int w = 0; w < nw; ++w) tot += red[w];
+    float mean = tot / (float)D;
+    __syncthreads();
+    float q = 0.f;
+    for (int c = threadIdx.x; c < D; c += blockDim.x) { float dlt = y[c] - mean; q += dlt * dlt; }
+    q = wave_sum(q);
+    if (lane == 0) red[wave] = q;
+    __syncthreads();
+    float qt = 0.f;
+    for (int w = 0; w < nw; ++w) qt += red[w];
+    float rstd = 1.0f / sqrtf(qt / (float)D + eps);
+    const float* shift = modf + (long)b * 2 * D;
+    const float* scale = shift + D;
+    for (int c = threadIdx.x; c < D; c += blockDim.x)
+        y[c] = (y[c] - mean) * rstd * (1.f + scale[c]) + shift[c];
+    __syncthreads();
+    int P = C * patch * patch;
+    int j = nv % Wp, i = (nv / Wp) % Hp, f = nv / (Wp * Hp);
+    for (int o = wave; o < P; o += nw) {
+        const T* w = W_out + (long)o * D;
+        float acc = 0.f;
+        for (int c = lane; c < D; c += WAVE) acc += to_f32(w[c]) * y[c];
+        acc = wave_sum(acc);
+        if (lane == 0) {
+            int dx = o % patch, dy = (o / patch) % patch, c = o / (patch * patch);
+            eps_out[((((long)b * C + c) * F + f) * H + (i * patch + dy)) * Wd + (j * patch + dx)] = acc + b_out[o];
+        }
+    }
+}
+
+hipError_t launch_final_proj(int dtype, const float* X, const float* modf, const void* W_out,
+                             const float* b_out, float* eps_out, int batch, int C, int F, int H,
+                             int Wd, int patch, int text_tokens, int D, float eps, hipStream_t st) {
+    int Nv = F * (H / patch) * (Wd / patch);
+    dim3 grid(Nv, batch);
+    size_t sh = (size_t)(D + 8) * sizeof(float);
+    if (dtype == PS_BF16)
+        final_proj_kernel<bf16_t><<<grid, 256, sh, st>>>(X, modf, (const bf16_t*)W_out, b_out, eps_out, C, F, H,
+                                                        Wd, patch, text_tokens, D, eps);
+    else
+        final_proj_kernel<float><<<grid, 256, sh, st>>>(X, modf, (const float*)W_out, b_out, eps_out, C, F, H, Wd,
+                                                       patch, text_tokens, D, eps);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------- scheduler update + relative-MAE sums
+// Two-stage deterministic reduction: stage 1 streams the tensors once (float4, grid-stride
+// with a fixed grid), each block leaves its partial sums in the workspace; stage 2 (one
+// block) adds the partials in a fixed order in double.
+static constexpr int RED_THREADS = 256;
+static constexpr int RED_MAX_BLOCKS = 2048;
+
+static int red_blocks(size_t n) {
+    size_t per_block = (size_t)RED_THREADS * 4 * 4;     // 4 float4 per thread per sweep
+    size_t b = (n + per_block - 1) / per_block;
+    if (b < 1) b = 1;
+    if (b > RED_MAX_BLOCKS) b = RED_MAX_BLOCKS;
+    return (int)b;
+}
+
+size_t reduce_workspace_bytes(size_t n) { (void)n; return (size_t)RED_MAX_BLOCKS * 4 * sizeof(double); }
+
+template <int NS>
+__device__ __forceinline__ void block_store_partials(double (&acc)[NS], double* __restrict__ part) {
+    __shared__ double sm[NS][RED_THREADS / WAVE];
+    int lane = threadIdx.x % WAVE, wave = threadIdx.x / WAVE;
+#pragma unroll
+    for (int k = 0; k < NS; ++k) {
+        double v = wave_sum_d(acc[k]);
+        if (lane == 0) sm[k][wave] = v;
+    }
+    __syncthreads();
+    if (threadIdx.x < NS) {
+        double t = 0.0;
+        for (int w = 0; w < RED_THREADS / WAVE; ++w) t += sm[threadIdx.x][w];
+        part[(long)blockIdx.x * NS + threadIdx.x] = t;
+    }
+}
+
+template <bool SUMS, bool PREV>
+__global__ void __launch_bounds__(RED_THREADS)
+sampler_step_kernel(const float* x, const float* __restrict__ e,
+                    const float* __restrict__ ep, float* xo, float a, float b,
+                    size_t n, double* __restrict__ part) {
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    size_t nvec = n / 4;
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    const float4* x4 = reinterpret_cast<const float4*>(x);
+    const float4* e4 = reinterpret_cast<const float4*>(e);
+    const float4* p4 = reinterpret_cast<const float4*>(ep);
+    float4* o4 = reinterpret_cast<float4*>(xo);
+    int cnt = 0;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += stride) {
+        float4 xv = x4[i], ev = e4[i];
+        float4 r;
+        r.x = a * xv.x + b * ev.x; r.y = a * xv.y + b * ev.y;
+        r.z = a * xv.z + b * ev.z; r.w = a * xv.w + b * ev.w;
+        o4[i] = r;
+        if constexpr (SUMS) {
+            s0 += (fabsf(r.x - xv.x) + fabsf(r.y - xv.y)) + (fabsf(r.z - xv.z) + fabsf(r.w - xv.w));
+            s1 += (fabsf(r.x) + fabsf(r.y)) + (fabsf(r.z) + fabsf(r.w));
+            s3 += (fabsf(ev.x) + fabsf(ev.y)) + (fabsf(ev.z) + fabsf(ev.w));
+            if constexpr (PREV) {
+                float4 pv = p4[i];
+                s2 += (fabsf(ev.x - pv.x) + fabsf(ev.y - pv.y)) + (fabsf(ev.z - pv.z) + fabsf(ev.w - pv.w));
+            }
+            if (++cnt == 16) {       // flush fp32 partials into double every 64 elements
+                acc[0] += s0; acc[1] += s1; acc[2] += s2; acc[3] += s3;
+                s0 = s1 = s2 = s3 = 0.f; cnt = 0;
+            }
+        }
+    }
+    // ragged tail (n % 4 elements) handled by the first threads of block 0
+    if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
+        size_t i = nvec * 4 + threadIdx.x;
+        float xv = x[i], ev = e[i];
+        float r = a * xv + b * ev;
+        xo[i] = r;
+        if constexpr (SUMS) {
+            s0 += fabsf(r - xv); s1 += fabsf(r); s3 += fabsf(ev);
+            if constexpr (PREV) s2 += fabsf(ev - ep[i]);
+        }
+    }
+    if constexpr (SUMS) {
+        acc[0] += s0; acc[1] += s1; acc[2] += s2; acc[3] += s3;
+        block_store_partials<4>(acc, part);
+    }
+}
+
+__global__ void finish_sums4_kernel(const double* __restrict__ part, int nblocks, float* __restrict__ out) {
+    int k = threadIdx.x;
+    if (k < 4) {
+        double t = 0.0;
+        for (int b = 0; b < nblocks; ++b) t += part[(long)b * 4 + k];
+        out[k] = (float)t;
+    }
+}
+
+hipError_t launch_sampler_step(const float* x, const float* e, const float* e_prev, float* x_out,
+                               float a, float b, size_t n, float* sums4, void* ws, hipStream_t st) {
+    if (n == 0) {
+        if (sums4) {
+            // nothing to reduce: the finishing kernel with zero blocks writes four zeros
+            finish_sums4_kernel<<<1, 64, 0, st>>>((const double*)ws, 0, sums4);
+        }
+        return hipGetLastError();
+    }
+    int blocks = red_blocks(n);
+    double* part = (double*)ws;
+    if (!sums4)
+        sampler_step_kernel<false, false><<<blocks, RED_THREADS, 0, st>>>(x, e, nullptr, x_out, a, b, n, nullptr);
+    else if (e_prev)
+        sampler_step_kernel<true, true><<<blocks, RED_THREADS, 0, st>>>(x, e, e_prev, x_out, a, b, n, part);
+    else
+        sampler_step_kernel<true, false><<<blocks, RED_THREADS, 0, st>>>(x, e, nullptr, x_out, a, b, n, part);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    if (sums4) finish_sums4_kernel<<<1, 64, 0, st>>>(part, blocks, sums4);
+    return hipGetLastError();
+}
+
+__global__ void __launch_bounds__(RED_THREADS)
+rel_mae_kernel(const float* __restrict__ a, const float* __restrict__ b, size_t n, double* __restrict__ part) {
+    float s0 = 0.f, s1 = 0.f;
+    double acc[2] = {0.0, 0.0};
+    size_t nvec = n / 4;
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    const float4* a4 = reinterpret_cast<const float4*>(a);
+    const float4* b4 = reinterpret_cast<const float4*>(b);
+    int cnt = 0;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += stride) {
+        float4 av = a4[i], bv = b4[i];
+        s0 += (fabsf(av.x - bv.x) + fabsf(av.y - bv.y)) + (fabsf(av.z - bv.z) + fabsf(av.w - bv.w));
+        s1 += (fabsf(av.x) + fabsf(av.y)) + (fabsf(av.z) + fabsf(av.w));
+        if (++cnt == 16) { acc[0] += s0; acc[1] += s1; s0 = s1 = 0.f; cnt = 0; }
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
+        size_t i = nvec * 4 + threadIdx.x;
+        s0 += fabsf(a[i] - b[i]); s1 += fabsf(a[i]);
+    }
+    acc[0] += s0; acc[1] += s1;
+    block_store_partials<2>(acc, part);
+}
+
+__global__ void finish_rel_mae_kernel(const double* __restrict__ part, int nblocks, float* __restrict__ out3) {
+    if (threadIdx.x == 0) {
+        double num = 0.0, den = 0.0;
+        for (int b = 0; b < nblocks; ++b) { num += part[(long)b * 2]; den += part[(long)b * 2 + 1]; }
+        out3[0] = (float)num;
+        out3[1] = (float)den;
+        out3[2] = (float)(num / den);     // IEEE: inf or nan when the denominator is 0
+    }
+}
+
+hipError_t launch_rel_mae(const float* a, const float* b, size_t n, float* out3, void* ws, hipStream_t st) {
+    int blocks = n ? red_blocks(n) : 0;
+    double* part = (double*)ws;
+    if (blocks) {
+        rel_mae_kernel<<<blocks, RED_THREADS, 0, st>>>(a, b, n, part);
+        hipError_t err = hipGetLastError();
+        if (err != hipSuccess) return err;
+    }
+    finish_rel_mae_kernel<<<1, 64, 0, st>>>(part, blocks, out3);
+    return hipGetLastError();
+}
+
+}  // namespace ps

@@ -1,0 +1,196 @@
+"""GPU parity of dit_forward and sampler_run against the CPU oracle, through the C ABI.
+
+fp32 (tiny network): 1e-4 relative on eps, on every per-step sample and on the per-step
+relative MAEs.  bf16 (CogVideoX-2b width): rel-MAE <= 2e-2 against the float64 oracle run
+on the same bf16-rounded weights and inputs.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import parastep_oracle as O
+from paper_2505_14741_amd import binding as B
+from paper_2505_14741_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def dev(a, dtype=torch.float32):
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(dtype).to(DEV)
+
+
+def host(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def close_fp32(got, ref, tol=1e-4):
+    scale = max(np.abs(ref).max(), 1e-30)
+    err = np.abs(got - ref).max()
+    assert err <= tol * scale, (err, scale)
+    assert O.rel_mae(ref, got)[2] <= tol
+
+
+_CACHE = {}
+
+
+def setup(name, init="std002", cfg=None):
+    """Weights (host copy for the oracle, device copy behind a dit handle), cached per case."""
+    cfg = cfg or I.CONFIGS[name]
+    key = (name, init, cfg.layers)
+    if key not in _CACHE:
+        weights = I.make_weights(cfg, I.WEIGHT_SEED.get(name, 1000), init)
+        _CACHE[key] = (cfg, dict(weights), B.dit_create(cfg, B.weights_to_device(cfg, weights)))
+    return _CACHE[key]
+
+
+# ----------------------------------------------------------------------------- dit_forward
+@pytest.mark.parametrize("name", ["tiny", "tiny_text"])
+@pytest.mark.parametrize("init", ["std002", "unit"])
+def test_tiny_forward_fp32(name, init):
+    print(f"dit_forward {name} {init}", flush=True)
+    cfg, W, d = setup(name, init)
+    x, ctx = I.make_latent(cfg, 2), I.make_context(cfg, 2)
+    t = [875, 125]
+    eps = host(B.dit_forward(d, dev(x), dev(ctx), t))
+    ref = O.dit_forward(cfg, W, x, ctx, t)
+    close_fp32(eps, ref)
+
+
+def test_tiny_forward_batch_invariance_bitwise():
+    cfg, W, d = setup("tiny_text", "unit")
+    x, ctx = dev(I.make_latent(cfg, 4)), dev(I.make_context(cfg, 4))
+    t = [875, 625, 375, 0]
+    full = B.dit_forward(d, x, ctx, t).clone()
+    for b in range(4):
+        one = B.dit_forward(d, x[b:b + 1].contiguous(), ctx[b:b + 1].contiguous(), t[b:b + 1])
+        assert torch.equal(one[0], full[b]), b
+
+
+@pytest.mark.parametrize("init", ["std002", "unit"])
+def test_reduced_30_layer_forward_bf16(init):
+    """All 30 layers at width 1920 on 112 tokens: whole-model parity the oracle can afford."""
+    print(f"dit_forward reduced {init}", flush=True)
+    cfg, W, d = setup("reduced", init)
+    x, ctx = I.make_latent(cfg, 1), I.make_context(cfg, 1)
+    eps = host(B.dit_forward(d, dev(x), dev(ctx, torch.bfloat16), [500]))
+    ref = O.dit_forward(cfg, W, x, ctx, [500])
+    r = O.rel_mae(ref, eps)[2]
+    print(f"  rel-MAE {r:.3e}", flush=True)
+    assert r <= 2e-2 and np.isfinite(eps).all()
+
+
+def test_reduced_forward_generic_and_mfma_paths_agree():
+    cfg, W, d = setup("reduced", "unit", cfg=I.CONFIGS["reduced"].with_(layers=2))
+    x, ctx = dev(I.make_latent(cfg, 1)), dev(I.make_context(cfg, 1), torch.bfloat16)
+    fast = host(B.dit_forward(d, x, ctx, [300]))
+    B.ps_set_kernel_path(1)
+    try:
+        slow = host(B.dit_forward(d, x, ctx, [300]))
+    finally:
+        B.ps_set_kernel_path(0)
+    assert O.rel_mae(slow, fast)[2] < 1e-2
+
+
+@pytest.mark.parametrize("init", ["std002", "unit"])
+def test_block_forward_bf16_whole(init):
+    """One block at CogVideoX-2b width, 4290 video + 226 text tokens, whole output vs oracle."""
+    print(f"dit_forward block {init}", flush=True)
+    cfg, W, d = setup("block", init)
+    x, ctx = I.make_latent(cfg, 1), I.make_context(cfg, 1)
+    eps = host(B.dit_forward(d, dev(x), dev(ctx, torch.bfloat16), [500]))
+    ref = O.dit_forward(cfg, W, x, ctx, [500])
+    r = O.rel_mae(ref, eps)[2]
+    print(f"  rel-MAE {r:.3e}", flush=True)
+    assert r <= 2e-2
+
+
+# ----------------------------------------------------------------------------- sampler_run
+def oracle_run(cfg, W, x_T, ctx, S, m, cyc, mode="reuse_then_predict"):
+    tau, a, b = O.ddim_coefficients(steps=S)
+    f = lambda x, t: O.dit_forward(cfg, W, x[None], ctx, [t])[0]
+    return O.run_sampler(f, x_T[0], tau, a, b, warmup=m, cycle_len=cyc, mode=mode)
+
+
+def gpu_run(d, x_T, ctx, S, m, cyc, batched=False, mode=0):
+    ts, a, b = B.ddim_coefficients(S)
+    sched = B.Schedule(ts, a, b, m, cyc, batched=batched, mode=mode)
+    x0, sums, calls = B.sampler_run(d, sched, x_T, ctx)
+    torch.cuda.synchronize()
+    return x0, sums, calls
+
+
+@pytest.mark.parametrize("name,init,S,m,cyc", [
+    ("tiny", "std002", 8, 2, [2, 2, 2]),
+    ("tiny", "unit", 8, 2, [2, 2, 2]),
+    ("tiny_text", "unit", 7, 1, [3, 3]),
+    ("tiny", "unit", 6, 2, [3, 3]),            # run ends mid-cycle
+    ("tiny_text", "unit", 10, 1, [1, 2, 4, 2]),  # changing cycle lengths
+])
+def test_tiny_run_matches_oracle(name, init, S, m, cyc):
+    print(f"sampler_run {name} {init} S={S} m={m} cyc={cyc}", flush=True)
+    cfg, W, d = setup(name, init)
+    x_T, ctx = I.make_latent(cfg, 1), I.make_context(cfg, 1)
+    ref = oracle_run(cfg, W, x_T, ctx, S, m, cyc)
+    x0, sums, calls = gpu_run(d, dev(x_T), dev(ctx), S, m, cyc)
+    assert calls == S == ref["calls"]
+    close_fp32(host(x0)[0], ref["x0"])
+    s = host(sums)
+    rx = s[:, 0] / s[:, 1]
+    re = s[1:, 2] / s[1:, 3]
+    np.testing.assert_allclose(rx, ref["rx"], rtol=1e-4)
+    np.testing.assert_allclose(re, ref["re"][1:], rtol=1e-4, atol=1e-7)
+    assert s[0, 2] == 0.0
+
+
+@pytest.mark.parametrize("S,m,cyc", [(8, 2, [2, 2, 2]), (9, 1, [4, 4]), (7, 1, [3, 3]), (10, 1, [1, 2, 4, 2])])
+def test_batched_run_equals_unbatched_bitwise(S, m, cyc):
+    cfg, W, d = setup("tiny_text", "unit")
+    x_T, ctx = dev(I.make_latent(cfg, 1)), dev(I.make_context(cfg, 1))
+    x0a, sa, ca = gpu_run(d, x_T, ctx, S, m, cyc, batched=False)
+    x0b, sb, cb = gpu_run(d, x_T, ctx, S, m, cyc, batched=True)
+    assert torch.equal(x0a, x0b) and torch.equal(sa, sb)
+    assert ca == S and cb == m + len(O.expand_cycles(S, m, cyc))
+
+
+def test_window_one_is_the_plain_loop_bitwise():
+    cfg, W, d = setup("tiny", "unit")
+    x_T = dev(I.make_latent(cfg, 1))
+    S = 8
+    ts, a, b = B.ddim_coefficients(S)
+    x = x_T.clone()
+    for i in range(S):
+        eps = B.dit_forward(d, x, None, [int(ts[i])])
+        x, _ = B.sampler_step(x, eps, None, float(a[i]), float(b[i]), want_sums=False)
+    for m, cyc in [(0, [1] * S), (S, []), (3, [1] * S)]:
+        x0, _, calls = gpu_run(d, x_T, None, S, m, cyc)
+        assert torch.equal(x0, x) and calls == S
+
+
+def test_direct_reuse_matches_oracle():
+    cfg, W, d = setup("tiny", "unit")
+    x_T = I.make_latent(cfg, 1)
+    ref = oracle_run(cfg, W, x_T, None, 7, 1, [2, 2, 2], mode="direct_reuse")
+    x0, sums, calls = gpu_run(d, dev(x_T), None, 7, 1, [2, 2, 2], mode=1)
+    assert calls == 4 == ref["calls"]
+    close_fp32(host(x0)[0], ref["x0"])
+    s = host(sums)
+    np.testing.assert_allclose(s[:, 0] / s[:, 1], ref["rx"], rtol=1e-4)
+
+
+def test_reduced_30_layer_reuse_run_bf16():
+    """Six DDIM steps, window 2, 30 layers at width 1920 on 112 tokens, vs the oracle."""
+    print("sampler_run reduced", flush=True)
+    cfg, W, d = setup("reduced", "unit")
+    x_T, ctx = I.make_latent(cfg, 1), I.make_context(cfg, 1)
+    ref = oracle_run(cfg, W, x_T, ctx, 6, 2, [2, 2])
+    x0, sums, calls = gpu_run(d, dev(x_T), dev(ctx, torch.bfloat16), 6, 2, [2, 2])
+    r = O.rel_mae(ref["x0"], host(x0)[0])[2]
+    print(f"  x0 rel-MAE {r:.3e}", flush=True)
+    assert calls == 6 and r <= 2e-2
+    # reuse changes the result but stays finite and reproducible; window 1 is the no-reuse run
+    x0p, _, _ = gpu_run(d, dev(x_T), dev(ctx, torch.bfloat16), 6, 2, [1, 1, 1, 1])
+    dev_r = host(B.rel_mae(x0p, x0))[2]
+    assert np.isfinite(dev_r) and dev_r > 0
+    x0again, _, _ = gpu_run(d, dev(x_T), dev(ctx, torch.bfloat16), 6, 2, [2, 2])
+    assert torch.equal(x0again, x0)

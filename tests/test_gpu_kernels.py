@@ -1,0 +1,246 @@
+"""GPU parity of the stand-alone entry points (sampler_step, rel_mae, attn3d, dit_linear)
+against the CPU oracle, element by element, through the C ABI.
+
+Tolerances: fp32 paths must agree with the float64 oracle to 1e-4 relative
+(rel-MAE <= 1e-4 and max |err| <= 1e-4 * max |ref|); bf16 paths to 2e-2 rel-MAE against
+the oracle run on the same bf16-rounded inputs.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import parastep_oracle as O
+from paper_2505_14741_amd import binding as B
+from paper_2505_14741_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def dev(a, dtype=torch.float32):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(dtype).to(DEV)
+
+
+def host(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def assert_close_fp32(got, ref, tol=1e-4):
+    ref = np.asarray(ref, dtype=np.float64)
+    got = np.asarray(got, dtype=np.float64)
+    scale = max(np.abs(ref).max(), 1e-30)
+    assert np.abs(got - ref).max() <= tol * scale, (np.abs(got - ref).max(), scale)
+    assert O.rel_mae(ref, got)[2] <= tol
+
+
+def assert_close_bf16(got, ref, tol=2e-2, max_tol=None):
+    r = O.rel_mae(ref, got)[2]
+    assert r <= tol, r
+    if max_tol is not None:
+        assert np.abs(np.asarray(got) - np.asarray(ref)).max() <= max_tol * max(np.abs(ref).max(), 1e-30)
+    return r
+
+
+# ------------------------------------------------------------------- sampler_step / rel_mae
+@pytest.mark.parametrize("n", [4, 5, 7, 1000, 4099, 2048 * 16 + 3, 1123200])
+def test_sampler_step_matches_oracle(n):
+    print(f"sampler_step n={n}", flush=True)
+    rng = np.random.default_rng(n)
+    x, e, p = (rng.standard_normal(n).astype(np.float32) for _ in range(3))
+    a, b = np.float32(1.0372), np.float32(-0.2114)
+    xo, sums = B.sampler_step(dev(x), dev(e), dev(p), a, b)
+    torch.cuda.synchronize()
+    ref = O.sampler_step(x, e, a, b)
+    assert_close_fp32(host(xo), ref, 1e-6)
+    want = [np.abs(ref - x).sum(), np.abs(ref).sum(), np.abs(e.astype(np.float64) - p).sum(), np.abs(e).sum()]
+    np.testing.assert_allclose(host(sums), want, rtol=2e-5)
+    # without eps_prev, and in place
+    xd = dev(x)
+    xo2, sums2 = B.sampler_step(xd, dev(e), None, a, b, x_out=xd)
+    torch.cuda.synchronize()
+    assert torch.equal(xo2, xo)
+    got = host(sums2)
+    np.testing.assert_allclose(got[[0, 1, 3]], np.array(want)[[0, 1, 3]], rtol=2e-5)
+    assert got[2] == 0.0
+    # no sums requested
+    xo3, none = B.sampler_step(dev(x), dev(e), None, a, b, want_sums=False)
+    torch.cuda.synchronize()
+    assert none is None and torch.equal(xo3, xo)
+
+
+def test_sampler_step_is_deterministic_and_exact_in_fp32():
+    n = 1123200
+    rng = np.random.default_rng(1)
+    x, e, p = (dev(rng.standard_normal(n).astype(np.float32)) for _ in range(3))
+    r1 = B.sampler_step(x, e, p, 0.99, 0.05)
+    r2 = B.sampler_step(x, e, p, 0.99, 0.05)
+    torch.cuda.synchronize()
+    assert torch.equal(r1[0], r2[0]) and torch.equal(r1[1], r2[1])
+    # element-wise result is the fp32 expression a*x + b*e up to one rounding of each product/sum
+    ref = np.float32(0.99) * x.cpu().numpy() + np.float32(0.05) * e.cpu().numpy()
+    assert np.abs(r1[0].cpu().numpy() - ref).max() <= 2.5e-7 * np.abs(ref).max()
+
+
+@pytest.mark.parametrize("n", [1, 4, 6, 1023, 65537, 1123200])
+def test_rel_mae_matches_oracle(n):
+    print(f"rel_mae n={n}", flush=True)
+    rng = np.random.default_rng(n + 1)
+    a, b = rng.standard_normal(n).astype(np.float32), rng.standard_normal(n).astype(np.float32)
+    out = host(B.rel_mae(dev(a), dev(b)))
+    num, den, ratio = O.rel_mae(a, b)
+    np.testing.assert_allclose(out, [num, den, ratio], rtol=2e-5)
+
+
+def test_rel_mae_closed_forms_and_zero_denominator():
+    a = dev(np.random.default_rng(0).standard_normal(5000).astype(np.float32))
+    assert host(B.rel_mae(a, a))[2] == 0.0
+    assert host(B.rel_mae(a, torch.zeros_like(a)))[2] == pytest.approx(1.0, rel=1e-6)
+    assert host(B.rel_mae(a, -a))[2] == pytest.approx(2.0, rel=1e-6)
+    assert host(B.rel_mae(a, 1.25 * a))[2] == pytest.approx(0.25, rel=1e-5)
+    z = torch.zeros(64, device=DEV)
+    assert math.isnan(host(B.rel_mae(z, z))[2])
+    assert math.isinf(host(B.rel_mae(z, torch.ones_like(z)))[2])
+
+
+# ---------------------------------------------------------------------------------- attn3d
+@pytest.mark.parametrize("d", [16, 32, 64])
+@pytest.mark.parametrize("N", [1, 63, 64, 65, 127, 129, 300])
+def test_attention_fp32_matches_oracle(N, d):
+    print(f"attn3d fp32 N={N} d={d}", flush=True)
+    q, k, v = I.make_qkv(2, N, 3, d, dtype="f32")
+    scale = 1.0 / math.sqrt(d)
+    o = B.attn3d(dev(q), dev(k), dev(v), scale)
+    torch.cuda.synchronize()
+    assert_close_fp32(host(o), O.attn3d(q, k, v, scale))
+
+
+@pytest.mark.parametrize("N", [1, 31, 63, 64, 65, 127, 129, 255, 257, 1000])
+def test_attention_bf16_mfma_matches_oracle(N):
+    print(f"attn3d bf16 N={N}", flush=True)
+    q, k, v = I.make_qkv(2, N, 3, 64, dtype="bf16")
+    o = B.attn3d(dev(q, torch.bfloat16), dev(k, torch.bfloat16), dev(v, torch.bfloat16), 0.125)
+    torch.cuda.synchronize()
+    ref = O.attn3d(q, k, v, 0.125)
+    r = assert_close_bf16(host(o), ref, 2e-2, max_tol=3e-2)
+    assert r < 8e-3      # bf16 rounding of P and of the output only
+
+
+def test_attention_bf16_large_logits_and_poisoned_workspace():
+    """Logit std ~ 4 (sharp softmax), NaN-filled scratch and output must not leak."""
+    N = 333
+    q, k, v = I.make_qkv(1, N, 2, 64, dtype="bf16", scale=2.0)
+    qd, kd, vd = (dev(a, torch.bfloat16) for a in (q, k, v))
+    out = torch.full_like(qd, float("nan"))
+    junk = torch.full((1 << 22,), float("nan"), device=DEV)      # poison recently freed memory
+    del junk
+    o = B.attn3d(qd, kd, vd, 0.125, out=out)
+    torch.cuda.synchronize()
+    assert torch.isfinite(o).all()
+    assert_close_bf16(host(o), O.attn3d(q, k, v, 0.125), 2e-2)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_attention_invariants(dtype):
+    td = torch.float32 if dtype == "f32" else torch.bfloat16
+    N, H, d = 200, 2, 64
+    q, k, v = I.make_qkv(1, N, H, d, dtype=dtype)
+    # identical keys -> mean of V for every query
+    k1 = k.copy(); k1[:] = k[:, :1]
+    o = host(B.attn3d(dev(q, td), dev(k1, td), dev(v, td), 0.125))
+    ref = np.broadcast_to(v.astype(np.float64).mean(axis=1, keepdims=True), o.shape)
+    assert np.abs(o - ref).max() < (1e-5 if dtype == "f32" else 6e-3)
+    # one dominant key -> its value
+    k2 = np.zeros_like(k)
+    qn = q[0, 5, 0] / np.linalg.norm(q[0, 5, 0])
+    k2[0, 77, 0] = I.round_to_bf16((60.0 * qn).astype(np.float32)) if dtype == "bf16" else 60.0 * qn
+    o2 = host(B.attn3d(dev(q, td), dev(k2, td), dev(v, td), 1.0))
+    assert np.abs(o2[0, 5, 0] - v[0, 77, 0]).max() < (1e-5 if dtype == "f32" else 1e-2)
+    # permuting keys together with values changes nothing but the summation order
+    perm = np.random.default_rng(0).permutation(N)
+    oa = host(B.attn3d(dev(q, td), dev(k, td), dev(v, td), 0.125))
+    ob = host(B.attn3d(dev(q, td), dev(k[:, perm], td), dev(v[:, perm], td), 0.125))
+    assert np.abs(oa - ob).max() < (1e-5 if dtype == "f32" else 8e-3)
+
+
+def test_attention_bf16_generic_and_mfma_paths_agree():
+    q, k, v = I.make_qkv(1, 190, 2, 64, dtype="bf16")
+    args = (dev(q, torch.bfloat16), dev(k, torch.bfloat16), dev(v, torch.bfloat16), 0.125)
+    fast = host(B.attn3d(*args))
+    B.ps_set_kernel_path(1)
+    try:
+        slow = host(B.attn3d(*args))
+    finally:
+        B.ps_set_kernel_path(0)
+    ref = O.attn3d(q, k, v, 0.125)
+    assert O.rel_mae(ref, slow)[2] < 4e-3 and O.rel_mae(ref, fast)[2] < 8e-3
+
+
+def test_attention_block_shape_whole():
+    """One block's attention at CogVideoX-2b width: 4516 tokens, 30 heads of 64, logit std ~1."""
+    cfg = I.CONFIGS["block"]
+    print("attn3d bf16 N=4516 H=30 whole", flush=True)
+    q, k, v = I.make_qkv(1, cfg.tokens, cfg.heads, 64, dtype="bf16")
+    o = host(B.attn3d(dev(q, torch.bfloat16), dev(k, torch.bfloat16), dev(v, torch.bfloat16), 0.125))
+    ref = O.attn3d(q, k, v, 0.125)
+    assert_close_bf16(o, ref, 2e-2)
+
+
+@pytest.mark.parametrize("name,batch", [("full", 1), ("long", 1), ("full", 4)])
+def test_attention_full_shape_sampled_rows(name, batch):
+    """Launch configuration of the benchmark; the oracle evaluates 48 sampled query rows of
+    every head (each output row needs only its query row and all keys/values)."""
+    cfg = I.CONFIGS[name]
+    N = cfg.tokens
+    print(f"attn3d bf16 N={N} B={batch} sampled rows", flush=True)
+    q, k, v = I.make_qkv(batch, N, cfg.heads, 64, dtype="bf16")
+    o = B.attn3d(dev(q, torch.bfloat16), dev(k, torch.bfloat16), dev(v, torch.bfloat16), 0.125)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    rows = np.unique(np.concatenate([[0, 63, 64, 255, 256, N - 257, N - 2, N - 1], rng.integers(0, N, 40)]))
+    for b in sorted({0, batch - 1}):
+        ref = O.attn3d(q[b:b + 1, rows], k[b:b + 1], v[b:b + 1], 0.125)
+        got = host(o[b:b + 1, torch.from_numpy(rows).to(DEV)])
+        assert_close_bf16(got, ref, 2e-2)
+    assert torch.isfinite(o).all()
+
+
+# ------------------------------------------------------------------------------ dit_linear
+@pytest.mark.parametrize("M,Nn,K", [(1, 64, 64), (5, 66, 64), (130, 192, 128), (257, 130, 192), (300, 384, 64)])
+@pytest.mark.parametrize("act", [0, 1])
+def test_linear_small_shapes_both_dtypes(M, Nn, K, act):
+    print(f"dit_linear M={M} N={Nn} K={K} act={act}", flush=True)
+    rng = np.random.default_rng(M + Nn)
+    for dtype, td in (("f32", torch.float32), ("bf16", torch.bfloat16)):
+        a = I.make_tokens(M, K, 3, dtype)
+        w = (rng.standard_normal((Nn, K)) / math.sqrt(K)).astype(np.float32)
+        w = I.round_to_bf16(w) if dtype == "bf16" else w
+        bias = rng.standard_normal(Nn).astype(np.float32)
+        out = host(B.dit_linear(dev(a, td), dev(w, td), dev(bias), act))
+        ref = a.astype(np.float64) @ w.astype(np.float64).T + bias
+        if act:
+            ref = O.gelu_tanh(ref)
+        if dtype == "f32":
+            assert_close_fp32(out, ref)
+        else:
+            assert_close_bf16(out, ref, 5e-3, max_tol=1e-2)
+
+
+@pytest.mark.parametrize("Nn,K,act", [(5760, 1920, 0), (1920, 1920, 0), (7680, 1920, 1), (1920, 7680, 0)])
+def test_linear_full_shapes_sampled_rows(Nn, K, act):
+    """The four projections of a block at 17776 tokens; the oracle checks 64 sampled rows."""
+    M = I.CONFIGS["full"].tokens
+    print(f"dit_linear M={M} N={Nn} K={K}", flush=True)
+    a = I.make_tokens(M, K, 21, "bf16")
+    rng = np.random.default_rng(22)
+    w = I.round_to_bf16((rng.standard_normal((Nn, K)) / math.sqrt(K)).astype(np.float32))
+    bias = rng.standard_normal(Nn).astype(np.float32)
+    out = B.dit_linear(dev(a, torch.bfloat16), dev(w, torch.bfloat16), dev(bias), act)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([[0, 127, 128, 255, 256, M - 129, M - 1], rng.integers(0, M, 57)]))
+    ref = a[rows].astype(np.float64) @ w.astype(np.float64).T + bias
+    if act:
+        ref = O.gelu_tanh(ref)
+    assert_close_bf16(host(out[torch.from_numpy(rows).to(DEV)]), ref, 5e-3, max_tol=1e-2)
+    assert torch.isfinite(out).all()

@@ -1,0 +1,201 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every declared symbol, its
+host-only DDIM table matches the oracle, and every error path answers before any launch."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import parastep_oracle as O
+from paper_2505_14741_amd import binding as B
+from paper_2505_14741_amd import inputs as I
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "parastep.h")).read()
+    return re.findall(r"^PS_API\s+[\w\s\*]+?\b(\w+)\(", text, flags=re.M)
+
+
+def test_library_exports_every_declared_symbol():
+    L = B.lib()
+    names = declared_symbols()
+    assert len(names) >= 18
+    for n in names:
+        assert hasattr(L, n), n
+    assert set(names) == set(B.EXPORTED)
+
+
+def test_strerror_is_total():
+    L = B.lib()
+    seen = {L.ps_strerror(s) for s in range(0, -7, -1)}
+    assert len(seen) == 7 and L.ps_strerror(-99) == b"unknown status"
+
+
+@pytest.mark.parametrize("S", [5, 8, 50])
+def test_ddim_table_matches_oracle(S):
+    ts, a, b = B.ddim_coefficients(S)
+    tau, ao, bo = O.ddim_coefficients(steps=S)
+    np.testing.assert_array_equal(ts, tau)
+    np.testing.assert_allclose(a, ao, rtol=1e-7)
+    np.testing.assert_allclose(b, bo, rtol=2e-7)
+
+
+def test_ddim_table_rejects_bad_arguments():
+    L = B.lib()
+    ts = (C.c_int32 * 4)(); a = (C.c_float * 4)(); b = (C.c_float * 4)()
+    assert L.ddim_coefficients(1000, 1e-4, 2e-2, 4, None, a, b) == -1
+    assert L.ddim_coefficients(1000, 1e-4, 2e-2, 0, ts, a, b) == -5
+    assert L.ddim_coefficients(3, 1e-4, 2e-2, 4, ts, a, b) == -5
+    assert L.ddim_coefficients(1000, 2e-2, 1e-4, 4, ts, a, b) == -5
+
+
+def _cfg_struct(cfg, **over):
+    vals = dict(layers=cfg.layers, hidden=cfg.hidden, heads=cfg.heads, head_dim=cfg.head_dim,
+                mlp_ratio=cfg.mlp_ratio, in_channels=cfg.in_channels, patch=cfg.patch, frames=cfg.frames,
+                height=cfg.height, width=cfg.width, text_tokens=cfg.text_tokens,
+                time_embed_dim=cfg.time_embed_dim, dtype=0, ln_eps=cfg.ln_eps, rope_theta=cfg.rope_theta)
+    vals.update(over)
+    return B._DitConfig(**vals)
+
+
+def _fake_weights(n):
+    # never dereferenced: creation only records the addresses
+    return (C.c_void_p * n)(*[0x1000 * (i + 1) for i in range(n)])
+
+
+def _create(cfg_struct, nw=None, weights=None):
+    L = B.lib()
+    n = L.dit_num_weights(cfg_struct.layers) if nw is None else nw
+    h = C.c_void_p()
+    w = _fake_weights(max(n, 1)) if weights is None else weights
+    rc = L.dit_create(C.byref(cfg_struct), w, n, C.byref(h))
+    return rc, h
+
+
+def test_dit_create_validation():
+    L = B.lib()
+    cfg = I.CONFIGS["tiny"]
+    assert L.dit_num_weights(2) == 30 and L.dit_num_weights(30) == 310
+    rc, h = _create(_cfg_struct(cfg))
+    assert rc == 0 and h.value
+    assert L.dit_workspace_bytes(h, 1) > 0 and L.dit_workspace_bytes(h, 0) == 0 and L.dit_workspace_bytes(h, 17) == 0
+    assert L.dit_workspace_bytes(h, 4) > 3 * L.dit_workspace_bytes(h, 1) // 2
+    assert L.dit_destroy(h) == 0
+    assert L.dit_destroy(None) == -1
+    assert _create(_cfg_struct(cfg, dtype=7))[0] == -3
+    assert _create(_cfg_struct(cfg, hidden=60))[0] == -2            # != heads*head_dim
+    assert _create(_cfg_struct(cfg, head_dim=24, hidden=96))[0] == -2
+    assert _create(_cfg_struct(cfg, height=15))[0] == -2            # not divisible by patch
+    assert _create(_cfg_struct(cfg, layers=0))[0] == -2
+    assert _create(_cfg_struct(cfg, text_tokens=-1))[0] == -2
+    assert _create(_cfg_struct(cfg), nw=29)[0] == -2                # wrong weight count
+    w = _fake_weights(30); w[7] = None
+    assert _create(_cfg_struct(cfg), weights=w)[0] == -1            # NULL weight
+    w = _fake_weights(30); w[3] = 0x1004
+    assert _create(_cfg_struct(cfg), weights=w)[0] == -2            # misaligned weight
+    assert L.dit_create(None, _fake_weights(30), 30, C.byref(C.c_void_p())) == -1
+
+
+def test_dit_forward_validation_has_no_side_effects():
+    L = B.lib()
+    cfg = I.CONFIGS["tiny_text"]
+    rc, h = _create(_cfg_struct(cfg))
+    assert rc == 0
+    need = L.dit_workspace_bytes(h, 1)
+    t = (C.c_int32 * 1)(500)
+    X, E, CTX, WS = 0x10000, 0x20000, 0x30000, 0x40000
+    f = lambda **k: L.dit_forward(k.get("h", h), k.get("x", X), k.get("ctx", CTX), k.get("t", t), k.get("e", E),
+                                  k.get("batch", 1), k.get("ws", WS), k.get("wsb", need), None)
+    assert f(x=None) == -1 and f(e=None) == -1 and f(t=None) == -1 and f(h=None) == -1
+    assert f(ctx=None) == -1                                        # text tokens need a context
+    assert f(batch=0) == -2 and f(batch=17) == -2
+    assert f(e=X) == -2                                             # aliasing
+    assert f(x=X + 4) == -2                                         # misaligned
+    assert f(t=(C.c_int32 * 1)(-3)) == -2
+    assert f(ws=None) == -4 and f(wsb=need - 1) == -4 and f(ws=WS + 16) == -4
+    L.dit_destroy(h)
+
+
+def test_attn3d_validation():
+    L = B.lib()
+    Q, K, V, Oo, WS = 0x1000, 0x2000, 0x3000, 0x4000, 0x10000
+    f = lambda **k: L.attn3d(k.get("q", Q), K, V, k.get("o", Oo), k.get("b", 1), k.get("n", 10), 2, k.get("d", 16),
+                             k.get("scale", 0.25), k.get("dt", 0), k.get("ws", None), k.get("wsb", 0), None)
+    assert f(q=None) == -1 and f(o=None) == -1
+    assert f(dt=5) == -3
+    assert f(n=0) == -2 and f(b=0) == -2 and f(d=48) == -2 and f(d=128) == -2
+    assert f(scale=0.0) == -2 and f(scale=float("nan")) == -2 and f(scale=-1.0) == -2
+    assert f(o=Q) == -2 and f(q=Q + 2) == -2
+    # the bf16 head-dim-64 kernel needs a workspace; fp32 does not
+    assert L.attn3d_workspace_bytes(1, 100, 2, 64, 1) >= 2 * 64 * 128 * 2
+    assert L.attn3d_workspace_bytes(1, 100, 2, 16, 0) == 0
+    assert f(d=64, dt=1, ws=None) == -4 and f(d=64, dt=1, ws=WS, wsb=8) == -4
+
+
+def test_sampler_step_and_rel_mae_validation():
+    L = B.lib()
+    X, E, P, WS = 0x1000, 0x2000, 0x3000, 0x10000
+    need = L.sampler_step_workspace_bytes(1000)
+    assert need > 0 and need % 256 == 0
+    f = lambda **k: L.sampler_step(k.get("x", X), k.get("e", E), k.get("p", P), k.get("xo", X), 1.0, 0.5, 1000,
+                                   k.get("s", 0x5000), k.get("ws", WS), k.get("wsb", need), None)
+    assert f(x=None) == -1 and f(e=None) == -1 and f(xo=None) == -1
+    assert f(xo=E) == -2 and f(xo=P) == -2 and f(x=X + 8) == -2
+    assert f(ws=None) == -4 and f(wsb=need - 1) == -4 and f(ws=WS + 64) == -4
+    g = lambda **k: L.rel_mae(k.get("a", X), k.get("b", E), 1000, k.get("o", 0x5000), k.get("ws", WS),
+                              k.get("wsb", need), None)
+    assert g(a=None) == -1 and g(o=None) == -1 and g(ws=None) == -4 and g(a=X + 4) == -2
+
+
+def _sched(steps=8, warmup=2, cyc=(2, 2, 2), batched=0, mode=0, ts=None):
+    tau, a, b = O.ddim_coefficients(steps=steps)
+    return B.Schedule(tau if ts is None else ts, a, b, warmup, list(cyc), batched=batched, mode=mode)
+
+
+def test_schedule_validation():
+    L = B.lib()
+    cfg = I.CONFIGS["tiny"]
+    rc, h = _create(_cfg_struct(cfg))
+    ok = _sched()
+    assert L.sampler_workspace_bytes(h, C.byref(ok.c)) > 0
+    assert L.sampler_workspace_bytes(h, C.byref(_sched(batched=1).c)) > L.sampler_workspace_bytes(h, C.byref(ok.c))
+    bad = [
+        _sched(warmup=0),                         # eps_cache undefined: no warm-up, window 2
+        _sched(cyc=(2, 2)),                       # cycles do not cover steps - warmup
+        _sched(cyc=(2, 0, 4)),                    # zero-length cycle
+        _sched(cyc=(17,)),                        # beyond the batch limit
+        _sched(mode=2), _sched(batched=1, mode=1), _sched(warmup=-1),
+        _sched(ts=[875, 750, 625, 625, 375, 250, 125, 0]),     # not strictly descending
+    ]
+    for s in bad:
+        assert L.sampler_workspace_bytes(h, C.byref(s.c)) == 0
+        assert L.sampler_run(h, C.byref(s.c), 0x1000, None, 0x2000, None, None, 0x10000, 1 << 40, None) == -5
+    # window 1 needs no warm-up; all-warm-up needs no cycles
+    assert L.sampler_workspace_bytes(h, C.byref(_sched(warmup=0, cyc=[1] * 8).c)) > 0
+    assert L.sampler_workspace_bytes(h, C.byref(_sched(warmup=8, cyc=[]).c)) > 0
+    # pointer and workspace checks
+    need = L.sampler_workspace_bytes(h, C.byref(ok.c))
+    assert L.sampler_run(h, C.byref(ok.c), None, None, 0x2000, None, None, 0x10000, need, None) == -1
+    assert L.sampler_run(h, C.byref(ok.c), 0x1000, None, 0x2000, None, None, 0x10000, need - 1, None) == -4
+    assert L.sampler_run(h, C.byref(ok.c), 0x1000, None, 0x2000, None, None, None, need, None) == -4
+    L.dit_destroy(h)
+
+
+def test_inputs_are_reproducible_and_bf16_exact():
+    cfg = I.CONFIGS["reduced"]
+    w1 = I.make_weights(cfg.with_(layers=1), 5)
+    w2 = I.make_weights(cfg.with_(layers=1), 5)
+    for (n1, a1), (n2, a2) in zip(w1, w2):
+        assert n1 == n2 and np.array_equal(a1, a2)
+    m = dict(w1)["W_qkv.0"]
+    assert np.array_equal(m, I.round_to_bf16(m))                    # already representable
+    assert (m.view(np.uint32) & 0xFFFF).max() == 0
+    r = I.round_to_bf16(np.array([1.0 + 2 ** -8, 1.0 + 3 * 2 ** -8, -1.0 - 2 ** -9], dtype=np.float32))
+    np.testing.assert_array_equal(r, np.array([1.0, 1.0 + 2 ** -6, -1.0], dtype=np.float32))   # ties to even
+    assert [n for n, _ in I.weight_shapes(cfg)][:8] == ["W_pe", "b_pe", "W_t1", "b_t1", "W_t2", "b_t2",
+                                                         "W_mod.0", "b_mod.0"]
+    assert cfg.tokens == 16 + 2 * 6 * 8 and I.CONFIGS["full"].tokens == 17776 and I.CONFIGS["long"].tokens == 33976
+    assert I.CONFIGS["block"].tokens == 4516 and I.CONFIGS["full"].latent_elems == 1123200
