@@ -132,11 +132,14 @@ PS_API int ps_set_kernel_path(int path);
  * Section 3) and, if sums4 != NULL, the four sums behind the adjacent-step relative
  * MAEs of Eq. (1):  sums4 = { sum|x_out-x|, sum|x_out|, sum|eps-eps_prev|, sum|eps| }
  * (the last two use eps_prev; with eps_prev == NULL they are 0 and sum|eps|).
+ * The coefficients are doubles because a -> 1 towards the end of a run: the kernel works
+ * in fp32 on the increment  d = (a-1)*x + b*eps,  x_out = x + d,  sum|x_out-x| = sum|d|,
+ * with (a-1) rounded to fp32 only after the subtraction.
  * x_out may alias x.  workspace: DEVICE, >= sampler_step_workspace_bytes(n), only
  * needed when sums4 != NULL. */
 PS_API size_t sampler_step_workspace_bytes(size_t n);
 PS_API int sampler_step(const float* x, const float* eps, const float* eps_prev, float* x_out,
-                 float a, float b, size_t n, float* sums4,
+                 double a, double b, size_t n, float* sums4,
                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Relative MAE of Eq. (1): out3 = { sum|a-b|, sum|a|, sum|a-b| / sum|a| } (DEVICE fp32).
@@ -150,7 +153,7 @@ PS_API int rel_mae(const float* a, const float* b, size_t n, float* out3,
  * b_i = sqrt(1-abar_prev) - a_i*sqrt(1-abar_tau), abar_prev = 1 after the last step.
  * Outputs are HOST arrays of length `steps`. */
 PS_API int ddim_coefficients(int train_steps, double beta_start, double beta_end, int steps,
-                      int32_t* timesteps_out, float* a_out, float* b_out);
+                      int32_t* timesteps_out, double* a_out, double* b_out);
 
 /* ------------------------------------------------------------- reuse-then-predict run
  * Algorithm 1 with all ranks of a cycle simulated on one device.
@@ -164,8 +167,8 @@ PS_API int ddim_coefficients(int train_steps, double beta_start, double beta_end
 typedef struct {
     int steps;
     const int32_t* timesteps;   /* HOST [steps], descending */
-    const float* coef_a;        /* HOST [steps] */
-    const float* coef_b;        /* HOST [steps] */
+    const double* coef_a;       /* HOST [steps] */
+    const double* coef_b;       /* HOST [steps] */
     int warmup;
     int n_cycles;
     const int32_t* cycle_len;

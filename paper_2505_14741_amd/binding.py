@@ -37,8 +37,8 @@ class _DitConfig(C.Structure):
 
 
 class _Schedule(C.Structure):
-    _fields_ = [("steps", C.c_int), ("timesteps", C.POINTER(C.c_int32)), ("coef_a", C.POINTER(C.c_float)),
-                ("coef_b", C.POINTER(C.c_float)), ("warmup", C.c_int), ("n_cycles", C.c_int),
+    _fields_ = [("steps", C.c_int), ("timesteps", C.POINTER(C.c_int32)), ("coef_a", C.POINTER(C.c_double)),
+                ("coef_b", C.POINTER(C.c_double)), ("warmup", C.c_int), ("n_cycles", C.c_int),
                 ("cycle_len", C.POINTER(C.c_int32)), ("batched", C.c_int), ("mode", C.c_int)]
 
 
@@ -65,11 +65,11 @@ def lib():
         "attn3d": (i32, [vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, vp, sz, vp]),
         "dit_linear": (i32, [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp]),
         "sampler_step_workspace_bytes": (sz, [sz]),
-        "sampler_step": (i32, [vp, vp, vp, vp, f32, f32, sz, vp, vp, sz, vp]),
+        "sampler_step": (i32, [vp, vp, vp, vp, C.c_double, C.c_double, sz, vp, vp, sz, vp]),
         "rel_mae_workspace_bytes": (sz, [sz]),
         "rel_mae": (i32, [vp, vp, sz, vp, vp, sz, vp]),
-        "ddim_coefficients": (i32, [i32, C.c_double, C.c_double, i32, C.POINTER(C.c_int32), C.POINTER(f32),
-                                    C.POINTER(f32)]),
+        "ddim_coefficients": (i32, [i32, C.c_double, C.c_double, i32, C.POINTER(C.c_int32),
+                                    C.POINTER(C.c_double), C.POINTER(C.c_double)]),
         "sampler_workspace_bytes": (sz, [vp, C.POINTER(_Schedule)]),
         "sampler_run": (i32, [vp, C.POINTER(_Schedule), vp, vp, vp, vp, C.POINTER(i32), vp, sz, vp]),
     }
@@ -231,10 +231,10 @@ def rel_mae(a: torch.Tensor, b: torch.Tensor) -> torch.Tensor:
 
 def ddim_coefficients(steps: int, train_steps: int = 1000, beta_start: float = 1e-4, beta_end: float = 2e-2):
     ts = (C.c_int32 * steps)()
-    a = (C.c_float * steps)()
-    b = (C.c_float * steps)()
+    a = (C.c_double * steps)()
+    b = (C.c_double * steps)()
     _check(lib().ddim_coefficients(train_steps, beta_start, beta_end, steps, ts, a, b), "ddim_coefficients")
-    return (np.array(ts[:], dtype=np.int32), np.array(a[:], dtype=np.float32), np.array(b[:], dtype=np.float32))
+    return (np.array(ts[:], dtype=np.int32), np.array(a[:], dtype=np.float64), np.array(b[:], dtype=np.float64))
 
 
 # ------------------------------------------------------------------ reuse-then-predict
@@ -244,11 +244,11 @@ class Schedule:
     def __init__(self, timesteps, coef_a, coef_b, warmup: int, cycle_len: Sequence[int], batched: bool = False,
                  mode: int = 0):
         self.ts = np.ascontiguousarray(timesteps, dtype=np.int32)
-        self.a = np.ascontiguousarray(coef_a, dtype=np.float32)
-        self.b = np.ascontiguousarray(coef_b, dtype=np.float32)
+        self.a = np.ascontiguousarray(coef_a, dtype=np.float64)
+        self.b = np.ascontiguousarray(coef_b, dtype=np.float64)
         self.cyc = np.ascontiguousarray(cycle_len, dtype=np.int32)
         self.c = _Schedule(len(self.ts), self.ts.ctypes.data_as(C.POINTER(C.c_int32)),
-                           self.a.ctypes.data_as(C.POINTER(C.c_float)), self.b.ctypes.data_as(C.POINTER(C.c_float)),
+                           self.a.ctypes.data_as(C.POINTER(C.c_double)), self.b.ctypes.data_as(C.POINTER(C.c_double)),
                            int(warmup), len(self.cyc), self.cyc.ctypes.data_as(C.POINTER(C.c_int32)),
                            int(batched), int(mode))
 

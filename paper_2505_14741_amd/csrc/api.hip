@@ -359,7 +359,7 @@ int dit_linear(const void* a, const void* w, const float* bias, void* out, int m
 size_t sampler_step_workspace_bytes(size_t n) { return align256(reduce_workspace_bytes(n)); }
 size_t rel_mae_workspace_bytes(size_t n) { return align256(reduce_workspace_bytes(n)); }
 
-int sampler_step(const float* x, const float* eps, const float* eps_prev, float* x_out, float a, float b,
+int sampler_step(const float* x, const float* eps, const float* eps_prev, float* x_out, double a, double b,
                  size_t n, float* sums4, void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (!x || !eps || !x_out) return PS_ERR_NULL;
     if (!aligned(x, 16) || !aligned(eps, 16) || !aligned(x_out, 16) || (eps_prev && !aligned(eps_prev, 16)))
@@ -381,7 +381,7 @@ int rel_mae(const float* a, const float* b, size_t n, float* out3, void* workspa
 }
 
 int ddim_coefficients(int train_steps, double beta_start, double beta_end, int steps, int32_t* timesteps_out,
-                      float* a_out, float* b_out) {
+                      double* a_out, double* b_out) {
     if (!timesteps_out || !a_out || !b_out) return PS_ERR_NULL;
     if (train_steps < 2 || steps < 1 || steps > train_steps) return PS_ERR_SCHEDULE;
     if (!(beta_start > 0.0) || !(beta_end >= beta_start) || !(beta_end < 1.0)) return PS_ERR_SCHEDULE;
@@ -400,8 +400,8 @@ int ddim_coefficients(int train_steps, double beta_start, double beta_end, int s
         double a = std::sqrt(ab_p / ab_t);
         double b = std::sqrt(1.0 - ab_p) - a * std::sqrt(1.0 - ab_t);
         timesteps_out[i] = tau;
-        a_out[i] = (float)a;
-        b_out[i] = (float)b;
+        a_out[i] = a;
+        b_out[i] = b;
     }
     return PS_OK;
 }

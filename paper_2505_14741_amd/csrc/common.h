@@ -91,7 +91,7 @@ hipError_t launch_final_proj(int dtype, const float* X, const float* modf, const
 
 size_t reduce_workspace_bytes(size_t n);
 hipError_t launch_sampler_step(const float* x, const float* e, const float* e_prev, float* x_out,
-                               float a, float b, size_t n, float* sums4, void* ws, hipStream_t st);
+                               double a, double b, size_t n, float* sums4, void* ws, hipStream_t st);
 hipError_t launch_rel_mae(const float* a, const float* b, size_t n, float* out3, void* ws,
                           hipStream_t st);
 

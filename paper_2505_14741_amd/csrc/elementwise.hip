@@ -365,7 +365,7 @@ __device__ __forceinline__ void block_store_partials(double (&acc)[NS], double* 
 template <bool SUMS, bool PREV>
 __global__ void __launch_bounds__(RED_THREADS)
 sampler_step_kernel(const float* x, const float* __restrict__ e,
-                    const float* __restrict__ ep, float* xo, float a, float b,
+                    const float* __restrict__ ep, float* xo, float am1, float b,
                     size_t n, double* __restrict__ part) {
     float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
     double acc[4] = {0.0, 0.0, 0.0, 0.0};
@@ -378,12 +378,15 @@ sampler_step_kernel(const float* x, const float* __restrict__ e,
     int cnt = 0;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += stride) {
         float4 xv = x4[i], ev = e4[i];
-        float4 r;
-        r.x = a * xv.x + b * ev.x; r.y = a * xv.y + b * ev.y;
-        r.z = a * xv.z + b * ev.z; r.w = a * xv.w + b * ev.w;
+        // increment form: d = (a-1)x + b*eps, x' = x + d (a -> 1 near the end of a run, and the
+        // sum of |x' - x| must not come from a difference of rounded values)
+        float4 dl, r;
+        dl.x = am1 * xv.x + b * ev.x; dl.y = am1 * xv.y + b * ev.y;
+        dl.z = am1 * xv.z + b * ev.z; dl.w = am1 * xv.w + b * ev.w;
+        r.x = xv.x + dl.x; r.y = xv.y + dl.y; r.z = xv.z + dl.z; r.w = xv.w + dl.w;
         o4[i] = r;
         if constexpr (SUMS) {
-            s0 += (fabsf(r.x - xv.x) + fabsf(r.y - xv.y)) + (fabsf(r.z - xv.z) + fabsf(r.w - xv.w));
+            s0 += (fabsf(dl.x) + fabsf(dl.y)) + (fabsf(dl.z) + fabsf(dl.w));
             s1 += (fabsf(r.x) + fabsf(r.y)) + (fabsf(r.z) + fabsf(r.w));
             s3 += (fabsf(ev.x) + fabsf(ev.y)) + (fabsf(ev.z) + fabsf(ev.w));
             if constexpr (PREV) {
@@ -400,10 +403,11 @@ sampler_step_kernel(const float* x, const float* __restrict__ e,
     if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
         size_t i = nvec * 4 + threadIdx.x;
         float xv = x[i], ev = e[i];
-        float r = a * xv + b * ev;
+        float dl = am1 * xv + b * ev;
+        float r = xv + dl;
         xo[i] = r;
         if constexpr (SUMS) {
-            s0 += fabsf(r - xv); s1 += fabsf(r); s3 += fabsf(ev);
+            s0 += fabsf(dl); s1 += fabsf(r); s3 += fabsf(ev);
             if constexpr (PREV) s2 += fabsf(ev - ep[i]);
         }
     }
@@ -423,7 +427,7 @@ __global__ void finish_sums4_kernel(const double* __restrict__ part, int nblocks
 }
 
 hipError_t launch_sampler_step(const float* x, const float* e, const float* e_prev, float* x_out,
-                               float a, float b, size_t n, float* sums4, void* ws, hipStream_t st) {
+                               double a, double b, size_t n, float* sums4, void* ws, hipStream_t st) {
     if (n == 0) {
         if (sums4) {
             // nothing to reduce: the finishing kernel with zero blocks writes four zeros
@@ -433,12 +437,13 @@ hipError_t launch_sampler_step(const float* x, const float* e, const float* e_pr
     }
     int blocks = red_blocks(n);
     double* part = (double*)ws;
+    const float am1 = (float)(a - 1.0), bf = (float)b;
     if (!sums4)
-        sampler_step_kernel<false, false><<<blocks, RED_THREADS, 0, st>>>(x, e, nullptr, x_out, a, b, n, nullptr);
+        sampler_step_kernel<false, false><<<blocks, RED_THREADS, 0, st>>>(x, e, nullptr, x_out, am1, bf, n, nullptr);
     else if (e_prev)
-        sampler_step_kernel<true, true><<<blocks, RED_THREADS, 0, st>>>(x, e, e_prev, x_out, a, b, n, part);
+        sampler_step_kernel<true, true><<<blocks, RED_THREADS, 0, st>>>(x, e, e_prev, x_out, am1, bf, n, part);
     else
-        sampler_step_kernel<true, false><<<blocks, RED_THREADS, 0, st>>>(x, e, nullptr, x_out, a, b, n, part);
+        sampler_step_kernel<true, false><<<blocks, RED_THREADS, 0, st>>>(x, e, nullptr, x_out, am1, bf, n, part);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     if (sums4) finish_sums4_kernel<<<1, 64, 0, st>>>(part, blocks, sums4);

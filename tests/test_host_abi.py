@@ -39,13 +39,13 @@ def test_ddim_table_matches_oracle(S):
     ts, a, b = B.ddim_coefficients(S)
     tau, ao, bo = O.ddim_coefficients(steps=S)
     np.testing.assert_array_equal(ts, tau)
-    np.testing.assert_allclose(a, ao, rtol=1e-7)
-    np.testing.assert_allclose(b, bo, rtol=2e-7)
+    np.testing.assert_allclose(a, ao, rtol=1e-14)
+    np.testing.assert_allclose(b, bo, rtol=1e-12)
 
 
 def test_ddim_table_rejects_bad_arguments():
     L = B.lib()
-    ts = (C.c_int32 * 4)(); a = (C.c_float * 4)(); b = (C.c_float * 4)()
+    ts = (C.c_int32 * 4)(); a = (C.c_double * 4)(); b = (C.c_double * 4)()
     assert L.ddim_coefficients(1000, 1e-4, 2e-2, 4, None, a, b) == -1
     assert L.ddim_coefficients(1000, 1e-4, 2e-2, 0, ts, a, b) == -5
     assert L.ddim_coefficients(3, 1e-4, 2e-2, 4, ts, a, b) == -5
