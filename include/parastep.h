@@ -108,9 +108,10 @@ PS_API int dit_profile_read(dit* d, double* ms_out, int64_t* launches_out);
  * over all `seq` tokens (no mask, Section 1's "3D attention": one token axis holding
  * text tokens and the flattened frame/row/col grid).  q, k, v, o: DEVICE
  * [B, seq, heads, head_dim] contiguous in `dtype`, 16-byte aligned; o must not alias
- * the inputs.  seq >= 1, scale > 0, head_dim in {16, 32, 64}.
+ * the inputs.  seq >= 1, scale > 0, head_dim in {16, 32, 64}; rows past the end are never
+ * read, but V must be finite (masked keys multiply V by an exact 0).
  * workspace: DEVICE, 256-byte aligned, >= attn3d_workspace_bytes(...) (may be NULL when
- * that is 0); scratch only. */
+ * that is 0, which it currently always is); scratch only. */
 PS_API size_t attn3d_workspace_bytes(int batch, int seq, int heads, int head_dim, int dtype);
 PS_API int attn3d(const void* q, const void* k, const void* v, void* o,
            int batch, int seq, int heads, int head_dim, float scale, int dtype,
@@ -123,8 +124,9 @@ PS_API int attn3d(const void* q, const void* k, const void* v, void* o,
 PS_API int dit_linear(const void* a, const void* w, const float* bias, void* out, int m, int n_out, int k,
                int act, int dtype, void* hip_stream);
 
-/* Test hook: 0 = pick the fastest kernel for each shape (default), 1 = always use the
- * generic fp32-FMA kernels.  Process-wide; returns the previous value. */
+/* Test and tuning hook: 0 = pick the fastest kernel for each shape (default), 1 = always
+ * use the generic fp32-FMA kernels, 0x100|v = force tile variant v (1..4) of the bf16 MFMA
+ * GEMM.  Process-wide; returns the previous value. */
 PS_API int ps_set_kernel_path(int path);
 
 /* ------------------------------------------------------------- scheduler and metric

@@ -216,7 +216,7 @@ const char* ps_strerror(int status) {
 
 int ps_set_kernel_path(int path) {
     int old = get_kernel_path();
-    set_kernel_path(path ? 1 : 0);
+    set_kernel_path(path);
     return old;
 }
 

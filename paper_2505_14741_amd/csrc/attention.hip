@@ -7,9 +7,10 @@
 //    column: S^T = K Q^T puts the keys of one query into one lane's accumulator
 //    registers (row statistics need no cross-lane reduction beyond one 32-lane swap),
 //    and those registers, converted to bf16, are directly the B operand of
-//    O^T += V^T P^T.  V is consumed as V^T [head][d][key] so that its fragments, like
-//    K's, are contiguous 16/8-byte LDS reads; K/V^T tiles of 64 keys are double-buffered
-//    in LDS and shared by the 4 waves of a workgroup, each wave owning 64 queries.
+//    O^T += V^T P^T.  K and V tiles of 64 keys go from global memory straight into a
+//    three-stage LDS ring (global_load_lds_dwordx4), shared by the 4 waves of a
+//    workgroup, each wave owning 64 queries; V stays in its natural [key][d] layout and
+//    its transposed fragments come from ds_read_b64_tr_b16.
 #include "common.h"
 
 namespace ps {
@@ -97,50 +98,81 @@ static hipError_t launch_generic_attn(const T* q, const T* k, const T* v, T* o, 
 // --------------------------------------------------------------------------------- MFMA
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
-typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+typedef __attribute__((ext_vector_type(2))) int i32x2_t;
 
-// V [B, seq, H, 64] (strided) -> Vt [B*H][64][npad], keys beyond seq zero-filled.
-// One workgroup per (64-key tile, head, batch); transposes through LDS.
-__global__ void __launch_bounds__(256)
-transpose_v_kernel(const bf16_t* __restrict__ v, bf16_t* __restrict__ vt, int seq, int npad, int heads,
-                   long v_tok, long v_head, long v_batch) {
-    __shared__ unsigned short tile[64][66];
-    int b = blockIdx.z, h = blockIdx.y, k0 = blockIdx.x * 64;
-    const unsigned short* vp = reinterpret_cast<const unsigned short*>(v) + b * v_batch + h * v_head;
-    for (int e = threadIdx.x; e < 64 * 64; e += 256) {
-        int r = e >> 6, c = e & 63;                       // r: key, c: d
-        int kr = k0 + r;
-        tile[r][c] = kr < seq ? vp[(long)kr * v_tok + c] : (unsigned short)0;
-    }
-    __syncthreads();
-    unsigned short* op = reinterpret_cast<unsigned short*>(vt) + ((long)(b * heads + h) * 64) * npad + k0;
-    for (int e = threadIdx.x; e < 64 * 64; e += 256) {
-        int c = e >> 6, r = e & 63;                       // c: d row of Vt, r: key
-        op[(long)c * npad + r] = tile[r][c];
-    }
+#define PS_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+#define PS_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+
+// ds_read_b64_tr_b16: within each group of 16 lanes, lane i receives, for e = 0..3, the
+// 16-bit element (i%4) of the 8 bytes addressed by lane 4*e + i/4 of the same group.
+// All 16 transposed V reads of a 64-key tile are issued from one asm statement: through
+// the builtin the compiler cannot tell these reads from the in-flight global->LDS loads
+// of later tiles and would wait for those (vmcnt(0)) first.  The results are valid only
+// after lds_wait_v_frags().
+//   f[2*(2*st+dt)+0] : keys 16st + 4h + 0..3,  f[..+1] : keys 16st + 8 + 4h + 0..3
+//   a0 / a1: this lane's byte address for d tile 0 / 1 (key row and swizzled slot folded in)
+__device__ __forceinline__ void lds_issue_v_frags(i32x2_t (&f)[16], unsigned a0, unsigned a1) {
+    asm volatile(
+        "ds_read_b64_tr_b16 %0, %16 offset:0\n"
+        "ds_read_b64_tr_b16 %1, %16 offset:1024\n"
+        "ds_read_b64_tr_b16 %2, %17 offset:0\n"
+        "ds_read_b64_tr_b16 %3, %17 offset:1024\n"
+        "ds_read_b64_tr_b16 %4, %16 offset:2048\n"
+        "ds_read_b64_tr_b16 %5, %16 offset:3072\n"
+        "ds_read_b64_tr_b16 %6, %17 offset:2048\n"
+        "ds_read_b64_tr_b16 %7, %17 offset:3072\n"
+        "ds_read_b64_tr_b16 %8, %16 offset:4096\n"
+        "ds_read_b64_tr_b16 %9, %16 offset:5120\n"
+        "ds_read_b64_tr_b16 %10, %17 offset:4096\n"
+        "ds_read_b64_tr_b16 %11, %17 offset:5120\n"
+        "ds_read_b64_tr_b16 %12, %16 offset:6144\n"
+        "ds_read_b64_tr_b16 %13, %16 offset:7168\n"
+        "ds_read_b64_tr_b16 %14, %17 offset:6144\n"
+        "ds_read_b64_tr_b16 %15, %17 offset:7168\n"
+        : "=&v"(f[0]), "=&v"(f[1]), "=&v"(f[2]), "=&v"(f[3]), "=&v"(f[4]), "=&v"(f[5]), "=&v"(f[6]), "=&v"(f[7]),
+          "=&v"(f[8]), "=&v"(f[9]), "=&v"(f[10]), "=&v"(f[11]), "=&v"(f[12]), "=&v"(f[13]), "=&v"(f[14]),
+          "=&v"(f[15])
+        : "v"(a0), "v"(a1)
+        : "memory");
+}
+__device__ __forceinline__ void lds_wait_v_frags(i32x2_t (&f)[16]) {
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]), "+v"(f[4]), "+v"(f[5]), "+v"(f[6]), "+v"(f[7]),
+                   "+v"(f[8]), "+v"(f[9]), "+v"(f[10]), "+v"(f[11]), "+v"(f[12]), "+v"(f[13]), "+v"(f[14]),
+                   "+v"(f[15])
+                 :
+                 : "memory");
 }
 
-__device__ __forceinline__ int swz8(int row) { return row & 7; }
+// max over a query's keys held by lanes l and l^32
+__device__ __forceinline__ float max_across_halves(float v) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_int(v), __float_as_int(v), false, false);
+    return fmaxf(__int_as_float(r[0]), __int_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_across_halves(float v) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_int(v), __float_as_int(v), false, false);
+    return __int_as_float(r[0]) + __int_as_float(r[1]);
+}
 
 template <int QT>   // 32-query column tiles per wave
 __global__ void __launch_bounds__(256, 2)
-attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ vt,
-                 bf16_t* __restrict__ o, int seq, int npad, int heads, float scale_log2e,
-                 int qblocks, AttnStrides s) {
-    constexpr int HD = 64, KV = 64;
+attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
+                 bf16_t* __restrict__ o, int seq, int heads, float scale_log2e, int qblocks, AttnStrides s) {
+    constexpr int KV = 64;
     constexpr int BQ = 4 * QT * 32;
-    __shared__ __attribute__((aligned(16))) unsigned char lds[2][2][KV * 128];   // [buf][K|Vt]
+    constexpr int NST = 3;                       // LDS ring depth
+    constexpr int STAGE = 2 * KV * 128;          // K tile then V tile, 128-byte rows
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * STAGE];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, half = lane >> 5;
     // workgroup -> (batch*head, query block); consecutive ids of one XCD walk the query
-    // blocks of one head so that head's K/V^T stay in that XCD's L2
-    const int total = gridDim.x;
+    // blocks of one head so that head's K and V stay in that XCD's L2
     int id = blockIdx.x;
     {
-        int per = total / 8, rem = total % 8, x = id % 8, j = id / 8;
+        int total = gridDim.x, per = total / 8, rem = total % 8, x = id % 8, j = id / 8;
         id = x * per + (x < rem ? x : rem) + j;
     }
     const int bh = id / qblocks, qb = id % qblocks;
@@ -148,7 +180,7 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
     const int q0 = qb * BQ + wave * (QT * 32);
 
     const bf16_t* kbase = k + b * s.k_batch + h * s.k_head;
-    const bf16_t* vbase = vt + (long)bh * HD * npad;
+    const bf16_t* vbase = v + b * s.v_batch + h * s.v_head;
 
     // Q fragments (B operand of S^T = K Q^T): lane = query column, 8 consecutive d
     bf16x8_t qf[QT][4];
@@ -173,39 +205,51 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
 #pragma unroll
     for (int t = 0; t < QT; ++t) { mc[t] = -1e30f; lsum[t] = 0.f; }
 
-    // staging: thread -> chunk tid%8 of rows tid/8 and tid/8+32, for K and for Vt
-    const int lrow = tid >> 3, lchunk = tid & 7;
-    uint4 rk[2], rv[2];
-    auto load_tile = [&](int kv0) {
+    // direct global->LDS loads: a wave instruction fills 8 rows of 128 bytes; lane j brings
+    // chunk (j%8)^(j/8) of row j/8 (the XOR swizzle is applied on the global side).
+    // Per stage: 8 K groups + 8 V groups; wave w takes K groups w, w+4 and V groups w, w+4.
+    const int lr = lane >> 3, lc = (lane & 7) ^ lr;
+    auto issue = [&](int tile, int buf) {
+        unsigned char* st = lds + buf * STAGE;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            int kr = kv0 + lrow + 32 * i;
-            kr = kr < seq ? kr : seq - 1;
-            rk[i] = *reinterpret_cast<const uint4*>(kbase + (long)kr * s.k_tok + lchunk * 8);
-            rv[i] = *reinterpret_cast<const uint4*>(vbase + (long)(lrow + 32 * i) * npad + kv0 + lchunk * 8);
+            int g = wave + 4 * i;
+            int kr = tile * KV + g * 8 + lr;
+            kr = kr < seq ? kr : seq - 1;            // rows past the end re-read the last key (masked later)
+            __builtin_amdgcn_global_load_lds(PS_GLOBAL_PTR(kbase + (long)kr * s.k_tok + lc * 8),
+                                             PS_LDS_PTR(st + g * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(PS_GLOBAL_PTR(vbase + (long)kr * s.v_tok + lc * 8),
+                                             PS_LDS_PTR(st + KV * 128 + g * 1024), 16, 0, 0);
         }
     };
-    auto store_tile = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            int r = lrow + 32 * i;
-            int off = r * 128 + ((lchunk ^ swz8(r)) << 4);
-            *reinterpret_cast<uint4*>(&lds[buf][0][off]) = rk[i];
-            *reinterpret_cast<uint4*>(&lds[buf][1][off]) = rv[i];
-        }
-    };
+
+    // V^T fragment addressing for ds_read_b64_tr_b16 (see lds_read_tr16): lane l = 16g + j
+    // points at key row 4*(g/2) + j/4 (+16*step, +8 for the second half of a k16-step) and
+    // at d columns 16*(g%2) + 4*(j%4) .. +3 (+32 per d tile)
+    const int tg = lane >> 4, tj = lane & 15;
+    const int trow = 4 * (tg >> 1) + (tj >> 2);
+    const int tchunk = 2 * (tg & 1) + ((tj & 3) >> 1);
+    const int tsub = (tj & 1) * 8;
+    // rows 16*step (+8) keep trow's low 3 bits, so the swizzled slot is the same for every
+    // step; d tile 1 flips bit 2 of the slot
+    const unsigned lds_base = (unsigned)(size_t)PS_LDS_PTR(lds);
+    const unsigned voff0 = KV * 128 + trow * 128 + ((tchunk ^ (trow & 7)) << 4) + tsub;
+    const unsigned voff1 = KV * 128 + trow * 128 + (((4 + tchunk) ^ (trow & 7)) << 4) + tsub;
 
     const int ntiles = (seq + KV - 1) / KV;
-    load_tile(0);
-    store_tile(0);
-    __syncthreads();
-
+    issue(0, 0);
+    issue(1, 1);                                   // tiles past the end are harmless re-reads
+    int buf = 0;
     for (int j = 0; j < ntiles; ++j) {
-        const int buf = j & 1;
         const int kv0 = j * KV;
-        if (j + 1 < ntiles) load_tile(kv0 + KV);
-        const unsigned char* lk = &lds[buf][0][0];
-        const unsigned char* lv = &lds[buf][1][0];
+        // tile j has landed when at most the 4 loads of tile j+1 are still in flight
+        asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        __syncthreads();
+        {
+            int nb = buf + 2; nb = nb >= NST ? nb - NST : nb;
+            issue(j + 2, nb);
+        }
+        const unsigned char* lk = lds + buf * STAGE;
 
         // S^T[key tile rt][query tile t]
         f32x16_t sacc[2][QT];
@@ -220,12 +264,15 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
 #pragma unroll
             for (int rt = 0; rt < 2; ++rt) {
                 int r = rt * 32 + col;
-                bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(lk + r * 128 + (((ks * 2 + half) ^ swz8(r)) << 4));
+                bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(lk + r * 128 + (((ks * 2 + half) ^ (r & 7)) << 4));
 #pragma unroll
                 for (int t = 0; t < QT; ++t)
                     sacc[rt][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t][ks], sacc[rt][t], 0, 0, 0);
             }
         }
+        // V^T fragments: issued now, consumed after the softmax
+        i32x2_t vfr[16];
+        lds_issue_v_frags(vfr, lds_base + buf * STAGE + voff0, lds_base + buf * STAGE + voff1);
         // mask keys beyond the sequence (last tile only)
         if (kv0 + KV > seq) {
 #pragma unroll
@@ -248,7 +295,7 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
             for (int e = 1; e < 16; ++e) mx = fmaxf(mx, sacc[0][t][e]);
 #pragma unroll
             for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[1][t][e]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            mx = max_across_halves(mx);
             float mnew = fmaxf(mc[t], mx * scale_log2e);
             if (__any(mnew > mc[t])) {
                 float alpha = __builtin_amdgcn_exp2f(mc[t] - mnew);
@@ -276,31 +323,29 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
             }
             lsum[t] += rs;
         }
-        // O^T[d tile][query tile] += Vt[d tile][keys] P^T[keys][queries]
-        // k-slot (half, e) of step g in key tile rt is key 32rt + 16g + 8(e/4) + 4half + e%4
+        // O^T[d tile][query tile] += V^T[d tile][keys] P^T[keys][queries]
+        // k-slot (half, e) of step st is key 16st + 8(e/4) + 4half + e%4
+        lds_wait_v_frags(vfr);
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
 #pragma unroll
             for (int dt = 0; dt < 2; ++dt) {
-                int r = dt * 32 + col;
-                const unsigned char* rowp = lv + r * 128;
-                int c0 = (st * 2) ^ swz8(r), c1 = (st * 2 + 1) ^ swz8(r);
-                bf16x4_t lo = *reinterpret_cast<const bf16x4_t*>(rowp + (c0 << 4) + half * 8);
-                bf16x4_t hi = *reinterpret_cast<const bf16x4_t*>(rowp + (c1 << 4) + half * 8);
+                bf16x4_t lo = __builtin_bit_cast(bf16x4_t, vfr[2 * (2 * st + dt)]);
+                bf16x4_t hi = __builtin_bit_cast(bf16x4_t, vfr[2 * (2 * st + dt) + 1]);
                 bf16x8_t vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
                 for (int t = 0; t < QT; ++t)
                     oacc[dt][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[t][st], oacc[dt][t], 0, 0, 0);
             }
         }
-        if (j + 1 < ntiles) store_tile(buf ^ 1);
-        __syncthreads();
+        buf = buf + 1 == NST ? 0 : buf + 1;
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // drain the look-ahead loads before exit
 
     // finish: total row sum = both halves; O[query][d] = O^T / l
 #pragma unroll
     for (int t = 0; t < QT; ++t) {
-        float l = lsum[t] + __shfl_xor(lsum[t], 32, 64);
+        float l = sum_across_halves(lsum[t]);
         float inv = 1.0f / l;
         int qi = q0 + t * 32 + col;
         if (qi < seq) {
@@ -319,27 +364,21 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
 }
 
 size_t attention_workspace_bytes(int dtype, int batch, int seq, int heads, int head_dim) {
-    if (dtype != PS_BF16 || head_dim != 64) return 0;
-    size_t npad = ((size_t)seq + 63) / 64 * 64;
-    return (size_t)batch * heads * 64 * npad * sizeof(bf16_t);
+    (void)dtype; (void)batch; (void)seq; (void)heads; (void)head_dim;
+    return 0;
 }
 
 hipError_t launch_attention(int dtype, const void* q, const void* k, const void* v, void* o,
                             int batch, int seq, int heads, int head_dim, float scale,
                             const AttnStrides& s, void* ws, hipStream_t st) {
-    if (dtype == PS_BF16 && head_dim == 64 && get_kernel_path() == 0 && ws != nullptr) {
-        int npad = (seq + 63) / 64 * 64;
-        bf16_t* vt = (bf16_t*)ws;
-        dim3 tg(npad / 64, heads, batch);
-        transpose_v_kernel<<<tg, 256, 0, st>>>((const bf16_t*)v, vt, seq, npad, heads, s.v_tok, s.v_head, s.v_batch);
-        hipError_t err = hipGetLastError();
-        if (err != hipSuccess) return err;
+    (void)ws;
+    if (dtype == PS_BF16 && head_dim == 64 && get_kernel_path() != 1) {
         constexpr int QT = 2;
         constexpr int BQ = 4 * QT * 32;
         int qblocks = (seq + BQ - 1) / BQ;
         dim3 grid(qblocks * heads * batch);
-        attn_mfma_kernel<QT><<<grid, 256, 0, st>>>((const bf16_t*)q, (const bf16_t*)k, vt, (bf16_t*)o, seq, npad,
-                                                   heads, scale * 1.4426950408889634f, qblocks, s);
+        attn_mfma_kernel<QT><<<grid, 256, 0, st>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o,
+                                                   seq, heads, scale * 1.4426950408889634f, qblocks, s);
         return hipGetLastError();
     }
     if (dtype == PS_BF16)

@@ -1,5 +1,6 @@
 // GEMM epilogues applied to a pair of adjacent output columns (col even), so that the
-// interleaved rotary pairs (2m, 2m+1) of a head are handled by one thread.
+// interleaved rotary pairs (2m, 2m+1) of a head are handled by one thread.  v0, v1 already
+// include the bias.
 #pragma once
 #include "common.h"
 
@@ -8,8 +9,6 @@ namespace ps {
 template <int KIND, typename T>
 __device__ __forceinline__ void epilogue_pair(const Epilogue& ep, T* __restrict__ C, int Nn, int m,
                                               int col, float v0, float v1) {
-    v0 += ep.bias[col];
-    v1 += ep.bias[col + 1];
     if constexpr (KIND == EPI_BIAS_GELU) {
         v0 = gelu_tanh_f(v0);
         v1 = gelu_tanh_f(v1);
@@ -46,6 +45,12 @@ __device__ __forceinline__ void epilogue_pair(const Epilogue& ep, T* __restrict_
     } else {
         *reinterpret_cast<float2*>(C + (long)m * Nn + col) = make_float2(v0, v1);
     }
+}
+
+// swap a value between lanes 2i and 2i+1 (DPP quad_perm [1,0,3,2])
+__device__ __forceinline__ float swap_adjacent_lanes(float v) {
+    int r = __builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, false);
+    return __int_as_float(r);
 }
 
 }  // namespace ps

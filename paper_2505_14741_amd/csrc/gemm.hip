@@ -6,8 +6,12 @@
 
 namespace ps {
 
-static int g_kernel_path = 0;   // 0 auto, 1 force the generic kernels
-void set_kernel_path(int p) { g_kernel_path = p; }
+void set_gemm_variant(int v);
+static int g_kernel_path = 0;   // 0 auto, 1 force the generic kernels, 0x100|v force MFMA GEMM tile variant v
+void set_kernel_path(int p) {
+    g_kernel_path = p;
+    set_gemm_variant((p & 0x100) ? (p & 0xff) : 0);
+}
 int get_kernel_path() { return g_kernel_path; }
 
 // 64x64 output tile, 16-deep K slices, 256 threads, 4x4 outputs per thread.
@@ -57,7 +61,8 @@ gemm_generic_kernel(const T* __restrict__ A, const T* __restrict__ W, T* __restr
 #pragma unroll
         for (int j = 0; j < 4; j += 2) {
             int col = n0 + tx * 4 + j;
-            if (col < Nn) epilogue_pair<KIND, T>(ep, C, Nn, m, col, acc[i][j], acc[i][j + 1]);
+            if (col < Nn)
+                epilogue_pair<KIND, T>(ep, C, Nn, m, col, acc[i][j] + ep.bias[col], acc[i][j + 1] + ep.bias[col + 1]);
         }
     }
 }
@@ -85,7 +90,7 @@ hipError_t launch_gemm(int dtype, const void* A, const void* W, void* C, int M, 
                        const Epilogue& epi, hipStream_t st) {
     if (M <= 0 || Nn <= 0 || K <= 0 || (Nn & 1)) return hipErrorInvalidValue;
     if (dtype == PS_BF16) {
-        if (g_kernel_path == 0 && gemm_mfma_supported(M, Nn, K))
+        if (g_kernel_path != 1 && gemm_mfma_supported(M, Nn, K))
             return launch_gemm_mfma((const bf16_t*)A, (const bf16_t*)W, (bf16_t*)C, M, Nn, K, epi, st);
         return launch_generic<bf16_t>((const bf16_t*)A, (const bf16_t*)W, (bf16_t*)C, M, Nn, K, epi, st);
     }
