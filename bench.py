@@ -80,6 +80,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="full", choices=["full", "long", "block"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kernel-path", type=lambda v: int(v, 0), default=0, help="tuning hook passed to ps_set_kernel_path")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives are built); use --gpus 1")
@@ -91,6 +92,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     B.lib()
     torch.cuda.set_device(0)
+    B.ps_set_kernel_path(args.kernel_path)
     cfg = I.CONFIGS[args.workload]
     N, D = cfg.tokens, cfg.hidden
     K, Wm = args.steps, args.warmup

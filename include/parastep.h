@@ -125,8 +125,9 @@ PS_API int dit_linear(const void* a, const void* w, const float* bias, void* out
                int act, int dtype, void* hip_stream);
 
 /* Test and tuning hook: 0 = pick the fastest kernel for each shape (default), 1 = always
- * use the generic fp32-FMA kernels, 0x100|v = force tile variant v (1..4) of the bf16 MFMA
- * GEMM.  Process-wide; returns the previous value. */
+ * use the generic fp32-FMA kernels, 2 = software-pipelined variant of the bf16 attention
+ * kernel, 0x100|v = force tile variant v (1..4) of the bf16 MFMA GEMM.  Process-wide;
+ * returns the previous value. */
 PS_API int ps_set_kernel_path(int path);
 
 /* ------------------------------------------------------------- scheduler and metric

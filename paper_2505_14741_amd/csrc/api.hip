@@ -163,6 +163,9 @@ int forward_impl(dit* d, const float* x, const void* ctx, const int32_t* t_host,
     as.q_batch = as.k_batch = as.v_batch = (long)N * 3 * D;
     as.o_tok = D; as.o_head = c.head_dim; as.o_batch = (long)N * D;
     const float scale = 1.0f / sqrtf((float)c.head_dim);
+    // the MFMA attention kernel takes queries that already carry scale*log2(e); the QKV
+    // projection applies the factor in fp32, before its single rounding to bf16
+    const bool prescale = attention_uses_mfma(dt, c.head_dim);
 
     for (int l = 0; l < L; ++l) {
         const LayerW& lw = d->layers[l];
@@ -173,11 +176,12 @@ int forward_impl(dit* d, const float* x, const void* ctx, const int32_t* t_host,
         Epilogue eq{};
         eq.kind = EPI_QKV_ROPE; eq.bias = lw.b_qkv; eq.D = D; eq.geom = geom;
         eq.rope_cos = rcos; eq.rope_sin = rsin; eq.head_dim = c.head_dim;
+        eq.q_scale = prescale ? scale * 1.4426950408889634f : 1.0f;
         PS_TIMED(KC_QKV, launch_gemm(dt, Hb, lw.W_qkv, QKV, M, 3 * D, D, eq, st));
         // o = attention(q, k, v) -> Hb (token-major, heads concatenated)
         const char* qp = (const char*)QKV;
         PS_TIMED(KC_ATTN, launch_attention(dt, qp, qp + (size_t)D * es, qp + (size_t)2 * D * es, Hb, batch, N,
-                                           c.heads, c.head_dim, scale, as, attn_ws, st));
+                                           c.heads, c.head_dim, scale, as, attn_ws, st, prescale));
         // X += gate_a * (W_o o + b_o)
         Epilogue eo{};
         eo.kind = EPI_GATE_RESIDUAL; eo.bias = lw.b_o; eo.resid = X; eo.mod_layer = mod_l;

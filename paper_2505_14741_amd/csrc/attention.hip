@@ -146,6 +146,11 @@ __device__ __forceinline__ void lds_wait_v_frags(i32x2_t (&f)[16]) {
                  : "memory");
 }
 
+__device__ __forceinline__ bf16x4_t lds_read_tr16(const unsigned char* p) {
+    s16x4_t v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(p));
+    return __builtin_bit_cast(bf16x4_t, v);
+}
+
 // max over a query's keys held by lanes l and l^32
 __device__ __forceinline__ float max_across_halves(float v) {
     auto r = __builtin_amdgcn_permlane32_swap(__float_as_int(v), __float_as_int(v), false, false);
@@ -156,7 +161,31 @@ __device__ __forceinline__ float sum_across_halves(float v) {
     return __int_as_float(r[0]) + __int_as_float(r[1]);
 }
 
-template <int QT>   // 32-query column tiles per wave
+// Softmax bookkeeping.  Every query keeps a reference value r (bf16-representable) and the
+// kernel accumulates sum_j 2^(c(s_j - r)) v_j and sum_j 2^(c(s_j - r)); any r gives the same
+// quotient, so r is only moved when it has to be:
+//  * the subtraction s - r costs no vector instruction: a fifth k16-step of the QK^T MFMA
+//    multiplies a constant "1" slot of the K operand with -r stored in the Q operand;
+//  * a tile goes through the fast path -- exp2, pack to bf16, row sum with v_dot2c on the
+//    packed pairs -- without looking for its maximum; the partial row sums tell whether any
+//    2^(c(s - r)) was large (>= 2^16) or overflowed, and only then (and on the first and
+//    on a ragged last tile) the tile is redone through the exact path: true row maximum,
+//    new r, rescale of the running sums.
+// PRESCALED: q already carries the factor c = scale*log2(e) (the QKV projection applies it
+// in fp32 before rounding), so p = exp2(acc) with no multiply; otherwise p = exp2(c*acc).
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+// acc + sum of eight bf16 values (v_dot2c_f32_bf16 against packed ones)
+__device__ __forceinline__ float rowsum_bf16x8(bf16x8_t p, float acc) {
+    bf16x2_t ones;
+    ones[0] = (__bf16)1.0f; ones[1] = (__bf16)1.0f;
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(p, p, 0, 1), ones, acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(p, p, 2, 3), ones, acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(p, p, 4, 5), ones, acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(p, p, 6, 7), ones, acc, false);
+    return acc;
+}
+
+template <int QT, bool PRESCALED>   // QT: 32-query column tiles per wave
 __global__ void __launch_bounds__(256, 2)
 attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
                  bf16_t* __restrict__ o, int seq, int heads, float scale_log2e, int qblocks, AttnStrides s) {
@@ -201,14 +230,27 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
         for (int t = 0; t < QT; ++t)
 #pragma unroll
             for (int e = 0; e < 16; ++e) oacc[d][t][e] = 0.f;
-    float mc[QT], lsum[QT];
+    float mref[QT], lsum[QT];
+    bf16x8_t qx[QT];                 // Q operand of the reference step: slot (half 0, e 0) = -r
+    bf16x8_t kone;                   // K operand of the reference step: slot (half 0, e 0) = 1
 #pragma unroll
-    for (int t = 0; t < QT; ++t) { mc[t] = -1e30f; lsum[t] = 0.f; }
+    for (int e = 0; e < 8; ++e) kone[e] = (__bf16)((e == 0 && half == 0) ? 1.0f : 0.0f);
+#pragma unroll
+    for (int t = 0; t < QT; ++t) {
+        mref[t] = 0.f; lsum[t] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qx[t][e] = (__bf16)0.0f;
+    }
+    const float cexp = PRESCALED ? 1.0f : scale_log2e;
 
-    // direct global->LDS loads: a wave instruction fills 8 rows of 128 bytes; lane j brings
-    // chunk (j%8)^(j/8) of row j/8 (the XOR swizzle is applied on the global side).
+    // direct global->LDS loads: a wave instruction fills 8 rows of 128 bytes (lane j lands
+    // at base + 16j), so the XOR swizzles are applied on the global side.  LDS has 64
+    // four-byte banks.  K fragments are 16-byte reads of 16 consecutive rows per cycle:
+    // slot p of row r holds chunk p ^ ((r>>1)&7).  V fragments are transposing 8-byte
+    // reads that touch 8 consecutive rows x 64 bytes: slot p of row r holds chunk p ^ (r&7).
     // Per stage: 8 K groups + 8 V groups; wave w takes K groups w, w+4 and V groups w, w+4.
-    const int lr = lane >> 3, lc = (lane & 7) ^ lr;
+    const int lr = lane >> 3;
+    const int lc_v = (lane & 7) ^ lr;
     auto issue = [&](int tile, int buf) {
         unsigned char* st = lds + buf * STAGE;
 #pragma unroll
@@ -216,9 +258,10 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
             int g = wave + 4 * i;
             int kr = tile * KV + g * 8 + lr;
             kr = kr < seq ? kr : seq - 1;            // rows past the end re-read the last key (masked later)
-            __builtin_amdgcn_global_load_lds(PS_GLOBAL_PTR(kbase + (long)kr * s.k_tok + lc * 8),
+            const int lc_k = (lane & 7) ^ (((g & 1) << 2) | (lane >> 4));
+            __builtin_amdgcn_global_load_lds(PS_GLOBAL_PTR(kbase + (long)kr * s.k_tok + lc_k * 8),
                                              PS_LDS_PTR(st + g * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds(PS_GLOBAL_PTR(vbase + (long)kr * s.v_tok + lc * 8),
+            __builtin_amdgcn_global_load_lds(PS_GLOBAL_PTR(vbase + (long)kr * s.v_tok + lc_v * 8),
                                              PS_LDS_PTR(st + KV * 128 + g * 1024), 16, 0, 0);
         }
     };
@@ -251,77 +294,121 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
         }
         const unsigned char* lk = lds + buf * STAGE;
 
-        // S^T[key tile rt][query tile t]
+        // S^T[key tile rt][query tile t] - r, as a function: the exact path recomputes it rather
+        // than keeping 64 accumulator registers alive across the fast path
         f32x16_t sacc[2][QT];
-#pragma unroll
-        for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-            for (int t = 0; t < QT; ++t)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) sacc[rt][t][e] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-#pragma unroll
-            for (int rt = 0; rt < 2; ++rt) {
-                int r = rt * 32 + col;
-                bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(lk + r * 128 + (((ks * 2 + half) ^ (r & 7)) << 4));
-#pragma unroll
-                for (int t = 0; t < QT; ++t)
-                    sacc[rt][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t][ks], sacc[rt][t], 0, 0, 0);
-            }
-        }
-        // V^T fragments: issued now, consumed after the softmax
-        i32x2_t vfr[16];
-        lds_issue_v_frags(vfr, lds_base + buf * STAGE + voff0, lds_base + buf * STAGE + voff1);
-        // mask keys beyond the sequence (last tile only)
-        if (kv0 + KV > seq) {
+        auto scores = [&]() {
 #pragma unroll
             for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    int key = kv0 + rt * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
-                    if (key >= seq) {
+                for (int t = 0; t < QT; ++t)
 #pragma unroll
-                        for (int t = 0; t < QT; ++t) sacc[rt][t][e] = -INFINITY;
-                    }
+                    for (int e = 0; e < 16; ++e) sacc[rt][t][e] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+#pragma unroll
+                for (int rt = 0; rt < 2; ++rt) {
+                    int r = rt * 32 + col;
+                    bf16x8_t kf =
+                        *reinterpret_cast<const bf16x8_t*>(lk + r * 128 + (((ks * 2 + half) ^ ((r >> 1) & 7)) << 4));
+#pragma unroll
+                    for (int t = 0; t < QT; ++t)
+                        sacc[rt][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t][ks], sacc[rt][t], 0, 0, 0);
                 }
-        }
-        // online softmax, per query column
+            }
+            // reference step: sacc -= r (per query column)
+#pragma unroll
+            for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+                for (int t = 0; t < QT; ++t)
+                    sacc[rt][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kone, qx[t], sacc[rt][t], 0, 0, 0);
+        };
+        // V^T fragments: issued now, consumed after the softmax
+        i32x2_t vfr[16];
+        lds_issue_v_frags(vfr, lds_base + buf * STAGE + voff0, lds_base + buf * STAGE + voff1);
         bf16x8_t pf[QT][4];
+        const bool ragged = kv0 + KV > seq;
+        bool redo = (j == 0) || ragged;
+        if (!redo) {
+            scores();
+            // fast path: p = 2^(c (s - r)) without a maximum
+            float rsv[QT];
 #pragma unroll
-        for (int t = 0; t < QT; ++t) {
-            float mx = sacc[0][t][0];
+            for (int t = 0; t < QT; ++t) {
+                float rs = 0.f;
 #pragma unroll
-            for (int e = 1; e < 16; ++e) mx = fmaxf(mx, sacc[0][t][e]);
+                for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[1][t][e]);
-            mx = max_across_halves(mx);
-            float mnew = fmaxf(mc[t], mx * scale_log2e);
-            if (__any(mnew > mc[t])) {
-                float alpha = __builtin_amdgcn_exp2f(mc[t] - mnew);
-                lsum[t] *= alpha;
+                    for (int g = 0; g < 2; ++g) {      // k16-step inside the 32-key tile
+                        bf16x8_t pk;
 #pragma unroll
-                for (int d = 0; d < 2; ++d)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) oacc[d][t][e] *= alpha;
-                mc[t] = mnew;
-            }
-            float rs = 0.f;
-#pragma unroll
-            for (int rt = 0; rt < 2; ++rt) {
-#pragma unroll
-                for (int g = 0; g < 2; ++g) {      // k16-step inside the 32-key tile
-                    bf16x8_t pk;
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        float p = __builtin_amdgcn_exp2f(sacc[rt][t][g * 8 + e] * scale_log2e - mc[t]);
-                        rs += p;
-                        pk[e] = (__bf16)p;
+                        for (int e = 0; e < 8; ++e) {
+                            float a = sacc[rt][t][g * 8 + e];
+                            pk[e] = (__bf16)__builtin_amdgcn_exp2f(PRESCALED ? a : a * cexp);
+                        }
+                        pf[t][rt * 2 + g] = pk;
+                        rs = rowsum_bf16x8(pk, rs);
                     }
-                    pf[t][rt * 2 + g] = pk;
-                }
+                // large or non-finite partial sum: some exponent was far above the reference
+                redo = redo || !(rs < 65536.0f);
+                rsv[t] = rs;
             }
-            lsum[t] += rs;
+            redo = __any(redo);
+            if (!redo) {
+#pragma unroll
+                for (int t = 0; t < QT; ++t) lsum[t] += rsv[t];
+            }
+        }
+        if (redo) {
+            scores();
+            if (ragged) {
+#pragma unroll
+                for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        int key = kv0 + rt * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
+                        if (key >= seq) {
+#pragma unroll
+                            for (int t = 0; t < QT; ++t) sacc[rt][t][e] = -INFINITY;
+                        }
+                    }
+            }
+#pragma unroll
+            for (int t = 0; t < QT; ++t) {
+                // exact path: sacc holds s - r_old; move the reference to the row maximum
+                float mx = sacc[0][t][0];
+#pragma unroll
+                for (int e = 1; e < 16; ++e) mx = fmaxf(mx, sacc[0][t][e]);
+#pragma unroll
+                for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[1][t][e]);
+                mx = max_across_halves(mx);                       // finite: every tile has a valid key
+                if (j > 0) mx = fmaxf(mx, 0.f);                   // the reference never moves down
+                const float rnew = (float)(__bf16)(mref[t] + mx); // new reference, bf16-representable
+                const float d = rnew - mref[t];
+                if (j > 0) {
+                    const float alpha = __builtin_amdgcn_exp2f(-d * cexp);
+                    lsum[t] *= alpha;
+#pragma unroll
+                    for (int dd = 0; dd < 2; ++dd)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) oacc[dd][t][e] *= alpha;
+                }
+                mref[t] = rnew;
+                qx[t][0] = (__bf16)(half == 0 ? -rnew : 0.0f);
+                float rs = 0.f;
+#pragma unroll
+                for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+                    for (int g = 0; g < 2; ++g) {
+                        bf16x8_t pk;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            pk[e] = (__bf16)__builtin_amdgcn_exp2f((sacc[rt][t][g * 8 + e] - d) * cexp);
+                        pf[t][rt * 2 + g] = pk;
+                        rs = rowsum_bf16x8(pk, rs);
+                    }
+                lsum[t] += rs;
+            }
         }
         // O^T[d tile][query tile] += V^T[d tile][keys] P^T[keys][queries]
         // k-slot (half, e) of step st is key 16st + 8(e/4) + 4half + e%4
@@ -363,24 +450,311 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
     }
 }
 
+// ------------------------------------------------------------ software-pipelined variant
+// Same mathematics as attn_mfma_kernel, restructured so that the matrix and vector work of
+// one wave are independent inside a loop body and the scheduler can interleave them.
+// The unit of work is (32-key sub-tile u, 32-query tile t); units are visited in the order
+// (u,0), (u,1), (u+1,0), ... and body w does
+//     PV(w)   O^T[.][t] += V^T(u) P^T(w)      (MFMA, P from the previous body)
+//     SM(w+1) P(w+1) = 2^(S(w+1) - r)          (vector: exp2, pack, row sum)
+//     QK(w+2) S(w+2) = K Q^T - r               (MFMA, consumed by the next body)
+// Units w and w+2 have the same t, so the score and probability registers of the two query
+// tiles are exactly the two pipeline slots.  The exponentials of one unit run under the
+// matrix instructions of its neighbours.
+// LDS stages hold 64 keys (two sub-tiles); a stage iteration (4 bodies) reads V of stage s
+// and K of stages s and s+1, so the ring has four stages and stage s+3 is requested while s
+// is consumed.  Global->LDS loads are issued from inline asm (the compiler then schedules
+// every LDS read, including the transposing ones, without waiting for loads in flight);
+// vmcnt waits and barriers below make each stage visible before it is read.
+// The reference r of a query moves only through the exact path (first sub-tile, a unit
+// whose row sums reveal a large exponent, and the careful tail).  Units of one query tile
+// are two bodies apart, so no look-ahead score ever has to be patched.
+__device__ __forceinline__ void lds_dma16(const void* gptr, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr)
+                 : "memory", "m0");
+}
+
+template <bool PRESCALED>
+__global__ void __launch_bounds__(256, 2)
+attn_mfma_pipe_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
+                      bf16_t* __restrict__ o, int seq, int heads, float scale_log2e, int qblocks, AttnStrides s) {
+    constexpr int QT = 2;
+    constexpr int KV = 64;                       // keys per LDS stage
+    constexpr int BQ = 4 * QT * 32;
+    constexpr int NST = 4;
+    constexpr int STAGE = 2 * KV * 128;
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * STAGE];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int col = lane & 31, half = lane >> 5;
+    int id = blockIdx.x;
+    {
+        int total = gridDim.x, per = total / 8, rem = total % 8, x = id % 8, j = id / 8;
+        id = x * per + (x < rem ? x : rem) + j;
+    }
+    const int bh = id / qblocks, qb = id % qblocks;
+    const int b = bh / heads, h = bh % heads;
+    const int q0 = qb * BQ + wave * (QT * 32);
+    const bf16_t* kbase = k + b * s.k_batch + h * s.k_head;
+    const bf16_t* vbase = v + b * s.v_batch + h * s.v_head;
+
+    bf16x8_t qf[QT][4];
+#pragma unroll
+    for (int t = 0; t < QT; ++t) {
+        int qi = q0 + t * 32 + col;
+        qi = qi < seq ? qi : seq - 1;
+        const bf16_t* qp = q + b * s.q_batch + (long)qi * s.q_tok + h * s.q_head;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+            qf[t][ks] = *reinterpret_cast<const bf16x8_t*>(qp + ks * 16 + half * 8);
+    }
+    f32x16_t oacc[2][QT];
+#pragma unroll
+    for (int d = 0; d < 2; ++d)
+#pragma unroll
+        for (int t = 0; t < QT; ++t)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) oacc[d][t][e] = 0.f;
+    float mref[QT], lsum[QT];
+    bf16x8_t qx[QT], kone;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) kone[e] = (__bf16)((e == 0 && half == 0) ? 1.0f : 0.0f);
+#pragma unroll
+    for (int t = 0; t < QT; ++t) {
+        mref[t] = 0.f; lsum[t] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qx[t][e] = (__bf16)0.0f;
+    }
+    const float cexp = PRESCALED ? 1.0f : scale_log2e;
+
+    // ---- staging (same layout and swizzles as attn_mfma_kernel)
+    const unsigned lds_base = (unsigned)(size_t)PS_LDS_PTR(lds);
+    const int lr = lane >> 3;
+    const int lc_v = (lane & 7) ^ lr;
+    auto issue = [&](int stage) {
+        const unsigned st = lds_base + (stage % NST) * STAGE;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            int g = wave + 4 * i;
+            int kr = stage * KV + g * 8 + lr;
+            kr = kr < seq ? kr : seq - 1;
+            const int lc_k = (lane & 7) ^ (((g & 1) << 2) | (lane >> 4));
+            lds_dma16(kbase + (long)kr * s.k_tok + lc_k * 8, __builtin_amdgcn_readfirstlane(st + g * 1024));
+            lds_dma16(vbase + (long)kr * s.v_tok + lc_v * 8, __builtin_amdgcn_readfirstlane(st + KV * 128 + g * 1024));
+        }
+    };
+    const int tg = lane >> 4, tj = lane & 15;
+    const int trow = 4 * (tg >> 1) + (tj >> 2);
+    const int tchunk = 2 * (tg & 1) + ((tj & 3) >> 1);
+    const int tsub = (tj & 1) * 8;
+    const int voff0 = KV * 128 + trow * 128 + ((tchunk ^ (trow & 7)) << 4) + tsub;
+    const int voff1 = KV * 128 + trow * 128 + (((4 + tchunk) ^ (trow & 7)) << 4) + tsub;
+    const int koff = col * 128;
+    const int ksw = (col >> 1) & 7;
+
+    f32x16_t sS[QT];                 // scores of the unit in flight for each query tile
+    bf16x8_t pP[QT][2];              // its probabilities (two k16-steps)
+
+    // ---- building blocks; t is a literal at every call site
+    auto qk = [&](int u, int t) {
+        const unsigned char* lk = lds + ((u >> 1) % NST) * STAGE + (u & 1) * 4096 + koff;
+        f32x16_t acc;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(lk + (((ks * 2 + half) ^ ksw) << 4));
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t][ks], acc, 0, 0, 0);
+        }
+        sS[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kone, qx[t], acc, 0, 0, 0);
+    };
+    auto pv = [&](int u, int t) {
+        const unsigned char* lv = lds + ((u >> 1) % NST) * STAGE + (u & 1) * 4096;
+#pragma unroll
+        for (int g = 0; g < 2; ++g)
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt) {
+                const unsigned char* pa = lv + (dt ? voff1 : voff0) + g * 2048;
+                bf16x4_t lo = lds_read_tr16(pa);
+                bf16x4_t hi = lds_read_tr16(pa + 1024);
+                bf16x8_t vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                oacc[dt][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pP[t][g], oacc[dt][t], 0, 0, 0);
+            }
+    };
+    // fast path: no maximum; returns the partial row sum (checked by the caller)
+    auto sm_fast = [&](int t) -> float {
+        float rs = 0.f;
+#pragma unroll
+        for (int g = 0; g < 2; ++g) {
+            bf16x8_t pk;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float a = sS[t][g * 8 + e];
+                pk[e] = (__bf16)__builtin_amdgcn_exp2f(PRESCALED ? a : a * cexp);
+            }
+            pP[t][g] = pk;
+            rs = rowsum_bf16x8(pk, rs);
+        }
+        return rs;
+    };
+    // exact path on sS[t] (= s - r_old for `valid` keys): moves r to the row maximum (never
+    // down once something has been accumulated) and rescales the running sums of tile t
+    auto sm_exact = [&](int t, int valid, bool first, bool make_p) {
+        if (valid < 32) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                int key = 8 * (e >> 2) + 4 * half + (e & 3);
+                if (key >= valid) sS[t][e] = -INFINITY;
+            }
+        }
+        float mx = sS[t][0];
+#pragma unroll
+        for (int e = 1; e < 16; ++e) mx = fmaxf(mx, sS[t][e]);
+        mx = max_across_halves(mx);                        // finite: the sub-tile has a valid key
+        if (!first) mx = fmaxf(mx, 0.f);
+        const float rnew = (float)(__bf16)(mref[t] + mx);
+        const float d = rnew - mref[t];
+        if (!first) {
+            const float alpha = __builtin_amdgcn_exp2f(-d * cexp);
+            lsum[t] *= alpha;
+#pragma unroll
+            for (int dd = 0; dd < 2; ++dd)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) oacc[dd][t][e] *= alpha;
+        }
+        mref[t] = rnew;
+        qx[t][0] = (__bf16)(half == 0 ? -rnew : 0.0f);
+        if (make_p) {
+            float rs = 0.f;
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {
+                bf16x8_t pk;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) pk[e] = (__bf16)__builtin_amdgcn_exp2f((sS[t][g * 8 + e] - d) * cexp);
+                pP[t][g] = pk;
+                rs = rowsum_bf16x8(pk, rs);
+            }
+            lsum[t] += rs;
+        } else {
+            // only re-base the scores; a later fast pass turns them into probabilities
+#pragma unroll
+            for (int e = 0; e < 16; ++e) sS[t][e] -= d;
+        }
+    };
+    // one pipeline body: PV(up, t) | SM(us, 1-t) | QK(uq, t)
+    auto body = [&](int up, int us, int uq, int t) {
+        pv(up, t);
+        const float rs = sm_fast(1 - t);
+        qk(uq, t);
+        if (__any(!(rs < 65536.0f))) {          // large or non-finite: redo that unit exactly
+            qk(us, 1 - t);
+            sm_exact(1 - t, 32, false, true);
+        } else {
+            lsum[1 - t] += rs;
+        }
+    };
+
+    const int U = (seq + 31) / 32;               // sub-tiles with at least one key
+    const int Ufull = seq / 32;                  // complete sub-tiles
+
+    issue(0); issue(1); issue(2);
+    asm volatile("s_waitcnt vmcnt(4)" ::: "memory");     // stages 0 and 1 landed
+    __syncthreads();
+    issue(3);
+    qk(0, 0);
+    qk(0, 1);
+    sm_exact(0, min(32, seq), true, true);
+    sm_exact(1, min(32, seq), true, false);
+    // entry state of a stage iteration s: pP[0] = P(2s,0), sS[1] = S(2s,1) - r
+
+    int sidx = 0;
+    for (; 2 * sidx + 3 <= Ufull; ++sidx) {      // touches sub-tiles 2s .. 2s+2, all complete
+        if (sidx > 0) {
+            // stages <= sidx+1 landed (sidx+2 may be in flight); nobody reads stage sidx-1 any
+            // more, whose buffer stage sidx+3 reuses
+            asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+            __syncthreads();
+            issue(sidx + 3);
+        }
+        const int u = 2 * sidx;
+        body(u, u, u + 1, 0);
+        body(u, u + 1, u + 1, 1);
+        body(u + 1, u + 1, u + 2, 0);
+        body(u + 1, u + 2, u + 2, 1);
+    }
+    // drain: P(2*sidx, 0) is pending, S(2*sidx, 1) is pending; the rest goes the careful way.
+    // Every stage the tail reads (at most sidx+1) was requested by the look-ahead.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    {
+        const int u = 2 * sidx;
+        pv(u, 0);
+        qk(u, 1);
+        sm_exact(1, min(32, seq - 32 * u), false, true);
+        pv(u, 1);
+        for (int uu = u + 1; uu < U; ++uu) {
+            const int valid = min(32, seq - 32 * uu);
+            qk(uu, 0);
+            sm_exact(0, valid, false, true);
+            pv(uu, 0);
+            qk(uu, 1);
+            sm_exact(1, valid, false, true);
+            pv(uu, 1);
+        }
+    }
+
+#pragma unroll
+    for (int t = 0; t < QT; ++t) {
+        float l = sum_across_halves(lsum[t]);
+        float inv = 1.0f / l;
+        int qi = q0 + t * 32 + col;
+        if (qi < seq) {
+            bf16_t* op = o + b * s.o_batch + (long)qi * s.o_tok + h * s.o_head;
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    bf16x4_t w;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) w[e] = (__bf16)(oacc[dt][t][g * 4 + e] * inv);
+                    *reinterpret_cast<bf16x4_t*>(op + dt * 32 + g * 8 + half * 4) = w;
+                }
+        }
+    }
+}
+
 size_t attention_workspace_bytes(int dtype, int batch, int seq, int heads, int head_dim) {
     (void)dtype; (void)batch; (void)seq; (void)heads; (void)head_dim;
     return 0;
 }
 
+bool attention_uses_mfma(int dtype, int head_dim) {
+    return dtype == PS_BF16 && head_dim == 64 && get_kernel_path() != 1;
+}
+
 hipError_t launch_attention(int dtype, const void* q, const void* k, const void* v, void* o,
                             int batch, int seq, int heads, int head_dim, float scale,
-                            const AttnStrides& s, void* ws, hipStream_t st) {
+                            const AttnStrides& s, void* ws, hipStream_t st, bool q_prescaled) {
     (void)ws;
-    if (dtype == PS_BF16 && head_dim == 64 && get_kernel_path() != 1) {
+    if (attention_uses_mfma(dtype, head_dim)) {
         constexpr int QT = 2;
         constexpr int BQ = 4 * QT * 32;
         int qblocks = (seq + BQ - 1) / BQ;
         dim3 grid(qblocks * heads * batch);
-        attn_mfma_kernel<QT><<<grid, 256, 0, st>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o,
-                                                   seq, heads, scale * 1.4426950408889634f, qblocks, s);
+        const float c = scale * 1.4426950408889634f;
+        const bool pipe = get_kernel_path() == 2;   // the software-pipelined variant is opt-in
+        const bf16_t *qq = (const bf16_t*)q, *kk = (const bf16_t*)k, *vv = (const bf16_t*)v;
+        if (pipe && q_prescaled)
+            attn_mfma_pipe_kernel<true><<<grid, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c, qblocks, s);
+        else if (pipe)
+            attn_mfma_pipe_kernel<false><<<grid, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c, qblocks, s);
+        else if (q_prescaled)
+            attn_mfma_kernel<QT, true><<<grid, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c, qblocks, s);
+        else
+            attn_mfma_kernel<QT, false><<<grid, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c, qblocks, s);
         return hipGetLastError();
     }
+    if (q_prescaled) return hipErrorInvalidValue;     // only the MFMA kernel takes pre-scaled queries
     if (dtype == PS_BF16)
         return launch_generic_attn<bf16_t>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, batch,
                                            seq, heads, head_dim, scale, s, st);

@@ -51,6 +51,7 @@ struct Epilogue {
     const float* rope_cos;    // fp32 [N_v, d/2]
     const float* rope_sin;
     int head_dim;
+    float q_scale;            // factor applied to the q columns (col < D) after the rotation
 };
 
 // ---- launchers (each validates nothing; callers have checked shapes) -----------------
@@ -64,9 +65,11 @@ struct AttnStrides { long q_tok, q_head, q_batch, k_tok, k_head, k_batch, v_tok,
                      o_tok, o_head, o_batch; };
 // `ws` is scratch of attention_workspace_bytes() bytes (may be NULL when that is 0).
 size_t attention_workspace_bytes(int dtype, int batch, int seq, int heads, int head_dim);
+// q_prescaled: q already carries scale*log2(e) (only valid when attention_uses_mfma()).
+bool attention_uses_mfma(int dtype, int head_dim);
 hipError_t launch_attention(int dtype, const void* q, const void* k, const void* v, void* o,
                             int batch, int seq, int heads, int head_dim, float scale,
-                            const AttnStrides& s, void* ws, hipStream_t st);
+                            const AttnStrides& s, void* ws, hipStream_t st, bool q_prescaled = false);
 void set_kernel_path(int p);
 int get_kernel_path();
 

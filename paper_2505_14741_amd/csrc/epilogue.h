@@ -36,6 +36,7 @@ __device__ __forceinline__ void epilogue_pair(const Epilogue& ep, T* __restrict_
             v0 = r0;
             v1 = r1;
         }
+        if (col < ep.D) { v0 *= ep.q_scale; v1 *= ep.q_scale; }
     }
     if constexpr (sizeof(T) == 2) {
         union { bf16_t h[2]; uint32_t u; } pk;

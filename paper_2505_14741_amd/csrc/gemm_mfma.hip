@@ -9,15 +9,18 @@
 // barrier per slice.
 //
 // LDS rows are 128 bytes (64 bf16).  A direct load writes lane j's 16 bytes at
-// base + 16*j, so one wave instruction fills 8 rows; the XOR swizzle that keeps fragment
-// reads conflict-free (16-byte slot p of row r holds chunk p ^ (r & 7)) is applied on the
-// global side: lane j fetches chunk (j%8) ^ (j/8) of row j/8.
+// base + 16*j, so one wave instruction fills 8 rows.  LDS has 64 four-byte banks and a
+// 16-byte read is served 16 lanes at a time, so the 16 consecutive rows a fragment read
+// touches must land in 16 different 16-byte bank groups: slot p of row r holds chunk
+// p ^ ((r >> 1) & 7) (row parity picks the half of the banks, the XOR the group).  The
+// swizzle is applied on the global side: lane j of row group g fetches chunk
+// (j%8) ^ (4*(g%2) + j/16) of row 8g + j/8.
 //
 // Output mapping of the 32x32 accumulator: lane l holds column l%32 and rows
 // 8*(i/4) + 4*(l/32) + i%4 for i < 16; activations are the row operand, so a lane's
 // column is an output feature and stores of one accumulator register are contiguous
-// across lanes.  Adjacent lanes swap one value so every lane owns an (even, odd) column
-// pair -- the unit the epilogues (bias, GELU, gate*residual, rotary pairs) work on.
+// across lanes (bf16 stores cover 64 bytes per row, fp32 residual updates 128).  The
+// rotary epilogue gets a pair's other element from the neighbouring lane with one DPP move.
 #include "common.h"
 #include "epilogue.h"
 
@@ -35,6 +38,97 @@ __device__ __forceinline__ int xcd_remap(int id, int total) {
     int per = total / 8, rem = total % 8;
     int x = id % 8, j = id / 8;
     return x * per + (x < rem ? x : rem) + j;
+}
+
+// tanh-form GELU written as x * sigmoid(2u), u = sqrt(2/pi)(x + 0.044715 x^3): two
+// transcendentals and four FMAs; used where the result is rounded to bf16.
+__device__ __forceinline__ float gelu_fast(float x) {
+    const float c0 = -2.0f * 0.7978845608028654f * 1.4426950408889634f;
+    const float c1 = c0 * 0.044715f;
+    float t = x * (c0 + c1 * x * x);
+    return x * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(t));
+}
+
+__device__ __forceinline__ unsigned short bf16_bits(float v) {
+    return __builtin_bit_cast(unsigned short, (__bf16)v);
+}
+
+// Writes the TM x TN accumulator tiles of one wave.  row0/col0: first row (incl. the
+// lane's 4*half offset) and the lane's column of tile (0,0).  Offsets are 32-bit element
+// indices from the uniform base pointers (the launcher guarantees M*Nn < 2^31).
+template <int TM, int TN, int KIND, bool CHECK>
+__device__ __forceinline__ void tile_epilogue(f32x16_t (&acc)[TM][TN], const Epilogue& ep, bf16_t* __restrict__ C,
+                                              int M, int Nn, int row0, int col0, int lane) {
+    unsigned short* __restrict__ Cb = reinterpret_cast<unsigned short*>(C);
+    const int tokens = ep.geom.tokens, text = ep.geom.text_tokens;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int col = col0 + j * 32;
+        if (CHECK && col >= Nn) continue;
+        const float bias = ep.bias[col];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int rb = row0 + i * 32;
+            if constexpr (KIND == EPI_BIAS || KIND == EPI_BIAS_GELU) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int m = rb + 8 * (e >> 2) + (e & 3);
+                    if (CHECK && m >= M) continue;
+                    float v = acc[i][j][e] + bias;
+                    if constexpr (KIND == EPI_BIAS_GELU) v = gelu_fast(v);
+                    Cb[(unsigned)(m * Nn + col)] = bf16_bits(v);
+                }
+            } else if constexpr (KIND == EPI_GATE_RESIDUAL) {
+                // X[m, col] += gate[batch(m), stream(m), col] * (acc + bias)
+                const int b_lo = rb / tokens, b_hi = (rb + 27) / tokens;
+                if (b_lo == b_hi) {
+                    const float* g = ep.mod_layer + b_lo * ep.mod_batch_stride + col;
+                    const float gv = g[ep.gate_chunk * ep.D], gt = g[(ep.gate_chunk + 6) * ep.D];
+                    const int n0r = rb - b_lo * tokens;
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int dr = 8 * (e >> 2) + (e & 3);
+                        const int m = rb + dr;
+                        if (CHECK && m >= M) continue;
+                        const float gate = (n0r + dr) < text ? gt : gv;
+                        const unsigned off = (unsigned)(m * Nn + col);
+                        ep.resid[off] += gate * (acc[i][j][e] + bias);
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int m = rb + 8 * (e >> 2) + (e & 3);
+                        if (CHECK && m >= M) continue;
+                        const int b = m / tokens, n = m - b * tokens;
+                        const int chunk = ep.gate_chunk + (n < text ? 6 : 0);
+                        const float gate = ep.mod_layer[b * ep.mod_batch_stride + (long)chunk * ep.D + col];
+                        const unsigned off = (unsigned)(m * Nn + col);
+                        ep.resid[off] += gate * (acc[i][j][e] + bias);
+                    }
+                }
+            } else {   // EPI_QKV_ROPE: rotate (even, odd) column pairs of q and k of video tokens
+                const bool rot = col < 2 * ep.D;
+                const int pr = (col % ep.head_dim) >> 1;
+                const int hd2 = ep.head_dim >> 1;
+                const bool odd = lane & 1;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int m = rb + 8 * (e >> 2) + (e & 3);
+                    float v = acc[i][j][e] + bias;
+                    const float partner = swap_adjacent_lanes(v);      // before any divergence
+                    if (CHECK && m >= M) continue;
+                    const int n = m % tokens;
+                    if (rot && n >= text) {
+                        const unsigned ti = (unsigned)((n - text) * hd2 + pr);
+                        const float cs = ep.rope_cos[ti], sn = ep.rope_sin[ti];
+                        v = odd ? (v * cs + partner * sn) : (v * cs - partner * sn);
+                    }
+                    if (col < ep.D) v *= ep.q_scale;
+                    Cb[(unsigned)(m * Nn + col)] = bf16_bits(v);
+                }
+            }
+        }
+    }
 }
 
 template <int BM, int BN, int WR, int WC, int KIND>
@@ -67,14 +161,14 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
         n0 = (in_band / rows_here) * BN;
     }
 
-    // direct global->LDS loads: this wave fills row groups wave, wave+NW, ...; lane j of a
-    // group fetches chunk (j%8)^(j/8) of row 8*g + j/8
-    const int lr = lane >> 3, lc = (lane & 7) ^ lr;
+    // direct global->LDS loads: this wave fills row groups wave, wave+NW, ...
+    const int lr = lane >> 3;
     const bf16_t* gp[GPW];
 #pragma unroll
     for (int i = 0; i < GPW; ++i) {
         int g = wave + NW * i;
         int row = g * 8 + lr;                       // row within [A rows | W rows]
+        const int lc = (lane & 7) ^ (((g & 1) << 2) | (lane >> 4));
         if (row < BM) {
             int r = m0 + row;
             r = r < M ? r : M - 1;
@@ -104,13 +198,13 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
 
     const int frow = lane & 31, fhalf = lane >> 5;
     // fragment byte offsets inside a stage (row*128 + swizzled chunk); the k16-step only
-    // changes the chunk: c = 2*ks + fhalf, slot = c ^ (row & 7)
+    // changes the chunk: c = 2*ks + fhalf, slot = c ^ ((row >> 1) & 7)
     int aoff[TM], boff[TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i) aoff[i] = (wm * WM + i * 32 + frow) * 128;
 #pragma unroll
     for (int j = 0; j < TN; ++j) boff[j] = (BM + wn * WN + j * 32 + frow) * 128;
-    const int sw = frow & 7;
+    const int sw = (frow >> 1) & 7;
 
     const int nk = K / BK;
     issue(0, 0);
@@ -136,35 +230,16 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
         }
     }
 
-    // epilogue: lanes pair up so each owns two adjacent columns of one row
-    const bool odd = lane & 1;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            int colbase = n0 + wn * WN + j * 32 + (frow & ~1);
-            int rowbase = m0 + wm * WM + i * 32 + 4 * fhalf;
-            if (colbase >= Nn) continue;
-            const float2 bias2 = *reinterpret_cast<const float2*>(ep.bias + colbase);
-#pragma unroll
-            for (int e = 0; e < 16; e += 2) {
-                float mine0 = acc[i][j][e], mine1 = acc[i][j][e + 1];
-                float send = odd ? mine0 : mine1;
-                float recv = swap_adjacent_lanes(send);
-                // even lane: row e   -> (own col, partner col)
-                // odd  lane: row e+1 -> (partner col, own col)
-                float v0 = odd ? recv : mine0;
-                float v1 = odd ? mine1 : recv;
-                int ee = odd ? e + 1 : e;
-                int m = rowbase + 8 * (ee >> 2) + (ee & 3);
-                if (m < M) epilogue_pair<KIND, bf16_t>(ep, C, Nn, m, colbase, v0 + bias2.x, v1 + bias2.y);
-            }
-        }
-    }
+    // epilogue: a lane owns one output column (feature) of each 32x32 tile and 16 of its rows
+    const bool interior = (m0 + BM <= M) && (n0 + BN <= Nn);
+    if (interior)
+        tile_epilogue<TM, TN, KIND, false>(acc, ep, C, M, Nn, m0 + wm * WM + 4 * fhalf, n0 + wn * WN + frow, lane);
+    else
+        tile_epilogue<TM, TN, KIND, true>(acc, ep, C, M, Nn, m0 + wm * WM + 4 * fhalf, n0 + wn * WN + frow, lane);
 }
 
 bool gemm_mfma_supported(int M, int Nn, int K) {
-    return K % 64 == 0 && Nn % 2 == 0 && M >= 1 && Nn >= 64 && K >= 64;
+    return K % 64 == 0 && Nn % 2 == 0 && M >= 1 && Nn >= 64 && K >= 64 && (long)M * Nn < (1L << 31);
 }
 
 template <int BM, int BN, int WR, int WC>
@@ -192,7 +267,14 @@ void set_gemm_variant(int v) { g_gemm_variant = v; }
 hipError_t launch_gemm_mfma(const bf16_t* A, const bf16_t* W, bf16_t* C, int M, int Nn, int K,
                             const Epilogue& ep, hipStream_t st) {
     int v = g_gemm_variant;
-    if (v == 0) v = (M >= 1024) ? 1 : 3;
+    if (v == 0) {
+        // measured at 17776 tokens inside the forward: two co-resident 128x128 workgroups hide
+        // each other's epilogue (rotary, fp32 residual read-modify-write); the wide GELU
+        // projection is better off with the 256x256 tile's lower L2 traffic
+        if (M < 1024) v = 3;
+        else if (ep.kind == EPI_BIAS_GELU || (ep.kind == EPI_BIAS && Nn >= 6144)) v = 1;
+        else v = 3;
+    }
     switch (v) {
         case 1: return launch_tile<256, 256, 2, 4>(A, W, C, M, Nn, K, ep, st);   // 8 waves, 128x64 each
         case 2: return launch_tile<256, 256, 2, 2>(A, W, C, M, Nn, K, ep, st);   // 4 waves, 128x128 each

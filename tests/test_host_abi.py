@@ -129,10 +129,10 @@ def test_attn3d_validation():
     assert f(n=0) == -2 and f(b=0) == -2 and f(d=48) == -2 and f(d=128) == -2
     assert f(scale=0.0) == -2 and f(scale=float("nan")) == -2 and f(scale=-1.0) == -2
     assert f(o=Q) == -2 and f(q=Q + 2) == -2
-    # the bf16 head-dim-64 kernel needs a workspace; fp32 does not
-    assert L.attn3d_workspace_bytes(1, 100, 2, 64, 1) >= 2 * 64 * 128 * 2
+    # no kernel needs scratch at present (V is transposed inside LDS reads), so NULL is accepted
+    assert L.attn3d_workspace_bytes(1, 100, 2, 64, 1) == 0
     assert L.attn3d_workspace_bytes(1, 100, 2, 16, 0) == 0
-    assert f(d=64, dt=1, ws=None) == -4 and f(d=64, dt=1, ws=WS, wsb=8) == -4
+    assert L.attn3d_workspace_bytes(0, 100, 2, 16, 0) == 0
 
 
 def test_sampler_step_and_rel_mae_validation():
