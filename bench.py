@@ -35,7 +35,7 @@ def device_weights(cfg, torch, seed):
     return out
 
 
-def cpu_baseline(cfg, rows=512):
+def cpu_baseline(cfg, rows=6144):
     """Time the oracle on a bounded sample of one step: `rows` token rows of one layer
     (all four projections for those rows, and full attention of those query rows over all
     keys and heads), then scale by the work of a whole step."""
@@ -81,6 +81,8 @@ def main():
     ap.add_argument("--workload", default="full", choices=["full", "long", "block"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-path", type=lambda v: int(v, 0), default=0, help="tuning hook passed to ps_set_kernel_path")
+    ap.add_argument("--kernel", default=None, choices=["attn3d", "copy", "sampler_step"],
+                    help="profiling target: launch only this kernel 3 times at the workload's shape and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives are built); use --gpus 1")
@@ -96,6 +98,31 @@ def main():
     cfg = I.CONFIGS[args.workload]
     N, D = cfg.tokens, cfg.hidden
     K, Wm = args.steps, args.warmup
+
+    if args.kernel:                               # counter / trace target (rocprofv3 -- python3 bench.py --kernel ...)
+        g = torch.Generator(device="cuda"); g.manual_seed(11)
+        if args.kernel == "attn3d":
+            q, k, v = (torch.randn((1, N, cfg.heads, cfg.head_dim), generator=g, device="cuda").to(torch.bfloat16)
+                       for _ in range(3))
+            o = torch.empty_like(q)
+            for _ in range(3):
+                B.attn3d(q, k, v, cfg.head_dim ** -0.5, out=o)
+            what = {"kernel": "attn3d", "tokens": N, "heads": cfg.heads, "flop": 4.0 * N * N * D}
+        elif args.kernel == "copy":               # plain copy of known size: scale for FETCH_SIZE / WRITE_SIZE
+            n = 1 << 28
+            a, b = torch.randn(n, generator=g, device="cuda"), torch.empty(n, device="cuda")
+            for _ in range(3):
+                b.copy_(a)
+            what = {"kernel": "copy", "bytes_read": 4 * n, "bytes_written": 4 * n}
+        else:
+            n = 1 << 28
+            xs, es, ps = (torch.randn(n, generator=g, device="cuda") for _ in range(3))
+            for _ in range(3):
+                B.sampler_step(xs, es, ps, 0.99, 0.05, x_out=xs)
+            what = {"kernel": "sampler_step", "n": n, "bytes": 16 * n}
+        torch.cuda.synchronize()
+        print(json.dumps(what))
+        return
 
     d = B.dit_create(cfg, device_weights(cfg, torch, 1003))
     g = torch.Generator(device="cuda"); g.manual_seed(42)

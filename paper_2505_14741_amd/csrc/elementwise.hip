@@ -329,14 +329,31 @@ hipError_t launch_final_proj(int dtype, const float* X, const float* modf, const
 }
 
 // ------------------------------------------------- scheduler update + relative-MAE sums
-// Two-stage deterministic reduction: stage 1 streams the tensors once (float4, grid-stride
-// with a fixed grid), each block leaves its partial sums in the workspace; stage 2 (one
-// block) adds the partials in a fixed order in double.
+// Two-stage deterministic reduction.  Stage 1 streams the tensors once with non-temporal
+// 16-byte accesses, two independent float4 per tensor in flight per thread, and a grid of
+// up to 32768 short workgroups (measured on MI355X: many short workgroups balance the HBM
+// channels better than a few long ones); each workgroup leaves its partial sums in the
+// workspace.  Stage 2 (one workgroup) adds the partials in a fixed order in double.
 static constexpr int RED_THREADS = 256;
-static constexpr int RED_MAX_BLOCKS = 2048;
+static constexpr int RED_MAX_BLOCKS = 32768;
+static constexpr int RED_UNROLL = 2;
+
+typedef __attribute__((ext_vector_type(4))) float v4f_t;
+__device__ __forceinline__ float4 stream_load(const float4* p) {
+    v4f_t v = __builtin_nontemporal_load(reinterpret_cast<const v4f_t*>(p));
+    return make_float4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ void stream_store(float4 r, float4* p) {
+    v4f_t v = {r.x, r.y, r.z, r.w};
+    __builtin_nontemporal_store(v, reinterpret_cast<v4f_t*>(p));
+}
+__device__ __forceinline__ float abs4(float4 v) { return (fabsf(v.x) + fabsf(v.y)) + (fabsf(v.z) + fabsf(v.w)); }
+__device__ __forceinline__ float absdiff4(float4 a, float4 b) {
+    return (fabsf(a.x - b.x) + fabsf(a.y - b.y)) + (fabsf(a.z - b.z) + fabsf(a.w - b.w));
+}
 
 static int red_blocks(size_t n) {
-    size_t per_block = (size_t)RED_THREADS * 4 * 4;     // 4 float4 per thread per sweep
+    size_t per_block = (size_t)RED_THREADS * 4 * RED_UNROLL;
     size_t b = (n + per_block - 1) / per_block;
     if (b < 1) b = 1;
     if (b > RED_MAX_BLOCKS) b = RED_MAX_BLOCKS;
@@ -362,77 +379,101 @@ __device__ __forceinline__ void block_store_partials(double (&acc)[NS], double* 
     }
 }
 
+// stage 2: NS sums over nblocks partials; thread k of 256 adds partials k, k+256, ... and the
+// 256 results are combined in a fixed tree, so the result does not depend on timing
+template <int NS>
+__device__ __forceinline__ void reduce_partials(const double* __restrict__ part, int nblocks, double (&out)[NS]) {
+    __shared__ double sm2[NS][RED_THREADS / WAVE];
+    double acc[NS];
+#pragma unroll
+    for (int k = 0; k < NS; ++k) acc[k] = 0.0;
+    for (int b = threadIdx.x; b < nblocks; b += RED_THREADS)
+#pragma unroll
+        for (int k = 0; k < NS; ++k) acc[k] += part[(long)b * NS + k];
+    int lane = threadIdx.x % WAVE, wave = threadIdx.x / WAVE;
+#pragma unroll
+    for (int k = 0; k < NS; ++k) {
+        double v = wave_sum_d(acc[k]);
+        if (lane == 0) sm2[k][wave] = v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < NS; ++k) {
+        double t = 0.0;
+        for (int w = 0; w < RED_THREADS / WAVE; ++w) t += sm2[k][w];
+        out[k] = t;
+    }
+}
+
+// increment form: d = (a-1)x + b*eps, x' = x + d (a -> 1 near the end of a run, and the sum
+// of |x' - x| must not come from a difference of rounded values)
 template <bool SUMS, bool PREV>
 __global__ void __launch_bounds__(RED_THREADS)
-sampler_step_kernel(const float* x, const float* __restrict__ e,
-                    const float* __restrict__ ep, float* xo, float am1, float b,
-                    size_t n, double* __restrict__ part) {
+sampler_step_kernel(const float* x, const float* __restrict__ e, const float* __restrict__ ep, float* xo,
+                    float am1, float b, size_t n, double* __restrict__ part) {
     float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-    double acc[4] = {0.0, 0.0, 0.0, 0.0};
-    size_t nvec = n / 4;
-    size_t stride = (size_t)gridDim.x * blockDim.x;
+    const size_t nvec = n / 4;
+    const size_t stride = (size_t)gridDim.x * RED_THREADS;
     const float4* x4 = reinterpret_cast<const float4*>(x);
     const float4* e4 = reinterpret_cast<const float4*>(e);
     const float4* p4 = reinterpret_cast<const float4*>(ep);
     float4* o4 = reinterpret_cast<float4*>(xo);
-    int cnt = 0;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += stride) {
-        float4 xv = x4[i], ev = e4[i];
-        // increment form: d = (a-1)x + b*eps, x' = x + d (a -> 1 near the end of a run, and the
-        // sum of |x' - x| must not come from a difference of rounded values)
+    auto one = [&](float4 xv, float4 ev, float4 pv, size_t i) {
         float4 dl, r;
         dl.x = am1 * xv.x + b * ev.x; dl.y = am1 * xv.y + b * ev.y;
         dl.z = am1 * xv.z + b * ev.z; dl.w = am1 * xv.w + b * ev.w;
         r.x = xv.x + dl.x; r.y = xv.y + dl.y; r.z = xv.z + dl.z; r.w = xv.w + dl.w;
-        o4[i] = r;
+        stream_store(r, o4 + i);
         if constexpr (SUMS) {
-            s0 += (fabsf(dl.x) + fabsf(dl.y)) + (fabsf(dl.z) + fabsf(dl.w));
-            s1 += (fabsf(r.x) + fabsf(r.y)) + (fabsf(r.z) + fabsf(r.w));
-            s3 += (fabsf(ev.x) + fabsf(ev.y)) + (fabsf(ev.z) + fabsf(ev.w));
-            if constexpr (PREV) {
-                float4 pv = p4[i];
-                s2 += (fabsf(ev.x - pv.x) + fabsf(ev.y - pv.y)) + (fabsf(ev.z - pv.z) + fabsf(ev.w - pv.w));
-            }
-            if (++cnt == 16) {       // flush fp32 partials into double every 64 elements
-                acc[0] += s0; acc[1] += s1; acc[2] += s2; acc[3] += s3;
-                s0 = s1 = s2 = s3 = 0.f; cnt = 0;
-            }
+            s0 += abs4(dl); s1 += abs4(r); s3 += abs4(ev);
+            if constexpr (PREV) s2 += absdiff4(ev, pv);
         }
+    };
+    size_t i = (size_t)blockIdx.x * RED_THREADS + threadIdx.x;
+    for (; i + stride < nvec; i += RED_UNROLL * stride) {
+        float4 xa = stream_load(x4 + i), xb = stream_load(x4 + i + stride);
+        float4 ea = stream_load(e4 + i), eb = stream_load(e4 + i + stride);
+        float4 pa = xa, pb = xb;
+        if constexpr (SUMS && PREV) { pa = stream_load(p4 + i); pb = stream_load(p4 + i + stride); }
+        one(xa, ea, pa, i);
+        one(xb, eb, pb, i + stride);
+    }
+    if (i < nvec) {
+        float4 xa = stream_load(x4 + i), ea = stream_load(e4 + i), pa = xa;
+        if constexpr (SUMS && PREV) pa = stream_load(p4 + i);
+        one(xa, ea, pa, i);
     }
     // ragged tail (n % 4 elements) handled by the first threads of block 0
     if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
-        size_t i = nvec * 4 + threadIdx.x;
-        float xv = x[i], ev = e[i];
+        size_t t = nvec * 4 + threadIdx.x;
+        float xv = x[t], ev = e[t];
         float dl = am1 * xv + b * ev;
         float r = xv + dl;
-        xo[i] = r;
+        xo[t] = r;
         if constexpr (SUMS) {
             s0 += fabsf(dl); s1 += fabsf(r); s3 += fabsf(ev);
-            if constexpr (PREV) s2 += fabsf(ev - ep[i]);
+            if constexpr (PREV) s2 += fabsf(ev - ep[t]);
         }
     }
     if constexpr (SUMS) {
-        acc[0] += s0; acc[1] += s1; acc[2] += s2; acc[3] += s3;
+        // a thread adds at most n / (4 * grid * 256) + 1 float4 per sum in fp32 (a few dozen
+        // terms at any size the grid cap allows below 2^32 elements), then everything is double
+        double acc[4] = {(double)s0, (double)s1, (double)s2, (double)s3};
         block_store_partials<4>(acc, part);
     }
 }
 
-__global__ void finish_sums4_kernel(const double* __restrict__ part, int nblocks, float* __restrict__ out) {
-    int k = threadIdx.x;
-    if (k < 4) {
-        double t = 0.0;
-        for (int b = 0; b < nblocks; ++b) t += part[(long)b * 4 + k];
-        out[k] = (float)t;
-    }
+__global__ void __launch_bounds__(RED_THREADS)
+finish_sums4_kernel(const double* __restrict__ part, int nblocks, float* __restrict__ out) {
+    double t[4];
+    reduce_partials<4>(part, nblocks, t);
+    if (threadIdx.x < 4) out[threadIdx.x] = (float)t[threadIdx.x];
 }
 
 hipError_t launch_sampler_step(const float* x, const float* e, const float* e_prev, float* x_out,
                                double a, double b, size_t n, float* sums4, void* ws, hipStream_t st) {
     if (n == 0) {
-        if (sums4) {
-            // nothing to reduce: the finishing kernel with zero blocks writes four zeros
-            finish_sums4_kernel<<<1, 64, 0, st>>>((const double*)ws, 0, sums4);
-        }
+        if (sums4) finish_sums4_kernel<<<1, RED_THREADS, 0, st>>>((const double*)ws, 0, sums4);   // four zeros
         return hipGetLastError();
     }
     int blocks = red_blocks(n);
@@ -446,40 +487,45 @@ hipError_t launch_sampler_step(const float* x, const float* e, const float* e_pr
         sampler_step_kernel<true, false><<<blocks, RED_THREADS, 0, st>>>(x, e, nullptr, x_out, am1, bf, n, part);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    if (sums4) finish_sums4_kernel<<<1, 64, 0, st>>>(part, blocks, sums4);
+    if (sums4) finish_sums4_kernel<<<1, RED_THREADS, 0, st>>>(part, blocks, sums4);
     return hipGetLastError();
 }
 
 __global__ void __launch_bounds__(RED_THREADS)
 rel_mae_kernel(const float* __restrict__ a, const float* __restrict__ b, size_t n, double* __restrict__ part) {
     float s0 = 0.f, s1 = 0.f;
-    double acc[2] = {0.0, 0.0};
-    size_t nvec = n / 4;
-    size_t stride = (size_t)gridDim.x * blockDim.x;
+    const size_t nvec = n / 4;
+    const size_t stride = (size_t)gridDim.x * RED_THREADS;
     const float4* a4 = reinterpret_cast<const float4*>(a);
     const float4* b4 = reinterpret_cast<const float4*>(b);
-    int cnt = 0;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += stride) {
-        float4 av = a4[i], bv = b4[i];
-        s0 += (fabsf(av.x - bv.x) + fabsf(av.y - bv.y)) + (fabsf(av.z - bv.z) + fabsf(av.w - bv.w));
-        s1 += (fabsf(av.x) + fabsf(av.y)) + (fabsf(av.z) + fabsf(av.w));
-        if (++cnt == 16) { acc[0] += s0; acc[1] += s1; s0 = s1 = 0.f; cnt = 0; }
+    size_t i = (size_t)blockIdx.x * RED_THREADS + threadIdx.x;
+    for (; i + stride < nvec; i += RED_UNROLL * stride) {
+        float4 a0 = stream_load(a4 + i), a1 = stream_load(a4 + i + stride);
+        float4 b0 = stream_load(b4 + i), b1 = stream_load(b4 + i + stride);
+        s0 += absdiff4(a0, b0) + absdiff4(a1, b1);
+        s1 += abs4(a0) + abs4(a1);
+    }
+    if (i < nvec) {
+        float4 a0 = stream_load(a4 + i), b0 = stream_load(b4 + i);
+        s0 += absdiff4(a0, b0);
+        s1 += abs4(a0);
     }
     if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
-        size_t i = nvec * 4 + threadIdx.x;
-        s0 += fabsf(a[i] - b[i]); s1 += fabsf(a[i]);
+        size_t t = nvec * 4 + threadIdx.x;
+        s0 += fabsf(a[t] - b[t]); s1 += fabsf(a[t]);
     }
-    acc[0] += s0; acc[1] += s1;
+    double acc[2] = {(double)s0, (double)s1};
     block_store_partials<2>(acc, part);
 }
 
-__global__ void finish_rel_mae_kernel(const double* __restrict__ part, int nblocks, float* __restrict__ out3) {
+__global__ void __launch_bounds__(RED_THREADS)
+finish_rel_mae_kernel(const double* __restrict__ part, int nblocks, float* __restrict__ out3) {
+    double t[2];
+    reduce_partials<2>(part, nblocks, t);
     if (threadIdx.x == 0) {
-        double num = 0.0, den = 0.0;
-        for (int b = 0; b < nblocks; ++b) { num += part[(long)b * 2]; den += part[(long)b * 2 + 1]; }
-        out3[0] = (float)num;
-        out3[1] = (float)den;
-        out3[2] = (float)(num / den);     // IEEE: inf or nan when the denominator is 0
+        out3[0] = (float)t[0];
+        out3[1] = (float)t[1];
+        out3[2] = (float)(t[0] / t[1]);     // IEEE: inf or nan when the denominator is 0
     }
 }
 
@@ -491,7 +537,7 @@ hipError_t launch_rel_mae(const float* a, const float* b, size_t n, float* out3,
         hipError_t err = hipGetLastError();
         if (err != hipSuccess) return err;
     }
-    finish_rel_mae_kernel<<<1, 64, 0, st>>>(part, blocks, out3);
+    finish_rel_mae_kernel<<<1, RED_THREADS, 0, st>>>(part, blocks, out3);
     return hipGetLastError();
 }
 
