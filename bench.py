@@ -21,6 +21,9 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+# HBM bytes per attention launch at the `full` shape, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a
+# plain 1 GiB copy (profiles/attn3d_full_hbm_traffic.md): 501 MB fetched + 68 MB written
+ATTN_HBM_BYTES_PER_LAUNCH = 5.70e8
 
 
 def device_weights(cfg, torch, seed):
@@ -186,7 +189,7 @@ def main():
                    "tokens": N, "layers": cfg.layers, "latent": list(cfg.latent_shape)},
         "roofline": {"kernel": "attn_mfma_kernel", "bound": "mfma", "achieved": round(att_tflops, 1),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(att_tflops / PEAK_BF16_TFLOPS, 4),
-                     "traffic": None, "avg_ms": round(att_avg, 4), "launches": int(att_n),
+                     "traffic": ATTN_HBM_BYTES_PER_LAUNCH if args.workload == "full" else None, "avg_ms": round(att_avg, 4), "launches": int(att_n),
                      "flop_per_launch": 4.0 * N * N * D},
         "attn_pct_of_bf16_peak": round(100 * att_tflops / PEAK_BF16_TFLOPS, 2),
         "gemm": {"tflops": round(gemm_tflops, 1), "frac": round(gemm_tflops / PEAK_BF16_TFLOPS, 4),
