@@ -53,12 +53,37 @@ __device__ __forceinline__ unsigned short bf16_bits(float v) {
     return __builtin_bit_cast(unsigned short, (__bf16)v);
 }
 
+// Residual values of one wave's outputs, requested before the main loop so that the
+// read-modify-write epilogue finds them in registers (rows past M re-read the last row).
+template <int TM, int TN>
+struct ResidualPrefetch {
+    float x[TM][TN][16];
+};
+template <int TM, int TN>
+__device__ __forceinline__ void prefetch_residual(ResidualPrefetch<TM, TN>& rp, const float* __restrict__ X, int M,
+                                                  int Nn, int row0, int col0) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        int col = col0 + j * 32;
+        col = col < Nn ? col : Nn - 1;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                int m = row0 + i * 32 + 8 * (e >> 2) + (e & 3);
+                m = m < M ? m : M - 1;
+                rp.x[i][j][e] = X[(unsigned)(m * Nn + col)];
+            }
+    }
+}
+
 // Writes the TM x TN accumulator tiles of one wave.  row0/col0: first row (incl. the
 // lane's 4*half offset) and the lane's column of tile (0,0).  Offsets are 32-bit element
 // indices from the uniform base pointers (the launcher guarantees M*Nn < 2^31).
 template <int TM, int TN, int KIND, bool CHECK>
 __device__ __forceinline__ void tile_epilogue(f32x16_t (&acc)[TM][TN], const Epilogue& ep, bf16_t* __restrict__ C,
-                                              int M, int Nn, int row0, int col0, int lane) {
+                                              int M, int Nn, int row0, int col0, int lane,
+                                              const ResidualPrefetch<TM, TN>* rp) {
     unsigned short* __restrict__ Cb = reinterpret_cast<unsigned short*>(C);
     const int tokens = ep.geom.tokens, text = ep.geom.text_tokens;
 #pragma unroll
@@ -92,7 +117,7 @@ __device__ __forceinline__ void tile_epilogue(f32x16_t (&acc)[TM][TN], const Epi
                         if (CHECK && m >= M) continue;
                         const float gate = (n0r + dr) < text ? gt : gv;
                         const unsigned off = (unsigned)(m * Nn + col);
-                        ep.resid[off] += gate * (acc[i][j][e] + bias);
+                        ep.resid[off] = rp->x[i][j][e] + gate * (acc[i][j][e] + bias);
                     }
                 } else {
 #pragma unroll
@@ -103,7 +128,7 @@ __device__ __forceinline__ void tile_epilogue(f32x16_t (&acc)[TM][TN], const Epi
                         const int chunk = ep.gate_chunk + (n < text ? 6 : 0);
                         const float gate = ep.mod_layer[b * ep.mod_batch_stride + (long)chunk * ep.D + col];
                         const unsigned off = (unsigned)(m * Nn + col);
-                        ep.resid[off] += gate * (acc[i][j][e] + bias);
+                        ep.resid[off] = rp->x[i][j][e] + gate * (acc[i][j][e] + bias);
                     }
                 }
             } else {   // EPI_QKV_ROPE: rotate (even, odd) column pairs of q and k of video tokens
@@ -131,19 +156,39 @@ __device__ __forceinline__ void tile_epilogue(f32x16_t (&acc)[TM][TN], const Epi
     }
 }
 
-template <int BM, int BN, int WR, int WC, int KIND>
-__global__ void __launch_bounds__(WR * WC * 64, 1)
+// global->LDS load of 16 bytes per lane, issued from inline asm: lane j's bytes land at
+// lds_addr + 16*j (lds_addr wave-uniform, passed through M0).  The compiler does not see the
+// LDS write, so it never orders LDS reads of other stages behind loads still in flight; the
+// explicit vmcnt waits and barriers in the kernel make a stage visible before it is read.
+__device__ __forceinline__ void lds_dma16(const void* gptr, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr)
+                 : "memory", "m0");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// BK: K depth of an LDS stage (64 or 32 bf16 = 128- or 64-byte rows); NST: ring depth.
+// Stage kt+NST-1 is requested while stage kt is multiplied.
+template <int BM, int BN, int WR, int WC, int BK, int NST, int KIND>
+__global__ void __launch_bounds__(WR * WC * 64, (WR * WC == 4 && BM * BN <= 128 * 128) ? 2 : 1)
 gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf16_t* __restrict__ C,
                  int M, int Nn, int K, int tiles_m, int tiles_n, Epilogue ep) {
-    constexpr int BK = 64;
+    static_assert(BK == 64 || BK == 32, "stage depth");
     constexpr int NW = WR * WC;
     constexpr int WM = BM / WR, WN = BN / WC;
     constexpr int TM = WM / 32, TN = WN / 32;
-    constexpr int GROUPS = (BM + BN) / 8;          // 8-row groups per stage, one wave instruction each
-    constexpr int GPW = GROUPS / NW;               // groups per wave
-    constexpr int STAGE = (BM + BN) * BK * 2;      // bytes
+    constexpr int ROWB = BK * 2;                         // bytes per LDS row
+    constexpr int RPI = 1024 / ROWB;                     // rows filled by one wave instruction (8 or 16)
+    constexpr int CPR = ROWB / 16;                       // 16-byte chunks per row (8 or 4)
+    constexpr int GROUPS = (BM + BN) / RPI;
+    constexpr int GPW = GROUPS / NW;                     // load instructions per wave per stage
+    constexpr int STAGE = (BM + BN) * ROWB;
     static_assert(GROUPS % NW == 0, "rows must split evenly over waves");
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * STAGE];
+    static_assert(BM % RPI == 0, "a load group must not straddle the A/W boundary");
+    static_assert((NST - 1) * GPW <= 63, "vmcnt range");
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * STAGE];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -161,14 +206,18 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
         n0 = (in_band / rows_here) * BN;
     }
 
-    // direct global->LDS loads: this wave fills row groups wave, wave+NW, ...
-    const int lr = lane >> 3;
+    // Swizzle (LDS has 64 four-byte banks; a 16-byte fragment read is served 16 lanes = 16
+    // consecutive rows at a time, which must hit 16 different 16-byte bank groups):
+    //   128-byte rows: slot p of row r holds chunk p ^ ((r>>1)&7)
+    //    64-byte rows: slot p of row r holds chunk p ^ ((r>>2)&3)
+    // applied on the global side of the direct load (lane j lands at base + 16j).
+    const int lr = lane / CPR;                           // row inside the load group
     const bf16_t* gp[GPW];
 #pragma unroll
     for (int i = 0; i < GPW; ++i) {
-        int g = wave + NW * i;
-        int row = g * 8 + lr;                       // row within [A rows | W rows]
-        const int lc = (lane & 7) ^ (((g & 1) << 2) | (lane >> 4));
+        const int g = wave + NW * i;
+        const int row = g * RPI + lr;                    // row within [A rows | W rows]
+        const int lc = BK == 64 ? ((lane & 7) ^ ((row >> 1) & 7)) : ((lane & 3) ^ ((row >> 2) & 3));
         if (row < BM) {
             int r = m0 + row;
             r = r < M ? r : M - 1;
@@ -179,12 +228,15 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
             gp[i] = W + (long)r * K + lc * 8;
         }
     }
-    auto issue = [&](int kt, int buf) {
+    const unsigned lds_base = (unsigned)(size_t)PS_LDS_PTR(lds);
+    const int nk = K / BK;
+    auto issue = [&](int kt) {
+        const int kc = kt < nk ? kt : nk - 1;            // past the end: harmless re-read keeps vmcnt uniform
+        const unsigned st = lds_base + (kt % NST) * STAGE;
 #pragma unroll
         for (int i = 0; i < GPW; ++i) {
-            int g = wave + NW * i;
-            __builtin_amdgcn_global_load_lds(PS_GLOBAL_PTR(gp[i] + (long)kt * BK),
-                                             PS_LDS_PTR(lds + buf * STAGE + g * 1024), 16, 0, 0);
+            const int g = wave + NW * i;
+            lds_dma16(gp[i] + (long)kc * BK, __builtin_amdgcn_readfirstlane(st + g * 1024));
         }
     };
 
@@ -197,23 +249,27 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
     const int frow = lane & 31, fhalf = lane >> 5;
-    // fragment byte offsets inside a stage (row*128 + swizzled chunk); the k16-step only
-    // changes the chunk: c = 2*ks + fhalf, slot = c ^ ((row >> 1) & 7)
     int aoff[TM], boff[TN];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) aoff[i] = (wm * WM + i * 32 + frow) * 128;
+    for (int i = 0; i < TM; ++i) aoff[i] = (wm * WM + i * 32 + frow) * ROWB;
 #pragma unroll
-    for (int j = 0; j < TN; ++j) boff[j] = (BM + wn * WN + j * 32 + frow) * 128;
-    const int sw = (frow >> 1) & 7;
+    for (int j = 0; j < TN; ++j) boff[j] = (BM + wn * WN + j * 32 + frow) * ROWB;
+    const int sw = BK == 64 ? ((frow >> 1) & 7) : ((frow >> 2) & 3);
 
-    const int nk = K / BK;
-    issue(0, 0);
+    // the residual read-modify-write epilogue gets its inputs now: these loads are older than
+    // every stage load, so the first stage wait also covers them and they cost one memory
+    // latency per tile instead of one per output row
+    ResidualPrefetch<TM, TN> rp;
+    if constexpr (KIND == EPI_GATE_RESIDUAL)
+        prefetch_residual<TM, TN>(rp, ep.resid, M, Nn, m0 + wm * WM + 4 * fhalf, n0 + wn * WN + frow);
+#pragma unroll
+    for (int p = 0; p < NST - 1; ++p) issue(p);
     for (int kt = 0; kt < nk; ++kt) {
-        const int buf = kt & 1;
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        if (kt + 1 < nk) issue(kt + 1, buf ^ 1);
-        const unsigned char* st = lds + buf * STAGE;
+        // stage kt has landed once at most the NST-2 younger stages are still in flight
+        wait_vmcnt<(NST - 2) * GPW>();
+        __syncthreads();                                 // ... for every wave; and stage kt-1 is no longer read
+        issue(kt + NST - 1);                             // into the buffer stage kt-1 occupied
+        const unsigned char* st = lds + (kt % NST) * STAGE;
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
             bf16x8_t fa[TM], fb[TN];
@@ -229,33 +285,39 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
         }
     }
+    wait_vmcnt<0>();                                     // drain the look-ahead loads before the wave ends
 
     // epilogue: a lane owns one output column (feature) of each 32x32 tile and 16 of its rows
     const bool interior = (m0 + BM <= M) && (n0 + BN <= Nn);
     if (interior)
-        tile_epilogue<TM, TN, KIND, false>(acc, ep, C, M, Nn, m0 + wm * WM + 4 * fhalf, n0 + wn * WN + frow, lane);
+        tile_epilogue<TM, TN, KIND, false>(acc, ep, C, M, Nn, m0 + wm * WM + 4 * fhalf, n0 + wn * WN + frow, lane, &rp);
     else
-        tile_epilogue<TM, TN, KIND, true>(acc, ep, C, M, Nn, m0 + wm * WM + 4 * fhalf, n0 + wn * WN + frow, lane);
+        tile_epilogue<TM, TN, KIND, true>(acc, ep, C, M, Nn, m0 + wm * WM + 4 * fhalf, n0 + wn * WN + frow, lane, &rp);
 }
 
 bool gemm_mfma_supported(int M, int Nn, int K) {
     return K % 64 == 0 && Nn % 2 == 0 && M >= 1 && Nn >= 64 && K >= 64 && (long)M * Nn < (1L << 31);
 }
 
-template <int BM, int BN, int WR, int WC>
+template <int BM, int BN, int WR, int WC, int BK, int NST>
 static hipError_t launch_tile(const bf16_t* A, const bf16_t* W, bf16_t* C, int M, int Nn, int K,
                               const Epilogue& ep, hipStream_t st) {
     int tm = (M + BM - 1) / BM, tn = (Nn + BN - 1) / BN;
     dim3 grid(tm * tn), block(WR * WC * 64);
     switch (ep.kind) {
         case EPI_BIAS:
-            gemm_mfma_kernel<BM, BN, WR, WC, EPI_BIAS><<<grid, block, 0, st>>>(A, W, C, M, Nn, K, tm, tn, ep); break;
+            gemm_mfma_kernel<BM, BN, WR, WC, BK, NST, EPI_BIAS><<<grid, block, 0, st>>>(A, W, C, M, Nn, K, tm, tn, ep);
+            break;
         case EPI_BIAS_GELU:
-            gemm_mfma_kernel<BM, BN, WR, WC, EPI_BIAS_GELU><<<grid, block, 0, st>>>(A, W, C, M, Nn, K, tm, tn, ep); break;
+            gemm_mfma_kernel<BM, BN, WR, WC, BK, NST, EPI_BIAS_GELU><<<grid, block, 0, st>>>(A, W, C, M, Nn, K, tm, tn, ep);
+            break;
         case EPI_GATE_RESIDUAL:
-            gemm_mfma_kernel<BM, BN, WR, WC, EPI_GATE_RESIDUAL><<<grid, block, 0, st>>>(A, W, C, M, Nn, K, tm, tn, ep); break;
+            gemm_mfma_kernel<BM, BN, WR, WC, BK, NST, EPI_GATE_RESIDUAL><<<grid, block, 0, st>>>(A, W, C, M, Nn, K, tm, tn,
+                                                                                                 ep);
+            break;
         case EPI_QKV_ROPE:
-            gemm_mfma_kernel<BM, BN, WR, WC, EPI_QKV_ROPE><<<grid, block, 0, st>>>(A, W, C, M, Nn, K, tm, tn, ep); break;
+            gemm_mfma_kernel<BM, BN, WR, WC, BK, NST, EPI_QKV_ROPE><<<grid, block, 0, st>>>(A, W, C, M, Nn, K, tm, tn, ep);
+            break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -276,10 +338,12 @@ hipError_t launch_gemm_mfma(const bf16_t* A, const bf16_t* W, bf16_t* C, int M, 
         else v = 3;
     }
     switch (v) {
-        case 1: return launch_tile<256, 256, 2, 4>(A, W, C, M, Nn, K, ep, st);   // 8 waves, 128x64 each
-        case 2: return launch_tile<256, 256, 2, 2>(A, W, C, M, Nn, K, ep, st);   // 4 waves, 128x128 each
-        case 3: return launch_tile<128, 128, 2, 2>(A, W, C, M, Nn, K, ep, st);   // 4 waves, 64x64 each
-        case 4: return launch_tile<256, 128, 2, 2>(A, W, C, M, Nn, K, ep, st);   // 4 waves, 128x64 each
+        case 1: return launch_tile<256, 256, 2, 4, 64, 2>(A, W, C, M, Nn, K, ep, st);   // 8 waves, 128x64 each
+        case 2: return launch_tile<256, 256, 2, 4, 32, 4>(A, W, C, M, Nn, K, ep, st);   // same tile, deeper ring
+        case 3: return launch_tile<128, 128, 2, 2, 64, 2>(A, W, C, M, Nn, K, ep, st);   // 4 waves, 64x64 each, 2 per CU
+        case 4: return launch_tile<128, 128, 2, 2, 32, 4>(A, W, C, M, Nn, K, ep, st);   // same tile, deeper ring
+        case 5: return launch_tile<256, 128, 4, 2, 64, 3>(A, W, C, M, Nn, K, ep, st);   // 8 waves, 64x64 each
+        case 6: return launch_tile<256, 128, 2, 2, 32, 3>(A, W, C, M, Nn, K, ep, st);   // 4 waves, 128x64, 2 per CU
         default: return hipErrorInvalidValue;
     }
 }
