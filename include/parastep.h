@@ -111,7 +111,8 @@ PS_API int dit_profile_read(dit* d, double* ms_out, int64_t* launches_out);
  * the inputs.  seq >= 1, scale > 0, head_dim in {16, 32, 64}; rows past the end are never
  * read, but V must be finite (masked keys multiply V by an exact 0).
  * workspace: DEVICE, 256-byte aligned, >= attn3d_workspace_bytes(...) (may be NULL when
- * that is 0, which it currently always is); scratch only. */
+ * that is 0); scratch only.  It is non-zero when the bf16 head-dim-64 kernel splits its last
+ * partial round of workgroups along the keys (partial sums are merged by a second kernel). */
 PS_API size_t attn3d_workspace_bytes(int batch, int seq, int heads, int head_dim, int dtype);
 PS_API int attn3d(const void* q, const void* k, const void* v, void* o,
            int batch, int seq, int heads, int head_dim, float scale, int dtype,
@@ -125,8 +126,8 @@ PS_API int dit_linear(const void* a, const void* w, const float* bias, void* out
                int act, int dtype, void* hip_stream);
 
 /* Test and tuning hook: 0 = pick the fastest kernel for each shape (default), 1 = always
- * use the generic fp32-FMA kernels, 2 = software-pipelined variant of the bf16 attention
- * kernel, 0x100|v = force tile variant v (1..4) of the bf16 MFMA GEMM.  Process-wide;
+ * use the generic fp32-FMA kernels, 2 = bf16 attention without the key-split of its last
+ * partial round of workgroups, 0x100|v = force tile variant v (1..6) of the bf16 MFMA GEMM.  Process-wide;
  * returns the previous value. */
 PS_API int ps_set_kernel_path(int path);
 

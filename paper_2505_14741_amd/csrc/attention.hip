@@ -173,6 +173,41 @@ __device__ __forceinline__ float sum_across_halves(float v) {
 //    new r, rescale of the running sums.
 // PRESCALED: q already carries the factor c = scale*log2(e) (the QKV projection applies it
 // in fp32 before rounding), so p = exp2(acc) with no multiply; otherwise p = exp2(c*acc).
+static constexpr int PART_STRIDE = 68;      // floats per row of a partial result (64 + l + r, padded to 16 B)
+
+// Merge of the key-range pieces of the split items: one thread per (row, 4 output values).
+// O = sum_i w_i O_i / sum_i w_i l_i with w_i = 2^(c (r_i - max_i r_i)).
+__global__ void __launch_bounds__(256)
+attn_merge_kernel(const float* __restrict__ part, bf16_t* __restrict__ o, int seq, int heads, int qblocks,
+                  int full_blocks, int nsplit, int nitems, float cexp, int bq, AttnStrides s) {
+    const int gid = blockIdx.x * 256 + threadIdx.x;
+    const int d4 = gid & 15, rowid = gid >> 4;          // 16 threads per row
+    const int item = rowid / bq, row = rowid % bq;
+    if (item >= nitems) return;
+    const int id = full_blocks + item;
+    const int bh = id / qblocks, qb = id % qblocks;
+    const int b = bh / heads, h = bh % heads;
+    const int qi = qb * bq + row;
+    if (qi >= seq) return;
+    const float* p0 = part + ((long)item * nsplit * bq + row) * PART_STRIDE;
+    float rmax = p0[65];
+    for (int i = 1; i < nsplit; ++i) rmax = fmaxf(rmax, p0[(long)i * bq * PART_STRIDE + 65]);
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    float l = 0.f;
+    for (int i = 0; i < nsplit; ++i) {
+        const float* pi = p0 + (long)i * bq * PART_STRIDE;
+        const float w = __builtin_amdgcn_exp2f((pi[65] - rmax) * cexp);
+        const float4 v = *reinterpret_cast<const float4*>(pi + d4 * 4);
+        acc.x += w * v.x; acc.y += w * v.y; acc.z += w * v.z; acc.w += w * v.w;
+        l += w * pi[64];
+    }
+    const float inv = 1.0f / l;
+    bf16x4_t wv;
+    wv[0] = (__bf16)(acc.x * inv); wv[1] = (__bf16)(acc.y * inv);
+    wv[2] = (__bf16)(acc.z * inv); wv[3] = (__bf16)(acc.w * inv);
+    *reinterpret_cast<bf16x4_t*>(o + b * s.o_batch + (long)qi * s.o_tok + h * s.o_head + d4 * 4) = wv;
+}
+
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 // acc + sum of eight bf16 values (v_dot2c_f32_bf16 against packed ones)
 __device__ __forceinline__ float rowsum_bf16x8(bf16x8_t p, float acc) {
@@ -188,7 +223,8 @@ __device__ __forceinline__ float rowsum_bf16x8(bf16x8_t p, float acc) {
 template <int QT, bool PRESCALED>   // QT: 32-query column tiles per wave
 __global__ void __launch_bounds__(256, 2)
 attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
-                 bf16_t* __restrict__ o, int seq, int heads, float scale_log2e, int qblocks, AttnStrides s) {
+                 bf16_t* __restrict__ o, int seq, int heads, float scale_log2e, int qblocks, AttnStrides s,
+                 int full_blocks, int nsplit, float* __restrict__ part) {
     constexpr int KV = 64;
     constexpr int BQ = 4 * QT * 32;
     constexpr int NST = 3;                       // LDS ring depth
@@ -199,10 +235,22 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
     const int col = lane & 31, half = lane >> 5;
     // workgroup -> (batch*head, query block); consecutive ids of one XCD walk the query
     // blocks of one head so that head's K and V stay in that XCD's L2
+    // The first full_blocks (query block, head) items each take one workgroup over all keys.
+    // The remaining items -- fewer than half a round of the chip's workgroup slots -- are each
+    // split nsplit ways along the keys, so the last round costs 1/nsplit of a full one; such
+    // a workgroup leaves unnormalised sums, row sum and reference in `part` for the merge kernel.
     int id = blockIdx.x;
-    {
-        int total = gridDim.x, per = total / 8, rem = total % 8, x = id % 8, j = id / 8;
+    int piece = -1, jt0 = 0, jt1 = (seq + KV - 1) / KV;
+    if (id < full_blocks) {
+        int per = full_blocks / 8, rem = full_blocks % 8, x = id % 8, j = id / 8;
         id = x * per + (x < rem ? x : rem) + j;
+    } else {
+        piece = id - full_blocks;
+        id = full_blocks + piece / nsplit;
+        const int pi = piece % nsplit;
+        const int nt = jt1;
+        jt0 = (int)((long)nt * pi / nsplit);
+        jt1 = (int)((long)nt * (pi + 1) / nsplit);
     }
     const int bh = id / qblocks, qb = id % qblocks;
     const int b = bh / heads, h = bh % heads;
@@ -279,11 +327,10 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
     const unsigned voff0 = KV * 128 + trow * 128 + ((tchunk ^ (trow & 7)) << 4) + tsub;
     const unsigned voff1 = KV * 128 + trow * 128 + (((4 + tchunk) ^ (trow & 7)) << 4) + tsub;
 
-    const int ntiles = (seq + KV - 1) / KV;
-    issue(0, 0);
-    issue(1, 1);                                   // tiles past the end are harmless re-reads
+    issue(jt0, 0);
+    issue(jt0 + 1, 1);                             // tiles past the end are harmless re-reads
     int buf = 0;
-    for (int j = 0; j < ntiles; ++j) {
+    for (int j = jt0; j < jt1; ++j) {
         const int kv0 = j * KV;
         // tile j has landed when at most the 4 loads of tile j+1 are still in flight
         asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
@@ -328,7 +375,7 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
         lds_issue_v_frags(vfr, lds_base + buf * STAGE + voff0, lds_base + buf * STAGE + voff1);
         bf16x8_t pf[QT][4];
         const bool ragged = kv0 + KV > seq;
-        bool redo = (j == 0) || ragged;
+        bool redo = (j == jt0) || ragged;
         if (!redo) {
             scores();
             // fast path: p = 2^(c (s - r)) without a maximum
@@ -382,10 +429,10 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
 #pragma unroll
                 for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[1][t][e]);
                 mx = max_across_halves(mx);                       // finite: every tile has a valid key
-                if (j > 0) mx = fmaxf(mx, 0.f);                   // the reference never moves down
+                if (j > jt0) mx = fmaxf(mx, 0.f);                 // the reference never moves down
                 const float rnew = (float)(__bf16)(mref[t] + mx); // new reference, bf16-representable
                 const float d = rnew - mref[t];
-                if (j > 0) {
+                if (j > jt0) {
                     const float alpha = __builtin_amdgcn_exp2f(-d * cexp);
                     lsum[t] *= alpha;
 #pragma unroll
@@ -430,6 +477,24 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // drain the look-ahead loads before exit
 
     // finish: total row sum = both halves; O[query][d] = O^T / l
+    if (piece >= 0) {
+        // partial result of a key range: [piece][row in block][64 sums | row sum | reference | pad]
+        float* pp = part + (long)piece * BQ * PART_STRIDE;
+#pragma unroll
+        for (int t = 0; t < QT; ++t) {
+            const float l = sum_across_halves(lsum[t]);
+            float* pr = pp + (long)(wave * (QT * 32) + t * 32 + col) * PART_STRIDE;
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    *reinterpret_cast<float4*>(pr + dt * 32 + g * 8 + half * 4) =
+                        make_float4(oacc[dt][t][g * 4], oacc[dt][t][g * 4 + 1], oacc[dt][t][g * 4 + 2],
+                                    oacc[dt][t][g * 4 + 3]);
+            if (half == 0) { pr[64] = l; pr[65] = mref[t]; }
+        }
+        return;
+    }
 #pragma unroll
     for (int t = 0; t < QT; ++t) {
         float l = sum_across_halves(lsum[t]);
@@ -450,282 +515,40 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
     }
 }
 
-// ------------------------------------------------------------ software-pipelined variant
-// Same mathematics as attn_mfma_kernel, restructured so that the matrix and vector work of
-// one wave are independent inside a loop body and the scheduler can interleave them.
-// The unit of work is (32-key sub-tile u, 32-query tile t); units are visited in the order
-// (u,0), (u,1), (u+1,0), ... and body w does
-//     PV(w)   O^T[.][t] += V^T(u) P^T(w)      (MFMA, P from the previous body)
-//     SM(w+1) P(w+1) = 2^(S(w+1) - r)          (vector: exp2, pack, row sum)
-//     QK(w+2) S(w+2) = K Q^T - r               (MFMA, consumed by the next body)
-// Units w and w+2 have the same t, so the score and probability registers of the two query
-// tiles are exactly the two pipeline slots.  The exponentials of one unit run under the
-// matrix instructions of its neighbours.
-// LDS stages hold 64 keys (two sub-tiles); a stage iteration (4 bodies) reads V of stage s
-// and K of stages s and s+1, so the ring has four stages and stage s+3 is requested while s
-// is consumed.  Global->LDS loads are issued from inline asm (the compiler then schedules
-// every LDS read, including the transposing ones, without waiting for loads in flight);
-// vmcnt waits and barriers below make each stage visible before it is read.
-// The reference r of a query moves only through the exact path (first sub-tile, a unit
-// whose row sums reveal a large exponent, and the careful tail).  Units of one query tile
-// are two bodies apart, so no look-ahead score ever has to be patched.
-__device__ __forceinline__ void lds_dma16(const void* gptr, unsigned lds_addr) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr)
-                 : "memory", "m0");
+// Split plan for the bf16 head-dim-64 kernel (see attn_mfma_kernel): how many work items run
+// whole, and how many ways the rest is split along the keys.
+struct AttnPlan { int qblocks, items, full, nsplit, pieces; };
+static int workgroup_slots() {
+    static int slots = 0;
+    if (slots == 0) {
+        int cus = 0, dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            cus = 256;
+        slots = 2 * cus;                      // two resident workgroups per CU
+    }
+    return slots;
 }
-
-template <bool PRESCALED>
-__global__ void __launch_bounds__(256, 2)
-attn_mfma_pipe_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
-                      bf16_t* __restrict__ o, int seq, int heads, float scale_log2e, int qblocks, AttnStrides s) {
-    constexpr int QT = 2;
-    constexpr int KV = 64;                       // keys per LDS stage
-    constexpr int BQ = 4 * QT * 32;
-    constexpr int NST = 4;
-    constexpr int STAGE = 2 * KV * 128;
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * STAGE];
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int col = lane & 31, half = lane >> 5;
-    int id = blockIdx.x;
-    {
-        int total = gridDim.x, per = total / 8, rem = total % 8, x = id % 8, j = id / 8;
-        id = x * per + (x < rem ? x : rem) + j;
-    }
-    const int bh = id / qblocks, qb = id % qblocks;
-    const int b = bh / heads, h = bh % heads;
-    const int q0 = qb * BQ + wave * (QT * 32);
-    const bf16_t* kbase = k + b * s.k_batch + h * s.k_head;
-    const bf16_t* vbase = v + b * s.v_batch + h * s.v_head;
-
-    bf16x8_t qf[QT][4];
-#pragma unroll
-    for (int t = 0; t < QT; ++t) {
-        int qi = q0 + t * 32 + col;
-        qi = qi < seq ? qi : seq - 1;
-        const bf16_t* qp = q + b * s.q_batch + (long)qi * s.q_tok + h * s.q_head;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-            qf[t][ks] = *reinterpret_cast<const bf16x8_t*>(qp + ks * 16 + half * 8);
-    }
-    f32x16_t oacc[2][QT];
-#pragma unroll
-    for (int d = 0; d < 2; ++d)
-#pragma unroll
-        for (int t = 0; t < QT; ++t)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) oacc[d][t][e] = 0.f;
-    float mref[QT], lsum[QT];
-    bf16x8_t qx[QT], kone;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) kone[e] = (__bf16)((e == 0 && half == 0) ? 1.0f : 0.0f);
-#pragma unroll
-    for (int t = 0; t < QT; ++t) {
-        mref[t] = 0.f; lsum[t] = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) qx[t][e] = (__bf16)0.0f;
-    }
-    const float cexp = PRESCALED ? 1.0f : scale_log2e;
-
-    // ---- staging (same layout and swizzles as attn_mfma_kernel)
-    const unsigned lds_base = (unsigned)(size_t)PS_LDS_PTR(lds);
-    const int lr = lane >> 3;
-    const int lc_v = (lane & 7) ^ lr;
-    auto issue = [&](int stage) {
-        const unsigned st = lds_base + (stage % NST) * STAGE;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            int g = wave + 4 * i;
-            int kr = stage * KV + g * 8 + lr;
-            kr = kr < seq ? kr : seq - 1;
-            const int lc_k = (lane & 7) ^ (((g & 1) << 2) | (lane >> 4));
-            lds_dma16(kbase + (long)kr * s.k_tok + lc_k * 8, __builtin_amdgcn_readfirstlane(st + g * 1024));
-            lds_dma16(vbase + (long)kr * s.v_tok + lc_v * 8, __builtin_amdgcn_readfirstlane(st + KV * 128 + g * 1024));
-        }
-    };
-    const int tg = lane >> 4, tj = lane & 15;
-    const int trow = 4 * (tg >> 1) + (tj >> 2);
-    const int tchunk = 2 * (tg & 1) + ((tj & 3) >> 1);
-    const int tsub = (tj & 1) * 8;
-    const int voff0 = KV * 128 + trow * 128 + ((tchunk ^ (trow & 7)) << 4) + tsub;
-    const int voff1 = KV * 128 + trow * 128 + (((4 + tchunk) ^ (trow & 7)) << 4) + tsub;
-    const int koff = col * 128;
-    const int ksw = (col >> 1) & 7;
-
-    f32x16_t sS[QT];                 // scores of the unit in flight for each query tile
-    bf16x8_t pP[QT][2];              // its probabilities (two k16-steps)
-
-    // ---- building blocks; t is a literal at every call site
-    auto qk = [&](int u, int t) {
-        const unsigned char* lk = lds + ((u >> 1) % NST) * STAGE + (u & 1) * 4096 + koff;
-        f32x16_t acc;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(lk + (((ks * 2 + half) ^ ksw) << 4));
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t][ks], acc, 0, 0, 0);
-        }
-        sS[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kone, qx[t], acc, 0, 0, 0);
-    };
-    auto pv = [&](int u, int t) {
-        const unsigned char* lv = lds + ((u >> 1) % NST) * STAGE + (u & 1) * 4096;
-#pragma unroll
-        for (int g = 0; g < 2; ++g)
-#pragma unroll
-            for (int dt = 0; dt < 2; ++dt) {
-                const unsigned char* pa = lv + (dt ? voff1 : voff0) + g * 2048;
-                bf16x4_t lo = lds_read_tr16(pa);
-                bf16x4_t hi = lds_read_tr16(pa + 1024);
-                bf16x8_t vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                oacc[dt][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pP[t][g], oacc[dt][t], 0, 0, 0);
-            }
-    };
-    // fast path: no maximum; returns the partial row sum (checked by the caller)
-    auto sm_fast = [&](int t) -> float {
-        float rs = 0.f;
-#pragma unroll
-        for (int g = 0; g < 2; ++g) {
-            bf16x8_t pk;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                float a = sS[t][g * 8 + e];
-                pk[e] = (__bf16)__builtin_amdgcn_exp2f(PRESCALED ? a : a * cexp);
-            }
-            pP[t][g] = pk;
-            rs = rowsum_bf16x8(pk, rs);
-        }
-        return rs;
-    };
-    // exact path on sS[t] (= s - r_old for `valid` keys): moves r to the row maximum (never
-    // down once something has been accumulated) and rescales the running sums of tile t
-    auto sm_exact = [&](int t, int valid, bool first, bool make_p) {
-        if (valid < 32) {
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                int key = 8 * (e >> 2) + 4 * half + (e & 3);
-                if (key >= valid) sS[t][e] = -INFINITY;
-            }
-        }
-        float mx = sS[t][0];
-#pragma unroll
-        for (int e = 1; e < 16; ++e) mx = fmaxf(mx, sS[t][e]);
-        mx = max_across_halves(mx);                        // finite: the sub-tile has a valid key
-        if (!first) mx = fmaxf(mx, 0.f);
-        const float rnew = (float)(__bf16)(mref[t] + mx);
-        const float d = rnew - mref[t];
-        if (!first) {
-            const float alpha = __builtin_amdgcn_exp2f(-d * cexp);
-            lsum[t] *= alpha;
-#pragma unroll
-            for (int dd = 0; dd < 2; ++dd)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) oacc[dd][t][e] *= alpha;
-        }
-        mref[t] = rnew;
-        qx[t][0] = (__bf16)(half == 0 ? -rnew : 0.0f);
-        if (make_p) {
-            float rs = 0.f;
-#pragma unroll
-            for (int g = 0; g < 2; ++g) {
-                bf16x8_t pk;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) pk[e] = (__bf16)__builtin_amdgcn_exp2f((sS[t][g * 8 + e] - d) * cexp);
-                pP[t][g] = pk;
-                rs = rowsum_bf16x8(pk, rs);
-            }
-            lsum[t] += rs;
-        } else {
-            // only re-base the scores; a later fast pass turns them into probabilities
-#pragma unroll
-            for (int e = 0; e < 16; ++e) sS[t][e] -= d;
-        }
-    };
-    // one pipeline body: PV(up, t) | SM(us, 1-t) | QK(uq, t)
-    auto body = [&](int up, int us, int uq, int t) {
-        pv(up, t);
-        const float rs = sm_fast(1 - t);
-        qk(uq, t);
-        if (__any(!(rs < 65536.0f))) {          // large or non-finite: redo that unit exactly
-            qk(us, 1 - t);
-            sm_exact(1 - t, 32, false, true);
-        } else {
-            lsum[1 - t] += rs;
-        }
-    };
-
-    const int U = (seq + 31) / 32;               // sub-tiles with at least one key
-    const int Ufull = seq / 32;                  // complete sub-tiles
-
-    issue(0); issue(1); issue(2);
-    asm volatile("s_waitcnt vmcnt(4)" ::: "memory");     // stages 0 and 1 landed
-    __syncthreads();
-    issue(3);
-    qk(0, 0);
-    qk(0, 1);
-    sm_exact(0, min(32, seq), true, true);
-    sm_exact(1, min(32, seq), true, false);
-    // entry state of a stage iteration s: pP[0] = P(2s,0), sS[1] = S(2s,1) - r
-
-    int sidx = 0;
-    for (; 2 * sidx + 3 <= Ufull; ++sidx) {      // touches sub-tiles 2s .. 2s+2, all complete
-        if (sidx > 0) {
-            // stages <= sidx+1 landed (sidx+2 may be in flight); nobody reads stage sidx-1 any
-            // more, whose buffer stage sidx+3 reuses
-            asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-            __syncthreads();
-            issue(sidx + 3);
-        }
-        const int u = 2 * sidx;
-        body(u, u, u + 1, 0);
-        body(u, u + 1, u + 1, 1);
-        body(u + 1, u + 1, u + 2, 0);
-        body(u + 1, u + 2, u + 2, 1);
-    }
-    // drain: P(2*sidx, 0) is pending, S(2*sidx, 1) is pending; the rest goes the careful way.
-    // Every stage the tail reads (at most sidx+1) was requested by the look-ahead.
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    {
-        const int u = 2 * sidx;
-        pv(u, 0);
-        qk(u, 1);
-        sm_exact(1, min(32, seq - 32 * u), false, true);
-        pv(u, 1);
-        for (int uu = u + 1; uu < U; ++uu) {
-            const int valid = min(32, seq - 32 * uu);
-            qk(uu, 0);
-            sm_exact(0, valid, false, true);
-            pv(uu, 0);
-            qk(uu, 1);
-            sm_exact(1, valid, false, true);
-            pv(uu, 1);
-        }
-    }
-
-#pragma unroll
-    for (int t = 0; t < QT; ++t) {
-        float l = sum_across_halves(lsum[t]);
-        float inv = 1.0f / l;
-        int qi = q0 + t * 32 + col;
-        if (qi < seq) {
-            bf16_t* op = o + b * s.o_batch + (long)qi * s.o_tok + h * s.o_head;
-#pragma unroll
-            for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    bf16x4_t w;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) w[e] = (__bf16)(oacc[dt][t][g * 4 + e] * inv);
-                    *reinterpret_cast<bf16x4_t*>(op + dt * 32 + g * 8 + half * 4) = w;
-                }
-        }
-    }
+static AttnPlan attention_plan(int batch, int seq, int heads) {
+    constexpr int BQ = 256, KV = 64;
+    AttnPlan p;
+    p.qblocks = (seq + BQ - 1) / BQ;
+    p.items = p.qblocks * heads * batch;
+    const int slots = workgroup_slots();
+    const int tail = p.items % slots;
+    const int ntiles = (seq + KV - 1) / KV;
+    int ns = tail > 0 ? slots / tail : 1;
+    if (ns > 8) ns = 8;
+    if (ns > ntiles / 2) ns = ntiles / 2;
+    if (tail == 0 || p.items < slots || ns < 2) { p.full = p.items; p.nsplit = 1; p.pieces = 0; }
+    else { p.full = p.items - tail; p.nsplit = ns; p.pieces = tail * ns; }
+    return p;
 }
 
 size_t attention_workspace_bytes(int dtype, int batch, int seq, int heads, int head_dim) {
-    (void)dtype; (void)batch; (void)seq; (void)heads; (void)head_dim;
-    return 0;
+    if (dtype != PS_BF16 || head_dim != 64 || batch < 1 || seq < 1 || heads < 1) return 0;
+    AttnPlan p = attention_plan(batch, seq, heads);
+    return (size_t)p.pieces * 256 * PART_STRIDE * sizeof(float);
 }
 
 bool attention_uses_mfma(int dtype, int head_dim) {
@@ -735,23 +558,27 @@ bool attention_uses_mfma(int dtype, int head_dim) {
 hipError_t launch_attention(int dtype, const void* q, const void* k, const void* v, void* o,
                             int batch, int seq, int heads, int head_dim, float scale,
                             const AttnStrides& s, void* ws, hipStream_t st, bool q_prescaled) {
-    (void)ws;
     if (attention_uses_mfma(dtype, head_dim)) {
         constexpr int QT = 2;
-        constexpr int BQ = 4 * QT * 32;
-        int qblocks = (seq + BQ - 1) / BQ;
-        dim3 grid(qblocks * heads * batch);
+        AttnPlan p = attention_plan(batch, seq, heads);
+        if (p.pieces > 0 && (ws == nullptr || get_kernel_path() == 2)) { p.full = p.items; p.nsplit = 1; p.pieces = 0; }
+        dim3 grid(p.full + p.pieces);
         const float c = scale * 1.4426950408889634f;
-        const bool pipe = get_kernel_path() == 2;   // the software-pipelined variant is opt-in
         const bf16_t *qq = (const bf16_t*)q, *kk = (const bf16_t*)k, *vv = (const bf16_t*)v;
-        if (pipe && q_prescaled)
-            attn_mfma_pipe_kernel<true><<<grid, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c, qblocks, s);
-        else if (pipe)
-            attn_mfma_pipe_kernel<false><<<grid, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c, qblocks, s);
-        else if (q_prescaled)
-            attn_mfma_kernel<QT, true><<<grid, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c, qblocks, s);
+        float* part = (float*)ws;
+        if (q_prescaled)
+            attn_mfma_kernel<QT, true><<<grid, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c, p.qblocks, s, p.full,
+                                                             p.nsplit, part);
         else
-            attn_mfma_kernel<QT, false><<<grid, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c, qblocks, s);
+            attn_mfma_kernel<QT, false><<<grid, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c, p.qblocks, s, p.full,
+                                                              p.nsplit, part);
+        hipError_t err = hipGetLastError();
+        if (err != hipSuccess || p.pieces == 0) return err;
+        const int nitems = p.items - p.full;
+        const long threads = (long)nitems * 256 * 16;
+        attn_merge_kernel<<<(unsigned)((threads + 255) / 256), 256, 0, st>>>(part, (bf16_t*)o, seq, heads, p.qblocks,
+                                                                            p.full, p.nsplit, nitems,
+                                                                            q_prescaled ? 1.0f : c, 256, s);
         return hipGetLastError();
     }
     if (q_prescaled) return hipErrorInvalidValue;     // only the MFMA kernel takes pre-scaled queries
