@@ -120,14 +120,15 @@ PS_API int attn3d(const void* q, const void* k, const void* v, void* o,
 
 /* The projection every DiT sub-layer uses, exposed for per-kernel parity and timing:
  * out[M, n_out] = act(a[M, k] * w[n_out, k]^T + bias), act 0 = none, 1 = tanh-GELU.
- * a, w, out DEVICE in `dtype`, row-major, 16-byte aligned; bias DEVICE fp32 [n_out].
+ * a, w, out DEVICE in `dtype`, row-major, 16-byte aligned; bias DEVICE fp32 [n_out],
+ * 16-byte aligned.
  * n_out even, k % 8 == 0. */
 PS_API int dit_linear(const void* a, const void* w, const float* bias, void* out, int m, int n_out, int k,
                int act, int dtype, void* hip_stream);
 
 /* Test and tuning hook: 0 = pick the fastest kernel for each shape (default), 1 = always
  * use the generic fp32-FMA kernels, 2 = bf16 attention without the key-split of its last
- * partial round of workgroups, 0x100|v = force tile variant v (1..6) of the bf16 MFMA GEMM.  Process-wide;
+ * partial round of workgroups, 0x100|v = force tile variant v of the bf16 MFMA GEMM (1: 256x256, 2: 128x128).  Process-wide;
  * returns the previous value. */
 PS_API int ps_set_kernel_path(int path);
 

@@ -352,7 +352,8 @@ int dit_linear(const void* a, const void* w, const float* bias, void* out, int m
     if (!a || !w || !bias || !out) return PS_ERR_NULL;
     if (dtype != PS_F32 && dtype != PS_BF16) return PS_ERR_DTYPE;
     if (m < 1 || n_out < 2 || k < 8 || (n_out & 1) || (k % 8) || (act != 0 && act != 1)) return PS_ERR_SHAPE;
-    if (!aligned(a, 16) || !aligned(w, 16) || !aligned(out, 16) || out == a || out == w) return PS_ERR_SHAPE;
+    if (!aligned(a, 16) || !aligned(w, 16) || !aligned(out, 16) || !aligned(bias, 16) || out == a || out == w)
+        return PS_ERR_SHAPE;
     Epilogue ep{};
     ep.kind = act ? EPI_BIAS_GELU : EPI_BIAS;
     ep.bias = bias;

@@ -164,13 +164,17 @@ __device__ __forceinline__ float sum_across_halves(float v) {
 // Softmax bookkeeping.  Every query keeps a reference value r (bf16-representable) and the
 // kernel accumulates sum_j 2^(c(s_j - r)) v_j and sum_j 2^(c(s_j - r)); any r gives the same
 // quotient, so r is only moved when it has to be:
-//  * the subtraction s - r costs no vector instruction: a fifth k16-step of the QK^T MFMA
-//    multiplies a constant "1" slot of the K operand with -r stored in the Q operand;
+//  * r starts at 0 and stays there while the exponents c*s of the first tile peak within
+//    +-32 and no later tile's sum of 2^(c(s - r)) reaches 2^64 (fp32 sums stay far from
+//    overflow, and a row whose maximum is >= -32 cannot sum to zero);
+//  * once some query of a wave has r != 0, the subtraction s - r still costs no vector
+//    instruction: a fifth k16-step of the QK^T MFMA multiplies a constant "1" slot of the K
+//    operand with -r stored in the Q operand (skipped while every r of the wave is 0);
 //  * a tile goes through the fast path -- exp2, pack to bf16, row sum with v_dot2c on the
 //    packed pairs -- without looking for its maximum; the partial row sums tell whether any
-//    2^(c(s - r)) was large (>= 2^16) or overflowed, and only then (and on the first and
-//    on a ragged last tile) the tile is redone through the exact path: true row maximum,
-//    new r, rescale of the running sums.
+//    2^(c(s - r)) was large or overflowed, and only then (and on the first and on a ragged
+//    last tile) the tile is redone through the exact path: true row maximum, new r, rescale
+//    of the running sums.
 // PRESCALED: q already carries the factor c = scale*log2(e) (the QKV projection applies it
 // in fp32 before rounding), so p = exp2(acc) with no multiply; otherwise p = exp2(c*acc).
 static constexpr int PART_STRIDE = 68;      // floats per row of a partial result (64 + l + r, padded to 16 B)
@@ -290,6 +294,12 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
         for (int e = 0; e < 8; ++e) qx[t][e] = (__bf16)0.0f;
     }
     const float cexp = PRESCALED ? 1.0f : scale_log2e;
+    // Exponents are taken relative to a per-query reference r that stays 0 as long as the scores
+    // (in log2 units) of the first tile peak within +-REF_WINDOW and no later tile's sum of
+    // 2^(s - r) reaches REF_SUM_LIMIT: fp32 sums over any sequence this kernel accepts stay far
+    // from overflow, and a row whose maximum is >= -REF_WINDOW cannot underflow to a zero sum.
+    constexpr float REF_WINDOW = 32.0f, REF_SUM_LIMIT = 0x1p+64f;
+    bool has_ref = false;                        // wave-uniform: some query of this wave has r != 0
 
     // direct global->LDS loads: a wave instruction fills 8 rows of 128 bytes (lane j lands
     // at base + 16j), so the XOR swizzles are applied on the global side.  LDS has 64
@@ -363,12 +373,14 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
                         sacc[rt][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t][ks], sacc[rt][t], 0, 0, 0);
                 }
             }
-            // reference step: sacc -= r (per query column)
+            // reference step: sacc -= r (per query column); skipped while every reference of the wave is 0
+            if (has_ref) {
 #pragma unroll
-            for (int rt = 0; rt < 2; ++rt)
+                for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-                for (int t = 0; t < QT; ++t)
-                    sacc[rt][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kone, qx[t], sacc[rt][t], 0, 0, 0);
+                    for (int t = 0; t < QT; ++t)
+                        sacc[rt][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kone, qx[t], sacc[rt][t], 0, 0, 0);
+            }
         };
         // V^T fragments: issued now, consumed after the softmax
         i32x2_t vfr[16];
@@ -397,7 +409,7 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
                         rs = rowsum_bf16x8(pk, rs);
                     }
                 // large or non-finite partial sum: some exponent was far above the reference
-                redo = redo || !(rs < 65536.0f);
+                redo = redo || !(rs < REF_SUM_LIMIT);
                 rsv[t] = rs;
             }
             redo = __any(redo);
@@ -408,6 +420,7 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
         }
         if (redo) {
             scores();
+            bool moved = false;
             if (ragged) {
 #pragma unroll
                 for (int rt = 0; rt < 2; ++rt)
@@ -430,7 +443,10 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
                 for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[1][t][e]);
                 mx = max_across_halves(mx);                       // finite: every tile has a valid key
                 if (j > jt0) mx = fmaxf(mx, 0.f);                 // the reference never moves down
+                // first tile: keep the reference at 0 while the maximum is within 2^+-REF_WINDOW of it
+                if (j == jt0 && fabsf(mx * cexp) <= REF_WINDOW) mx = 0.f;
                 const float rnew = (float)(__bf16)(mref[t] + mx); // new reference, bf16-representable
+                moved = moved || rnew != 0.f;
                 const float d = rnew - mref[t];
                 if (j > jt0) {
                     const float alpha = __builtin_amdgcn_exp2f(-d * cexp);
@@ -456,6 +472,7 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
                     }
                 lsum[t] += rs;
             }
+            has_ref = has_ref || __any(moved);
         }
         // O^T[d tile][query tile] += V^T[d tile][keys] P^T[keys][queries]
         // k-slot (half, e) of step st is key 16st + 8(e/4) + 4half + e%4

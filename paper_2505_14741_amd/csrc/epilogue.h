@@ -48,10 +48,4 @@ __device__ __forceinline__ void epilogue_pair(const Epilogue& ep, T* __restrict_
     }
 }
 
-// swap a value between lanes 2i and 2i+1 (DPP quad_perm [1,0,3,2])
-__device__ __forceinline__ float swap_adjacent_lanes(float v) {
-    int r = __builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, false);
-    return __int_as_float(r);
-}
-
 }  // namespace ps

@@ -1,12 +1,13 @@
 // bf16 MFMA GEMM for gfx950:  C[M, Nn] = A[M, K] * W[Nn, K]^T, fp32 accumulate, fused epilogue.
 //
 // Both operands are K-contiguous, so each lane's MFMA fragment (8 consecutive k of one
-// row) is a single 16-byte LDS read.  One workgroup per CU computes a BM x BN tile with
-// WR x WC waves, every wave owning (BM/WR) x (BN/WC) outputs as 32x32
-// v_mfma_f32_32x32x16_bf16 tiles.  K is consumed 64 at a time through a two-stage LDS ring
-// filled by direct global->LDS loads (global_load_lds_dwordx4: no staging registers, no
-// ds_write): the loads of slice k+1 are in flight while slice k is multiplied, one
-// barrier per slice.
+// row) is a single 16-byte LDS read.  A workgroup computes a BM x BN tile with WR x WC
+// waves, every wave owning (BM/WR) x 64 outputs as 32x32 v_mfma_f32_32x32x16_bf16 tiles.
+// K is consumed 64 at a time through a two-stage LDS ring filled by direct global->LDS
+// loads (global_load_lds_dwordx4: no staging registers, no ds_write): the loads of slice
+// k+1 are in flight while slice k is multiplied, one barrier per slice.  Fragments are
+// double-buffered in registers, each LDS read issued in the shadow of an MFMA of the
+// previous 16-deep step.
 //
 // LDS rows are 128 bytes (64 bf16).  A direct load writes lane j's 16 bytes at
 // base + 16*j, so one wave instruction fills 8 rows.  LDS has 64 four-byte banks and a
@@ -16,13 +17,15 @@
 // swizzle is applied on the global side: lane j of row group g fetches chunk
 // (j%8) ^ (4*(g%2) + j/16) of row 8g + j/8.
 //
-// Output mapping of the 32x32 accumulator: lane l holds column l%32 and rows
-// 8*(i/4) + 4*(l/32) + i%4 for i < 16; activations are the row operand, so a lane's
-// column is an output feature and stores of one accumulator register are contiguous
-// across lanes (bf16 stores cover 64 bytes per row, fp32 residual updates 128).  The
-// rotary epilogue gets a pair's other element from the neighbouring lane with one DPP move.
+// Epilogue: the 32x32 accumulator gives lane l column l%32 and rows 8*(i/4) + 4*(l/32) + i%4,
+// which would make every store a 2-byte scatter.  Each wave instead passes its tiles, 32 rows
+// x 64 columns at a time, through a private LDS patch (row stride 72 floats: conflict-free
+// both ways) and reads them back row-contiguous, 4 consecutive columns per lane and 16
+// lanes per row.  Bias, GELU, the gated residual update and the rotary rotation then work
+// on 16-byte pieces: one 8-byte bf16 store (or 16-byte fp32 store) per 4 outputs, whole
+// 128-byte lines per row, the residual / rotary-table operands fetched as 16- / 8-byte loads
+// one 32-row strip ahead.
 #include "common.h"
-#include "epilogue.h"
 
 namespace ps {
 
@@ -49,108 +52,128 @@ __device__ __forceinline__ float gelu_fast(float x) {
     return x * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(t));
 }
 
-__device__ __forceinline__ unsigned short bf16_bits(float v) {
-    return __builtin_bit_cast(unsigned short, (__bf16)v);
-}
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
 
-// Residual values of one wave's outputs, requested before the main loop so that the
-// read-modify-write epilogue finds them in registers (rows past M re-read the last row).
-template <int TM, int TN>
-struct ResidualPrefetch {
-    float x[TM][TN][16];
-};
-template <int TM, int TN>
-__device__ __forceinline__ void prefetch_residual(ResidualPrefetch<TM, TN>& rp, const float* __restrict__ X, int M,
-                                                  int Nn, int row0, int col0) {
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        int col = col0 + j * 32;
-        col = col < Nn ? col : Nn - 1;
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                int m = row0 + i * 32 + 8 * (e >> 2) + (e & 3);
-                m = m < M ? m : M - 1;
-                rp.x[i][j][e] = X[(unsigned)(m * Nn + col)];
-            }
-    }
-}
+constexpr int EPI_LDS_STRIDE = 72;                       // floats per row of a wave's 32 x 64 patch
+constexpr int EPI_LDS_FLOATS = 32 * EPI_LDS_STRIDE;
 
-// Writes the TM x TN accumulator tiles of one wave.  row0/col0: first row (incl. the
-// lane's 4*half offset) and the lane's column of tile (0,0).  Offsets are 32-bit element
-// indices from the uniform base pointers (the launcher guarantees M*Nn < 2^31).
-template <int TM, int TN, int KIND, bool CHECK>
-__device__ __forceinline__ void tile_epilogue(f32x16_t (&acc)[TM][TN], const Epilogue& ep, bf16_t* __restrict__ C,
-                                              int M, int Nn, int row0, int col0, int lane,
-                                              const ResidualPrefetch<TM, TN>* rp) {
-    unsigned short* __restrict__ Cb = reinterpret_cast<unsigned short*>(C);
+// Epilogue of one wave: TM strips of 32 rows x 64 columns.  wrow0 / wcol0: first row and
+// column of the wave's outputs; patch: the wave's private LDS area (EPI_LDS_FLOATS floats).
+// Offsets are 32-bit element indices from the uniform base pointers (the launcher
+// guarantees M*Nn < 2^31); Nn % 4 == 0, so a lane's 4 columns are inside or outside together.
+template <int TM, int KIND, bool CHECK>
+__device__ __forceinline__ void wave_epilogue(f32x16_t (&acc)[TM][2], const Epilogue& ep, bf16_t* __restrict__ C,
+                                              int M, int Nn, int wrow0, int wcol0, int lane, float* patch) {
+    const int frow = lane & 31, fhalf = lane >> 5;       // accumulator side: column, row offset 4*fhalf
+    const int rr = lane >> 4, cc = (lane & 15) * 4;      // row-contiguous side: row within 4, first column
+    const int col = wcol0 + cc;
+    const bool col_ok = !CHECK || col < Nn;
+    const int colc = col_ok ? col : 0;
+    const f32x4_t bias = *reinterpret_cast<const f32x4_t*>(ep.bias + colc);
     const int tokens = ep.geom.tokens, text = ep.geom.text_tokens;
+    // batch index of the wave's rows: one division per wave when they share it (the usual case)
+    const int row_last = min(wrow0 + TM * 32, M) - 1;
+    const int b_first = min(wrow0, M - 1) / tokens;      // (a wave of an edge tile may lie entirely past M)
+    const bool one_batch = row_last / tokens == b_first;
+    auto token_of = [&](int m, int& b) {
+        b = one_batch ? b_first : m / tokens;
+        return m - b * tokens;
+    };
+
+    // per-kind lane constants
+    f32x4_t gate_v = {0.f, 0.f, 0.f, 0.f}, gate_t = gate_v;
+    bool rot = false;
+    int pr = 0;
+    float qs = 1.0f;
+    if constexpr (KIND == EPI_GATE_RESIDUAL) {
+        const float* g = ep.mod_layer + b_first * ep.mod_batch_stride + colc;
+        gate_v = *reinterpret_cast<const f32x4_t*>(g + ep.gate_chunk * ep.D);
+        gate_t = *reinterpret_cast<const f32x4_t*>(g + (ep.gate_chunk + 6) * ep.D);
+    }
+    if constexpr (KIND == EPI_QKV_ROPE) {
+        rot = col < 2 * ep.D;                            // q and k columns rotate, v columns do not
+        pr = (colc % ep.head_dim) >> 1;                  // first of the lane's two (even, odd) pairs
+        qs = col < ep.D ? ep.q_scale : 1.0f;
+    }
+
+    // operands the strip needs from memory besides the accumulators (one 16-byte value per
+    // 4 outputs): the residual, or (cos, cos, sin, sin) of the two pairs
+    auto fetch = [&](int i, int k) -> f32x4_t {
+        int m = wrow0 + i * 32 + 4 * k + rr;
+        if (CHECK) m = m < M ? m : M - 1;
+        if constexpr (KIND == EPI_GATE_RESIDUAL) {
+            return *reinterpret_cast<const f32x4_t*>(ep.resid + (unsigned)(m * Nn + colc));
+        } else if constexpr (KIND == EPI_QKV_ROPE) {
+            int b;
+            const int n = token_of(m, b);
+            f32x4_t r = {1.f, 1.f, 0.f, 0.f};
+            if (rot && n >= text) {
+                const unsigned ti = (unsigned)((n - text) * (ep.head_dim >> 1) + pr);
+                const f32x2_t cs = *reinterpret_cast<const f32x2_t*>(ep.rope_cos + ti);
+                const f32x2_t sn = *reinterpret_cast<const f32x2_t*>(ep.rope_sin + ti);
+                r = {cs[0], cs[1], sn[0], sn[1]};
+            }
+            return r;
+        } else {
+            return f32x4_t{0.f, 0.f, 0.f, 0.f};
+        }
+    };
+    constexpr bool FETCHES = KIND == EPI_GATE_RESIDUAL || KIND == EPI_QKV_ROPE;
+
+    f32x4_t pf[8];                                       // refilled for the next strip as soon as a value is used
+    if constexpr (FETCHES) {
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int col = col0 + j * 32;
-        if (CHECK && col >= Nn) continue;
-        const float bias = ep.bias[col];
+        for (int k = 0; k < 8; ++k) pf[k] = fetch(0, k);
+    }
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int rb = row0 + i * 32;
-            if constexpr (KIND == EPI_BIAS || KIND == EPI_BIAS_GELU) {
+    for (int i = 0; i < TM; ++i) {
+        // accumulators -> patch (a store instruction covers 2 rows x 32 columns: 64 banks)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int m = rb + 8 * (e >> 2) + (e & 3);
-                    if (CHECK && m >= M) continue;
-                    float v = acc[i][j][e] + bias;
-                    if constexpr (KIND == EPI_BIAS_GELU) v = gelu_fast(v);
-                    Cb[(unsigned)(m * Nn + col)] = bf16_bits(v);
-                }
-            } else if constexpr (KIND == EPI_GATE_RESIDUAL) {
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                patch[(8 * (e >> 2) + 4 * fhalf + (e & 3)) * EPI_LDS_STRIDE + j * 32 + frow] = acc[i][j][e];
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // LDS is in order per wave; this pins the compiler too
+        f32x4_t v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            v[k] = *reinterpret_cast<const f32x4_t*>(patch + (4 * k + rr) * EPI_LDS_STRIDE + cc);
+        asm volatile("" ::: "memory");
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int m = wrow0 + i * 32 + 4 * k + rr;
+            f32x4_t x = v[k] + bias;
+            f32x4_t t = {0.f, 0.f, 0.f, 0.f};
+            if constexpr (FETCHES) {
+                t = pf[k];
+                if (i + 1 < TM) pf[k] = fetch(i + 1, k);
+            }
+            if constexpr (KIND == EPI_BIAS_GELU) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) x[c] = gelu_fast(x[c]);
+            }
+            if constexpr (KIND == EPI_QKV_ROPE) {
+                // t = (cos0, cos1, sin0, sin1); identity for text tokens and v columns
+                x = f32x4_t{x[0] * t[0] - x[1] * t[2], x[1] * t[0] + x[0] * t[2],
+                            x[2] * t[1] - x[3] * t[3], x[3] * t[1] + x[2] * t[3]} * qs;
+            }
+            if (CHECK && (m >= M || !col_ok)) continue;
+            const unsigned off = (unsigned)(m * Nn + col);
+            if constexpr (KIND == EPI_GATE_RESIDUAL) {
                 // X[m, col] += gate[batch(m), stream(m), col] * (acc + bias)
-                const int b_lo = rb / tokens, b_hi = (rb + 27) / tokens;
-                if (b_lo == b_hi) {
-                    const float* g = ep.mod_layer + b_lo * ep.mod_batch_stride + col;
-                    const float gv = g[ep.gate_chunk * ep.D], gt = g[(ep.gate_chunk + 6) * ep.D];
-                    const int n0r = rb - b_lo * tokens;
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        const int dr = 8 * (e >> 2) + (e & 3);
-                        const int m = rb + dr;
-                        if (CHECK && m >= M) continue;
-                        const float gate = (n0r + dr) < text ? gt : gv;
-                        const unsigned off = (unsigned)(m * Nn + col);
-                        ep.resid[off] = rp->x[i][j][e] + gate * (acc[i][j][e] + bias);
-                    }
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        const int m = rb + 8 * (e >> 2) + (e & 3);
-                        if (CHECK && m >= M) continue;
-                        const int b = m / tokens, n = m - b * tokens;
-                        const int chunk = ep.gate_chunk + (n < text ? 6 : 0);
-                        const float gate = ep.mod_layer[b * ep.mod_batch_stride + (long)chunk * ep.D + col];
-                        const unsigned off = (unsigned)(m * Nn + col);
-                        ep.resid[off] = rp->x[i][j][e] + gate * (acc[i][j][e] + bias);
-                    }
+                int b;
+                const int n = token_of(m, b);
+                f32x4_t gate = n < text ? gate_t : gate_v;
+                if (!one_batch) {
+                    const float* g = ep.mod_layer + b * ep.mod_batch_stride + col;
+                    gate = *reinterpret_cast<const f32x4_t*>(g + (ep.gate_chunk + (n < text ? 6 : 0)) * ep.D);
                 }
-            } else {   // EPI_QKV_ROPE: rotate (even, odd) column pairs of q and k of video tokens
-                const bool rot = col < 2 * ep.D;
-                const int pr = (col % ep.head_dim) >> 1;
-                const int hd2 = ep.head_dim >> 1;
-                const bool odd = lane & 1;
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int m = rb + 8 * (e >> 2) + (e & 3);
-                    float v = acc[i][j][e] + bias;
-                    const float partner = swap_adjacent_lanes(v);      // before any divergence
-                    if (CHECK && m >= M) continue;
-                    const int n = m % tokens;
-                    if (rot && n >= text) {
-                        const unsigned ti = (unsigned)((n - text) * hd2 + pr);
-                        const float cs = ep.rope_cos[ti], sn = ep.rope_sin[ti];
-                        v = odd ? (v * cs + partner * sn) : (v * cs - partner * sn);
-                    }
-                    if (col < ep.D) v *= ep.q_scale;
-                    Cb[(unsigned)(m * Nn + col)] = bf16_bits(v);
-                }
+                *reinterpret_cast<f32x4_t*>(ep.resid + off) = t + gate * x;
+            } else {
+                *reinterpret_cast<bf16x4_t*>(reinterpret_cast<unsigned short*>(C) + off) =
+                    __builtin_convertvector(x, bf16x4_t);
             }
         }
     }
@@ -169,26 +192,24 @@ __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-// BK: K depth of an LDS stage (64 or 32 bf16 = 128- or 64-byte rows); NST: ring depth.
-// Stage kt+NST-1 is requested while stage kt is multiplied.
-template <int BM, int BN, int WR, int WC, int BK, int NST, int KIND>
+// One BM x BN output tile per workgroup, WR x WC waves of (BM/WR) x 64 outputs each.
+template <int BM, int BN, int WR, int WC, int KIND>
 __global__ void __launch_bounds__(WR * WC * 64, (WR * WC == 4 && BM * BN <= 128 * 128) ? 2 : 1)
 gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf16_t* __restrict__ C,
                  int M, int Nn, int K, int tiles_m, int tiles_n, Epilogue ep) {
-    static_assert(BK == 64 || BK == 32, "stage depth");
+    constexpr int BK = 64, KS = BK / 16;
     constexpr int NW = WR * WC;
     constexpr int WM = BM / WR, WN = BN / WC;
     constexpr int TM = WM / 32, TN = WN / 32;
     constexpr int ROWB = BK * 2;                         // bytes per LDS row
-    constexpr int RPI = 1024 / ROWB;                     // rows filled by one wave instruction (8 or 16)
-    constexpr int CPR = ROWB / 16;                       // 16-byte chunks per row (8 or 4)
-    constexpr int GROUPS = (BM + BN) / RPI;
+    constexpr int GROUPS = (BM + BN) / 8;                // one wave instruction fills 8 rows
     constexpr int GPW = GROUPS / NW;                     // load instructions per wave per stage
     constexpr int STAGE = (BM + BN) * ROWB;
+    static_assert(TN == 2, "the epilogue handles strips of 64 columns per wave");
     static_assert(GROUPS % NW == 0, "rows must split evenly over waves");
-    static_assert(BM % RPI == 0, "a load group must not straddle the A/W boundary");
-    static_assert((NST - 1) * GPW <= 63, "vmcnt range");
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * STAGE];
+    static_assert(BM % 8 == 0, "a load group must not straddle the A/W boundary");
+    static_assert(NW * EPI_LDS_FLOATS * 4 <= 2 * STAGE, "epilogue patches reuse the stage memory");
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * STAGE];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -206,18 +227,15 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
         n0 = (in_band / rows_here) * BN;
     }
 
-    // Swizzle (LDS has 64 four-byte banks; a 16-byte fragment read is served 16 lanes = 16
-    // consecutive rows at a time, which must hit 16 different 16-byte bank groups):
-    //   128-byte rows: slot p of row r holds chunk p ^ ((r>>1)&7)
-    //    64-byte rows: slot p of row r holds chunk p ^ ((r>>2)&3)
-    // applied on the global side of the direct load (lane j lands at base + 16j).
-    const int lr = lane / CPR;                           // row inside the load group
+    // direct loads: lane j of load group g lands at group base + 16j = row 8g + j/8, slot j%8;
+    // the slot holds chunk (j%8) ^ ((row>>1)&7) of the row (swizzle applied on the global side)
+    const int lr = lane >> 3;
     const bf16_t* gp[GPW];
 #pragma unroll
     for (int i = 0; i < GPW; ++i) {
         const int g = wave + NW * i;
-        const int row = g * RPI + lr;                    // row within [A rows | W rows]
-        const int lc = BK == 64 ? ((lane & 7) ^ ((row >> 1) & 7)) : ((lane & 3) ^ ((row >> 2) & 3));
+        const int row = g * 8 + lr;                      // row within [A rows | W rows]
+        const int lc = (lane & 7) ^ ((row >> 1) & 7);
         if (row < BM) {
             int r = m0 + row;
             r = r < M ? r : M - 1;
@@ -232,7 +250,7 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
     const int nk = K / BK;
     auto issue = [&](int kt) {
         const int kc = kt < nk ? kt : nk - 1;            // past the end: harmless re-read keeps vmcnt uniform
-        const unsigned st = lds_base + (kt % NST) * STAGE;
+        const unsigned st = lds_base + (kt & 1) * STAGE;
 #pragma unroll
         for (int i = 0; i < GPW; ++i) {
             const int g = wave + NW * i;
@@ -254,69 +272,88 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
     for (int i = 0; i < TM; ++i) aoff[i] = (wm * WM + i * 32 + frow) * ROWB;
 #pragma unroll
     for (int j = 0; j < TN; ++j) boff[j] = (BM + wn * WN + j * 32 + frow) * ROWB;
-    const int sw = BK == 64 ? ((frow >> 1) & 7) : ((frow >> 2) & 3);
+    const int sw = (frow >> 1) & 7;
 
-    // the residual read-modify-write epilogue gets its inputs now: these loads are older than
-    // every stage load, so the first stage wait also covers them and they cost one memory
-    // latency per tile instead of one per output row
-    ResidualPrefetch<TM, TN> rp;
-    if constexpr (KIND == EPI_GATE_RESIDUAL)
-        prefetch_residual<TM, TN>(rp, ep.resid, M, Nn, m0 + wm * WM + 4 * fhalf, n0 + wn * WN + frow);
+    // Fragments are double-buffered in registers: the LDS reads of k-step s+1 are issued among
+    // the MFMAs of step s, and the reads of the next stage's first step follow the one barrier
+    // per stage, which sits in front of the last step's MFMAs (those already have their
+    // operands, so the matrix pipe keeps running while the stage hand-over completes).
+    bf16x8_t fa[2][TM], fb[2][TN];
+    auto load_frags = [&](int buf, const unsigned char* st, int ks) {
+        const int slot = ((ks * 2 + fhalf) ^ sw) << 4;
 #pragma unroll
-    for (int p = 0; p < NST - 1; ++p) issue(p);
+        for (int i = 0; i < TM; ++i) fa[buf][i] = *reinterpret_cast<const bf16x8_t*>(st + aoff[i] + slot);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[buf][j] = *reinterpret_cast<const bf16x8_t*>(st + boff[j] + slot);
+    };
+    issue(0);
+    wait_vmcnt<0>();
+    __syncthreads();
+    issue(1);
+    load_frags(0, lds, 0);
     for (int kt = 0; kt < nk; ++kt) {
-        // stage kt has landed once at most the NST-2 younger stages are still in flight
-        wait_vmcnt<(NST - 2) * GPW>();
-        __syncthreads();                                 // ... for every wave; and stage kt-1 is no longer read
-        issue(kt + NST - 1);                             // into the buffer stage kt-1 occupied
-        const unsigned char* st = lds + (kt % NST) * STAGE;
+        const unsigned char* st = lds + (kt & 1) * STAGE;
+        const unsigned char* nx = lds + ((kt + 1) & 1) * STAGE;
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8_t fa[TM], fb[TN];
-            const int slot = ((ks * 2 + fhalf) ^ sw) << 4;
-#pragma unroll
-            for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const bf16x8_t*>(st + aoff[i] + slot);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) fb[j] = *reinterpret_cast<const bf16x8_t*>(st + boff[j] + slot);
+        for (int ks = 0; ks < KS; ++ks) {
+            if (ks + 1 < KS) {
+                load_frags((ks + 1) & 1, st, ks + 1);
+            } else {
+                wait_vmcnt<0>();                         // own share of stage kt+1 has landed
+                __syncthreads();                         // ... everyone's; and stage kt is in registers everywhere
+                issue(kt + 2);                           // into the buffer stage kt occupied
+                load_frags((ks + 1) & 1, nx, 0);
+                __builtin_amdgcn_sched_barrier(0);       // hand-over code stays ahead of the MFMAs
+            }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
+            if (ks + 1 < KS) {
+                // one LDS read in the shadow of each MFMA, then the remaining MFMAs
+#pragma unroll
+                for (int r = 0; r < TM + TN; ++r) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - TM - TN > 0 ? TM * TN - TM - TN : 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
-    wait_vmcnt<0>();                                     // drain the look-ahead loads before the wave ends
+    wait_vmcnt<0>();                                     // the look-ahead loads past the end have landed
+    __syncthreads();                                     // ... in every wave: the stage memory is free
 
-    // epilogue: a lane owns one output column (feature) of each 32x32 tile and 16 of its rows
+    float* patch = reinterpret_cast<float*>(lds) + wave * EPI_LDS_FLOATS;
     const bool interior = (m0 + BM <= M) && (n0 + BN <= Nn);
     if (interior)
-        tile_epilogue<TM, TN, KIND, false>(acc, ep, C, M, Nn, m0 + wm * WM + 4 * fhalf, n0 + wn * WN + frow, lane, &rp);
+        wave_epilogue<TM, KIND, false>(acc, ep, C, M, Nn, m0 + wm * WM, n0 + wn * WN, lane, patch);
     else
-        tile_epilogue<TM, TN, KIND, true>(acc, ep, C, M, Nn, m0 + wm * WM + 4 * fhalf, n0 + wn * WN + frow, lane, &rp);
+        wave_epilogue<TM, KIND, true>(acc, ep, C, M, Nn, m0 + wm * WM, n0 + wn * WN, lane, patch);
 }
 
 bool gemm_mfma_supported(int M, int Nn, int K) {
-    return K % 64 == 0 && Nn % 2 == 0 && M >= 1 && Nn >= 64 && K >= 64 && (long)M * Nn < (1L << 31);
+    return K % 64 == 0 && Nn % 4 == 0 && M >= 1 && Nn >= 64 && K >= 64 && (long)M * Nn < (1L << 31);
 }
 
-template <int BM, int BN, int WR, int WC, int BK, int NST>
+template <int BM, int BN, int WR, int WC>
 static hipError_t launch_tile(const bf16_t* A, const bf16_t* W, bf16_t* C, int M, int Nn, int K,
                               const Epilogue& ep, hipStream_t st) {
     int tm = (M + BM - 1) / BM, tn = (Nn + BN - 1) / BN;
     dim3 grid(tm * tn), block(WR * WC * 64);
     switch (ep.kind) {
         case EPI_BIAS:
-            gemm_mfma_kernel<BM, BN, WR, WC, BK, NST, EPI_BIAS><<<grid, block, 0, st>>>(A, W, C, M, Nn, K, tm, tn, ep);
+            gemm_mfma_kernel<BM, BN, WR, WC, EPI_BIAS><<<grid, block, 0, st>>>(A, W, C, M, Nn, K, tm, tn, ep);
             break;
         case EPI_BIAS_GELU:
-            gemm_mfma_kernel<BM, BN, WR, WC, BK, NST, EPI_BIAS_GELU><<<grid, block, 0, st>>>(A, W, C, M, Nn, K, tm, tn, ep);
+            gemm_mfma_kernel<BM, BN, WR, WC, EPI_BIAS_GELU><<<grid, block, 0, st>>>(A, W, C, M, Nn, K, tm, tn, ep);
             break;
         case EPI_GATE_RESIDUAL:
-            gemm_mfma_kernel<BM, BN, WR, WC, BK, NST, EPI_GATE_RESIDUAL><<<grid, block, 0, st>>>(A, W, C, M, Nn, K, tm, tn,
-                                                                                                 ep);
+            gemm_mfma_kernel<BM, BN, WR, WC, EPI_GATE_RESIDUAL><<<grid, block, 0, st>>>(A, W, C, M, Nn, K, tm, tn, ep);
             break;
         case EPI_QKV_ROPE:
-            gemm_mfma_kernel<BM, BN, WR, WC, BK, NST, EPI_QKV_ROPE><<<grid, block, 0, st>>>(A, W, C, M, Nn, K, tm, tn, ep);
+            gemm_mfma_kernel<BM, BN, WR, WC, EPI_QKV_ROPE><<<grid, block, 0, st>>>(A, W, C, M, Nn, K, tm, tn, ep);
             break;
         default: return hipErrorInvalidValue;
     }
@@ -330,20 +367,13 @@ hipError_t launch_gemm_mfma(const bf16_t* A, const bf16_t* W, bf16_t* C, int M, 
                             const Epilogue& ep, hipStream_t st) {
     int v = g_gemm_variant;
     if (v == 0) {
-        // measured at 17776 tokens inside the forward: two co-resident 128x128 workgroups hide
-        // each other's epilogue (rotary, fp32 residual read-modify-write); the wide GELU
-        // projection is better off with the 256x256 tile's lower L2 traffic
-        if (M < 1024) v = 3;
-        else if (ep.kind == EPI_BIAS_GELU || (ep.kind == EPI_BIAS && Nn >= 6144)) v = 1;
-        else v = 3;
+        // measured at 17776 tokens: wide outputs are better off with the 256x256 tile's lower L2
+        // traffic; narrow ones with two co-resident 128x128 workgroups that hide each other's epilogue
+        v = (M >= 1024 && Nn >= 5760) ? 1 : 2;
     }
     switch (v) {
-        case 1: return launch_tile<256, 256, 2, 4, 64, 2>(A, W, C, M, Nn, K, ep, st);   // 8 waves, 128x64 each
-        case 2: return launch_tile<256, 256, 2, 4, 32, 4>(A, W, C, M, Nn, K, ep, st);   // same tile, deeper ring
-        case 3: return launch_tile<128, 128, 2, 2, 64, 2>(A, W, C, M, Nn, K, ep, st);   // 4 waves, 64x64 each, 2 per CU
-        case 4: return launch_tile<128, 128, 2, 2, 32, 4>(A, W, C, M, Nn, K, ep, st);   // same tile, deeper ring
-        case 5: return launch_tile<256, 128, 4, 2, 64, 3>(A, W, C, M, Nn, K, ep, st);   // 8 waves, 64x64 each
-        case 6: return launch_tile<256, 128, 2, 2, 32, 3>(A, W, C, M, Nn, K, ep, st);   // 4 waves, 128x64, 2 per CU
+        case 1: return launch_tile<256, 256, 2, 4>(A, W, C, M, Nn, K, ep, st);   // 8 waves, 128x64 each
+        case 2: return launch_tile<128, 128, 2, 2>(A, W, C, M, Nn, K, ep, st);   // 4 waves, 64x64 each, 2 per CU
         default: return hipErrorInvalidValue;
     }
 }

@@ -141,6 +141,33 @@ def test_attention_bf16_large_logits_and_poisoned_workspace():
     assert_close_bf16(host(o), O.attn3d(q, k, v, 0.125), 2e-2)
 
 
+@pytest.mark.parametrize("case", ["huge_everywhere", "small_first_tile_then_huge", "all_far_below_zero",
+                                  "moderate_above_window"])
+def test_attention_bf16_reference_shifts(case):
+    """The MFMA kernel keeps its exponent reference at 0 while it safely can; these inputs force
+    it to move: on the first tile, on a later tile (overflow of 2^(c s)), and downwards."""
+    N = 700
+    print(f"attn3d bf16 reference case {case}", flush=True)
+    q, k, v = I.make_qkv(1, N, 2, 64, dtype="bf16")
+    scale = 0.125
+    if case == "huge_everywhere":
+        scale = 8.0                                   # exponents ~ N(0, 92^2)
+    elif case == "small_first_tile_then_huge":
+        scale = 8.0
+        k[:, :64] = I.round_to_bf16((k[:, :64] * 0.01).astype(np.float32))
+    elif case == "all_far_below_zero":
+        scale = 1.0
+        q, k = q * 0.125, k * 0.125
+        q[..., 0], k[..., 0] = 8.0, -8.0              # every score ~ -64: exponent ~ -92
+        q, k = I.round_to_bf16(q.astype(np.float32)), I.round_to_bf16(k.astype(np.float32))
+    else:
+        scale = 1.0                                   # exponents ~ N(0, 11.5^2): some rows peak above 32
+    o = B.attn3d(dev(q, torch.bfloat16), dev(k, torch.bfloat16), dev(v, torch.bfloat16), scale)
+    torch.cuda.synchronize()
+    assert torch.isfinite(o).all()
+    assert_close_bf16(host(o), O.attn3d(q, k, v, scale), 2e-2, max_tol=3e-2)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_attention_invariants(dtype):
     td = torch.float32 if dtype == "f32" else torch.bfloat16
