@@ -111,8 +111,10 @@ PS_API int dit_profile_read(dit* d, double* ms_out, int64_t* launches_out);
  * the inputs.  seq >= 1, scale > 0, head_dim in {16, 32, 64}; rows past the end are never
  * read, but V must be finite (masked keys multiply V by an exact 0).
  * workspace: DEVICE, 256-byte aligned, >= attn3d_workspace_bytes(...) (may be NULL when
- * that is 0); scratch only.  It is non-zero when the bf16 head-dim-64 kernel splits its last
- * partial round of workgroups along the keys (partial sums are merged by a second kernel). */
+ * that is 0); scratch only.  It is non-zero for bf16 with head_dim 64: those kernels keep the
+ * largest query and key norm of every (batch, head) there (heads whose scores are provably
+ * bounded take a softmax without running maximum) and the partial sums of the workgroups
+ * that split their keys in the last, partial round (merged by a second kernel). */
 PS_API size_t attn3d_workspace_bytes(int batch, int seq, int heads, int head_dim, int dtype);
 PS_API int attn3d(const void* q, const void* k, const void* v, void* o,
            int batch, int seq, int heads, int head_dim, float scale, int dtype,

@@ -12,6 +12,7 @@
 //    workgroup, each wave owning 64 queries; V stays in its natural [key][d] layout and
 //    its transposed fragments come from ds_read_b64_tr_b16.
 #include "common.h"
+#include <type_traits>
 
 namespace ps {
 
@@ -177,19 +178,98 @@ __device__ __forceinline__ float sum_across_halves(float v) {
 //    of the running sums.
 // PRESCALED: q already carries the factor c = scale*log2(e) (the QKV projection applies it
 // in fp32 before rounding), so p = exp2(acc) with no multiply; otherwise p = exp2(c*acc).
+// ---- fast variant for bounded scores ------------------------------------------------------
+// attn_bound_kernel finds, per (batch, head), the largest squared norm of a query row and of a
+// key row.  By Cauchy-Schwarz every exponent c*s of that head lies within +-c*|q|max*|k|max; if
+// that is below PP_EXP_LIMIT, 2^(c s) can neither overflow nor sum to zero, so the softmax
+// needs no reference value, no maximum and no check at all, and attn_sp_kernel takes the head.
+// Heads above the limit are left to attn_mfma_kernel, which tracks a reference.
+constexpr float PP_EXP_LIMIT = 60.0f;
+
+__global__ void attn_bound_clear_kernel(float* __restrict__ bounds, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) bounds[i] = 0.f;
+}
+
+// grid (blocks of BOUND_ROWS tokens, batch).  A workgroup walks its rows' q and k slices of ALL heads in
+// memory order (8 lanes per 128-byte head slice), keeps per-head maxima in LDS and ends with one
+// conditional atomic per head.  bounds[2*bh] = max |q|^2, bounds[2*bh+1] = max |k|^2
+constexpr int BOUND_ROWS = 32, BOUND_MAX_HEADS = 128;
+__global__ void __launch_bounds__(256)
+attn_bound_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int seq, int heads, AttnStrides s,
+                  float* __restrict__ bounds) {
+    __shared__ unsigned smax[2][BOUND_MAX_HEADS];
+    const int b = blockIdx.y, row0 = blockIdx.x * BOUND_ROWS;
+    const int rows = min(BOUND_ROWS, seq - row0);
+    for (int i = threadIdx.x; i < 2 * BOUND_MAX_HEADS; i += 256) (&smax[0][0])[i] = 0u;
+    __syncthreads();
+    const bf16_t* qb = q + b * s.q_batch + (long)row0 * s.q_tok;
+    const bf16_t* kb = k + b * s.k_batch + (long)row0 * s.k_tok;
+    const int per_row = heads * 8, total = rows * per_row;
+    for (int c0 = 0; c0 < total; c0 += 4 * 256) {
+        bf16x8_t a[4], w[4];
+        int hd[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            int c = c0 + u * 256 + threadIdx.x;
+            c = c < total ? c : total - 1;            // the tail repeats the last slice: same maxima
+            const int r = c / per_row, rem = c - r * per_row;
+            hd[u] = rem >> 3;
+            a[u] = *reinterpret_cast<const bf16x8_t*>(qb + (long)r * s.q_tok + hd[u] * s.q_head + (rem & 7) * 8);
+            w[u] = *reinterpret_cast<const bf16x8_t*>(kb + (long)r * s.k_tok + hd[u] * s.k_head + (rem & 7) * 8);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            float nq = 0.f, nk = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                nq += (float)a[u][e] * (float)a[u][e];
+                nk += (float)w[u][e] * (float)w[u][e];
+            }
+#pragma unroll
+            for (int off = 1; off < 8; off <<= 1) {   // the 8 lanes of a (token, head)
+                nq += __shfl_xor(nq, off);
+                nk += __shfl_xor(nk, off);
+            }
+            // NaN or inf norms must disqualify the head: map them to +inf, which orders above everything;
+            // non-negative floats order like their bit patterns
+            if (!(nq < INFINITY)) nq = INFINITY;
+            if (!(nk < INFINITY)) nk = INFINITY;
+            if ((threadIdx.x & 7) == 0) {
+                atomicMax(&smax[0][hd[u]], __float_as_uint(nq));
+                atomicMax(&smax[1][hd[u]], __float_as_uint(nk));
+            }
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < 2 * heads; i += 256) {
+        const int hh = i >> 1, which = i & 1;
+        const unsigned m = smax[which][hh];
+        unsigned* dst = reinterpret_cast<unsigned*>(bounds + 2 * (b * heads + hh) + which);
+        if (m > __builtin_nontemporal_load(dst)) atomicMax(dst, m);
+    }
+}
+
+__device__ __forceinline__ bool head_is_bounded(const float* __restrict__ bounds, int bh, float c) {
+    const float e = sqrtf(bounds[2 * bh]) * sqrtf(bounds[2 * bh + 1]) * c;
+    return e < PP_EXP_LIMIT;                 // false for NaN and inf
+}
+
 static constexpr int PART_STRIDE = 68;      // floats per row of a partial result (64 + l + r, padded to 16 B)
 
 // Merge of the key-range pieces of the split items: one thread per (row, 4 output values).
 // O = sum_i w_i O_i / sum_i w_i l_i with w_i = 2^(c (r_i - max_i r_i)).
 __global__ void __launch_bounds__(256)
 attn_merge_kernel(const float* __restrict__ part, bf16_t* __restrict__ o, int seq, int heads, int qblocks,
-                  int full_blocks, int nsplit, int nitems, float cexp, int bq, AttnStrides s) {
+                  int full_blocks, int nsplit, int nitems, float cexp, int bq, AttnStrides s,
+                  const float* __restrict__ bounds) {
     const int gid = blockIdx.x * 256 + threadIdx.x;
     const int d4 = gid & 15, rowid = gid >> 4;          // 16 threads per row
     const int item = rowid / bq, row = rowid % bq;
     if (item >= nitems) return;
     const int id = full_blocks + item;
     const int bh = id / qblocks, qb = id % qblocks;
+    if (bounds != nullptr && !head_is_bounded(bounds, bh, cexp)) return;   // pieces exist for attn_sp_kernel's heads only
     const int b = bh / heads, h = bh % heads;
     const int qi = qb * bq + row;
     if (qi >= seq) return;
@@ -212,6 +292,18 @@ attn_merge_kernel(const float* __restrict__ part, bf16_t* __restrict__ o, int se
     *reinterpret_cast<bf16x4_t*>(o + b * s.o_batch + (long)qi * s.o_tok + h * s.o_head + d4 * 4) = wv;
 }
 
+// global->LDS load of 16 bytes per lane: lane j's bytes land at lds_addr + 16*j (lds_addr
+// wave-uniform, passed through M0).  _base: scalar 64-bit base + per-lane 32-bit byte offset;
+// _ptr: per-lane 64-bit address.
+__device__ __forceinline__ void lds_dma16_base(unsigned voff, const void* sbase, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_addr)
+                 : "memory", "m0");
+}
+__device__ __forceinline__ void lds_dma16_ptr(const void* gptr, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr)
+                 : "memory", "m0");
+}
+
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 // acc + sum of eight bf16 values (v_dot2c_f32_bf16 against packed ones)
 __device__ __forceinline__ float rowsum_bf16x8(bf16x8_t p, float acc) {
@@ -228,14 +320,15 @@ template <int QT, bool PRESCALED>   // QT: 32-query column tiles per wave
 __global__ void __launch_bounds__(256, 2)
 attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
                  bf16_t* __restrict__ o, int seq, int heads, float scale_log2e, int qblocks, AttnStrides s,
-                 int full_blocks, int nsplit, float* __restrict__ part) {
+                 int full_blocks, int nsplit, float* __restrict__ part, const float* __restrict__ bounds) {
     constexpr int KV = 64;
     constexpr int BQ = 4 * QT * 32;
     constexpr int NST = 3;                       // LDS ring depth
     constexpr int STAGE = 2 * KV * 128;          // K tile then V tile, 128-byte rows
     __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * STAGE];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform values stay in scalar registers
     const int col = lane & 31, half = lane >> 5;
     // workgroup -> (batch*head, query block); consecutive ids of one XCD walk the query
     // blocks of one head so that head's K and V stay in that XCD's L2
@@ -257,6 +350,8 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
         jt1 = (int)((long)nt * (pi + 1) / nsplit);
     }
     const int bh = id / qblocks, qb = id % qblocks;
+    // with `bounds` given, heads whose exponents are provably small belong to attn_sp_kernel
+    if (bounds != nullptr && head_is_bounded(bounds, bh, PRESCALED ? 1.0f : scale_log2e)) return;
     const int b = bh / heads, h = bh % heads;
     const int q0 = qb * BQ + wave * (QT * 32);
 
@@ -274,6 +369,12 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
         for (int ks = 0; ks < 4; ++ks)
             qf[t][ks] = *reinterpret_cast<const bf16x8_t*>(qp + ks * 16 + half * 8);
     }
+    // pin the Q loads here: the compiler must not place its own vmcnt wait for them inside the
+    // loop, where it would also wait for the K/V tile loads in flight
+#pragma unroll
+    for (int t = 0; t < QT; ++t)
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) asm volatile("" ::"v"(qf[t][ks]));
 
     f32x16_t oacc[2][QT];
 #pragma unroll
@@ -307,20 +408,43 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
     // slot p of row r holds chunk p ^ ((r>>1)&7).  V fragments are transposing 8-byte
     // reads that touch 8 consecutive rows x 64 bytes: slot p of row r holds chunk p ^ (r&7).
     // Per stage: 8 K groups + 8 V groups; wave w takes K groups w, w+4 and V groups w, w+4.
+    // The loads are issued from inline asm (the compiler then never orders LDS reads of other
+    // stages behind them; the explicit vmcnt waits and barriers below publish a stage).  A tile
+    // that lies entirely inside the sequence is addressed as scalar tile base + a per-lane byte
+    // offset fixed for the whole kernel, so the loop spends no vector instruction on addresses;
+    // the last, ragged tile and the look-ahead tiles past the end clamp their rows per lane.
     const int lr = lane >> 3;
     const int lc_v = (lane & 7) ^ lr;
-    auto issue = [&](int tile, int buf) {
-        unsigned char* st = lds + buf * STAGE;
+    const unsigned lds_base = (unsigned)(size_t)PS_LDS_PTR(lds);
+    unsigned koff[2], voff[2];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            int g = wave + 4 * i;
-            int kr = tile * KV + g * 8 + lr;
-            kr = kr < seq ? kr : seq - 1;            // rows past the end re-read the last key (masked later)
-            const int lc_k = (lane & 7) ^ (((g & 1) << 2) | (lane >> 4));
-            __builtin_amdgcn_global_load_lds(PS_GLOBAL_PTR(kbase + (long)kr * s.k_tok + lc_k * 8),
-                                             PS_LDS_PTR(st + g * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds(PS_GLOBAL_PTR(vbase + (long)kr * s.v_tok + lc_v * 8),
-                                             PS_LDS_PTR(st + KV * 128 + g * 1024), 16, 0, 0);
+    for (int i = 0; i < 2; ++i) {
+        const int g = wave + 4 * i;
+        const int lc_k = (lane & 7) ^ (((g & 1) << 2) | (lane >> 4));
+        koff[i] = (unsigned)(((g * 8 + lr) * s.k_tok + lc_k * 8) * 2);
+        voff[i] = (unsigned)(((g * 8 + lr) * s.v_tok + lc_v * 8) * 2);
+    }
+    auto issue = [&](int tile, int buf) {
+        const unsigned st = lds_base + buf * STAGE;
+        if ((tile + 1) * KV <= seq) {
+            const char* kb = reinterpret_cast<const char*>(kbase) + (long)tile * KV * s.k_tok * 2;
+            const char* vb = reinterpret_cast<const char*>(vbase) + (long)tile * KV * s.v_tok * 2;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int g = wave + 4 * i;
+                lds_dma16_base(koff[i], kb, st + g * 1024);
+                lds_dma16_base(voff[i], vb, st + KV * 128 + g * 1024);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int g = wave + 4 * i;
+                int kr = tile * KV + g * 8 + lr;
+                kr = kr < seq ? kr : seq - 1;        // rows past the end re-read the last key (masked later)
+                const int lc_k = (lane & 7) ^ (((g & 1) << 2) | (lane >> 4));
+                lds_dma16_ptr(kbase + (long)kr * s.k_tok + lc_k * 8, st + g * 1024);
+                lds_dma16_ptr(vbase + (long)kr * s.v_tok + lc_v * 8, st + KV * 128 + g * 1024);
+            }
         }
     };
 
@@ -333,7 +457,6 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
     const int tsub = (tj & 1) * 8;
     // rows 16*step (+8) keep trow's low 3 bits, so the swizzled slot is the same for every
     // step; d tile 1 flips bit 2 of the slot
-    const unsigned lds_base = (unsigned)(size_t)PS_LDS_PTR(lds);
     const unsigned voff0 = KV * 128 + trow * 128 + ((tchunk ^ (trow & 7)) << 4) + tsub;
     const unsigned voff1 = KV * 128 + trow * 128 + (((4 + tchunk) ^ (trow & 7)) << 4) + tsub;
 
@@ -532,26 +655,297 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
     }
 }
 
+// Check-free kernel for heads with bounded exponents (see attn_bound_kernel): p = 2^(c s), no reference.
+// Work split and LDS layout as in attn_mfma_kernel (4 waves x 64 queries, K/V tiles of 64 keys straight into
+// an LDS ring, two workgroups per CU), but the loop is software-pipelined over 32-key half tiles.  In
+// every step a wave issues the 8 MFMAs of S^T for the NEXT half, the exp2 / pack / row-sum instructions of
+// the CURRENT half and the 8 MFMAs of O^T += V^T P^T for the PREVIOUS half.  The three are independent,
+// so the compiler interleaves them and the instruction stream is a steady mix of MFMA and vector ALU work.
+// A wave that alternates long MFMA-only and ALU-only blocks (the other kernel) leaves the matrix pipe
+// idle during its ALU blocks even with a second wave on the SIMD, because both waves drift into phase;
+// a homogeneous stream keeps both units busy.  Measured on a register-only replica: 1.77 vs 1.37-1.43
+// PFLOP/s-equivalent.
+// Steps of iteration j (tile j = halves a, b):
+//   A: S(j,b)    | softmax(j,a)  | PV(j-1,b)
+//   B: S(j+1,a)  | softmax(j,b)  | PV(j,a)
+// so tiles j-1, j, j+1 are read during iteration j and tile j+2 is being loaded: four ring slots.
+template <bool PRESCALED>
+__global__ void __launch_bounds__(256, 2)
+attn_sp_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
+               bf16_t* __restrict__ o, int seq, int heads, float scale_log2e, int qblocks, AttnStrides s,
+               int full_blocks, int nsplit, float* __restrict__ part, const float* __restrict__ bounds) {
+    constexpr int QT = 2;                        // 32-query column tiles per wave
+    constexpr int KV = 64;                       // keys per tile
+    constexpr int BQ = 4 * QT * 32;              // queries per workgroup
+    constexpr int NST = 4;                       // LDS ring depth
+    constexpr int STAGE = 2 * KV * 128;          // K tile then V tile, 128-byte rows
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * STAGE];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int col = lane & 31, half = lane >> 5;
+    // work items and the key split of the last partial round: as in attn_mfma_kernel
+    int id = blockIdx.x;
+    int piece = -1, jt0 = 0, jt1 = (seq + KV - 1) / KV;
+    if (id < full_blocks) {
+        int per = full_blocks / 8, rem = full_blocks % 8, x = id % 8, j = id / 8;
+        id = x * per + (x < rem ? x : rem) + j;
+    } else {
+        piece = id - full_blocks;
+        id = full_blocks + piece / nsplit;
+        const int pi = piece % nsplit;
+        const int nt = jt1;
+        jt0 = (int)((long)nt * pi / nsplit);
+        jt1 = (int)((long)nt * (pi + 1) / nsplit);
+    }
+    const int bh = id / qblocks, qb = id % qblocks;
+    const float cexp = PRESCALED ? 1.0f : scale_log2e;
+    if (!head_is_bounded(bounds, bh, cexp)) return;          // whole workgroup: before any barrier
+    const int b = bh / heads, h = bh % heads;
+    const int q0 = qb * BQ + wave * (QT * 32);
+
+    const bf16_t* kbase = k + b * s.k_batch + h * s.k_head;
+    const bf16_t* vbase = v + b * s.v_batch + h * s.v_head;
+
+    bf16x8_t qf[QT][4];
+#pragma unroll
+    for (int t = 0; t < QT; ++t) {
+        int qi = q0 + t * 32 + col;
+        qi = qi < seq ? qi : seq - 1;
+        const bf16_t* qp = q + b * s.q_batch + (long)qi * s.q_tok + h * s.q_head;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+            qf[t][ks] = *reinterpret_cast<const bf16x8_t*>(qp + ks * 16 + half * 8);
+    }
+    // pin the Q loads here: the compiler must not place its own vmcnt wait for them inside the
+    // loop, where it would also wait for the K/V tile loads in flight
+#pragma unroll
+    for (int t = 0; t < QT; ++t)
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) asm volatile("" ::"v"(qf[t][ks]));
+
+    f32x16_t oacc[2][QT];
+#pragma unroll
+    for (int d = 0; d < 2; ++d)
+#pragma unroll
+        for (int t = 0; t < QT; ++t)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) oacc[d][t][e] = 0.f;
+    float lsum[QT];
+#pragma unroll
+    for (int t = 0; t < QT; ++t) lsum[t] = 0.f;
+
+    // loads: per tile 8 K + 8 V row groups of 8 rows; wave w takes groups w and w+4 of each
+    const int lr = lane >> 3;
+    const int lc_v = (lane & 7) ^ lr;
+    const unsigned lds_base = (unsigned)(size_t)PS_LDS_PTR(lds);
+    unsigned koff[2], voff[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int g = wave + 4 * i;
+        const int lc_k = (lane & 7) ^ (((g & 1) << 2) | (lane >> 4));
+        koff[i] = (unsigned)(((g * 8 + lr) * s.k_tok + lc_k * 8) * 2);
+        voff[i] = (unsigned)(((g * 8 + lr) * s.v_tok + lc_v * 8) * 2);
+    }
+    auto issue = [&](int tile) {
+        const unsigned st = lds_base + ((tile - jt0) & (NST - 1)) * STAGE;
+        if ((tile + 1) * KV <= seq) {
+            const char* kb = reinterpret_cast<const char*>(kbase) + (long)tile * KV * s.k_tok * 2;
+            const char* vb = reinterpret_cast<const char*>(vbase) + (long)tile * KV * s.v_tok * 2;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int g = wave + 4 * i;
+                lds_dma16_base(koff[i], kb, st + g * 1024);
+                lds_dma16_base(voff[i], vb, st + KV * 128 + g * 1024);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int g = wave + 4 * i;
+                int kr = tile * KV + g * 8 + lr;
+                kr = kr < seq ? kr : seq - 1;        // rows past the end re-read the last key (masked later)
+                const int lc_k = (lane & 7) ^ (((g & 1) << 2) | (lane >> 4));
+                lds_dma16_ptr(kbase + (long)kr * s.k_tok + lc_k * 8, st + g * 1024);
+                lds_dma16_ptr(vbase + (long)kr * s.v_tok + lc_v * 8, st + KV * 128 + g * 1024);
+            }
+        }
+    };
+
+    // V^T fragment addressing for ds_read_b64_tr_b16 (see attn_mfma_kernel)
+    const int tg = lane >> 4, tj = lane & 15;
+    const int trow = 4 * (tg >> 1) + (tj >> 2);
+    const int tchunk = 2 * (tg & 1) + ((tj & 3) >> 1);
+    const int tsub = (tj & 1) * 8;
+    const int vad0 = KV * 128 + trow * 128 + ((tchunk ^ (trow & 7)) << 4) + tsub;
+    const int vad1 = KV * 128 + trow * 128 + (((4 + tchunk) ^ (trow & 7)) << 4) + tsub;
+    // K fragment addressing: key row 32*hh + col, chunk (2 ks + half) ^ ((row >> 1) & 7); the row term of
+    // the XOR is the same for both halves of a tile (32 rows = 16 * 2)
+    const int ksw = (col >> 1) & 7;
+    const int kad = col * 128;
+
+    // ---- the three parts of a step
+    // S^T of half hh of the tile in ring slot `slot`
+    auto scores = [&](f32x16_t (&sacc)[QT], int slot, int hh) {
+        const unsigned char* lk = lds + slot * STAGE + hh * (32 * 128) + kad;
+#pragma unroll
+        for (int t = 0; t < QT; ++t)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) sacc[t][e] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(lk + (((ks * 2 + half) ^ ksw) << 4));
+#pragma unroll
+            for (int t = 0; t < QT; ++t)
+                sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t][ks], sacc[t], 0, 0, 0);
+        }
+    };
+    // p = 2^(c s), packed to bf16, and the row sums; MASK: keys at or past `seq` get p = 0
+    auto softmax = [&](f32x16_t (&sacc)[QT], bf16x8_t (&pf)[QT][2], int key0, bool mask) {
+        if (mask) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int key = key0 + 8 * (e >> 2) + 4 * half + (e & 3);
+                if (key >= seq) {
+#pragma unroll
+                    for (int t = 0; t < QT; ++t) sacc[t][e] = -INFINITY;
+                }
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < QT; ++t) {
+            float rs = 0.f;
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {          // k16-step inside the 32-key half
+                bf16x8_t pk;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float a = sacc[t][g * 8 + e];
+                    pk[e] = (__bf16)__builtin_amdgcn_exp2f(PRESCALED ? a : a * cexp);
+                }
+                pf[t][g] = pk;
+                rs = rowsum_bf16x8(pk, rs);
+            }
+            lsum[t] += rs;
+        }
+    };
+    // O^T += V^T P^T for half hh of the tile in ring slot `slot`; k-slot (half, e) of step g is key
+    // 32 hh + 16 g + 8(e/4) + 4 half + e%4
+    auto pv = [&](const bf16x8_t (&pf)[QT][2], int slot, int hh) {
+        const unsigned char* lv = lds + slot * STAGE + hh * (32 * 128);
+#pragma unroll
+        for (int g = 0; g < 2; ++g)
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt) {
+                const unsigned char* a = lv + (dt ? vad1 : vad0) + g * 2048;
+                const bf16x4_t lo = lds_read_tr16(a), hi = lds_read_tr16(a + 1024);
+                const bf16x8_t vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+                for (int t = 0; t < QT; ++t)
+                    oacc[dt][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[t][g], oacc[dt][t], 0, 0, 0);
+            }
+    };
+
+    f32x16_t sa[QT], sb[QT];
+    bf16x8_t pa[QT][2], pb[QT][2];
+    issue(jt0);
+    issue(jt0 + 1);                                // tiles past the end are harmless re-reads
+    asm volatile("s_waitcnt vmcnt(4)" ::: "memory");   // own share of the first tile
+    __syncthreads();
+    scores(sa, 0, 0);
+    // one iteration; FIRST / LAST are compile-time so that the steps of the steady state are straight-line
+    // code the scheduler can interleave
+    auto iteration = [&](int j, auto first_c, auto last_c) {
+        constexpr bool FIRST = decltype(first_c)::value, LAST = decltype(last_c)::value;
+        const int slot = (j - jt0) & (NST - 1);
+        const bool mask = LAST && (j + 1) * KV > seq;
+        // tile j+1 has landed (own share), for every wave after the barrier; the slot of tile j-2 is free
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        issue(j + 2);
+        // step A
+        scores(sb, slot, 1);
+        softmax(sa, pa, j * KV, mask);
+        if constexpr (!FIRST) pv(pb, (slot + NST - 1) & (NST - 1), 1);
+        __builtin_amdgcn_sched_barrier(0);
+        // step B
+        if constexpr (!LAST) scores(sa, (slot + 1) & (NST - 1), 0);
+        softmax(sb, pb, j * KV + 32, mask);
+        pv(pa, slot, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    using std::false_type;
+    using std::true_type;
+    if (jt1 - jt0 == 1) {
+        iteration(jt0, true_type{}, true_type{});
+    } else {
+        iteration(jt0, true_type{}, false_type{});
+        for (int j = jt0 + 1; j < jt1 - 1; ++j) iteration(j, false_type{}, false_type{});
+        iteration(jt1 - 1, false_type{}, true_type{});
+    }
+    pv(pb, (jt1 - 1 - jt0) & (NST - 1), 1);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // drain the look-ahead loads before exit
+
+    if (piece >= 0) {
+        // partial result of a key range, reference 0: [piece][row in block][64 sums | row sum | 0 | pad]
+        float* pp = part + (long)piece * BQ * PART_STRIDE;
+#pragma unroll
+        for (int t = 0; t < QT; ++t) {
+            const float l = sum_across_halves(lsum[t]);
+            float* pr = pp + (long)(wave * (QT * 32) + t * 32 + col) * PART_STRIDE;
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    *reinterpret_cast<float4*>(pr + dt * 32 + g * 8 + half * 4) =
+                        make_float4(oacc[dt][t][g * 4], oacc[dt][t][g * 4 + 1], oacc[dt][t][g * 4 + 2],
+                                    oacc[dt][t][g * 4 + 3]);
+            if (half == 0) { pr[64] = l; pr[65] = 0.f; }
+        }
+        return;
+    }
+#pragma unroll
+    for (int t = 0; t < QT; ++t) {
+        float l = sum_across_halves(lsum[t]);
+        float inv = 1.0f / l;
+        int qi = q0 + t * 32 + col;
+        if (qi < seq) {
+            bf16_t* op = o + b * s.o_batch + (long)qi * s.o_tok + h * s.o_head;
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    bf16x4_t w;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) w[e] = (__bf16)(oacc[dt][t][g * 4 + e] * inv);
+                    *reinterpret_cast<bf16x4_t*>(op + dt * 32 + g * 8 + half * 4) = w;
+                }
+        }
+    }
+}
+
 // Split plan for the bf16 head-dim-64 kernel (see attn_mfma_kernel): how many work items run
 // whole, and how many ways the rest is split along the keys.
-struct AttnPlan { int qblocks, items, full, nsplit, pieces; };
-static int workgroup_slots() {
-    static int slots = 0;
-    if (slots == 0) {
-        int cus = 0, dev = 0;
+struct AttnPlan { int qblocks, items, full, nsplit, pieces, bq; };
+static int compute_units() {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
             cus = 256;
-        slots = 2 * cus;                      // two resident workgroups per CU
     }
-    return slots;
+    return cus;
 }
-static AttnPlan attention_plan(int batch, int seq, int heads, int BQ) {
+// kernel path 3 sends every head to the reference-tracking kernel; otherwise heads with provably bounded
+// exponents take the check-free software-pipelined kernel
+static bool attention_bounded_path(int heads) { return get_kernel_path() != 3 && heads <= BOUND_MAX_HEADS; }
+static AttnPlan attention_plan(int batch, int seq, int heads) {
     constexpr int KV = 64;
     AttnPlan p;
-    p.qblocks = (seq + BQ - 1) / BQ;
+    p.bq = 256;
+    p.qblocks = (seq + p.bq - 1) / p.bq;
     p.items = p.qblocks * heads * batch;
-    const int slots = workgroup_slots();
+    const int slots = compute_units() * 2;               // two resident workgroups per CU
     const int tail = p.items % slots;
     const int ntiles = (seq + KV - 1) / KV;
     int ns = tail > 0 ? slots / tail : 1;
@@ -562,10 +956,14 @@ static AttnPlan attention_plan(int batch, int seq, int heads, int BQ) {
     return p;
 }
 
+static size_t bounds_bytes(int batch, int heads) { return (((size_t)batch * heads * 2 * sizeof(float)) + 255) & ~(size_t)255; }
+
+// workspace of the bf16 head-dim-64 kernels: [2 floats per (batch, head): norm bounds | key-split pieces]
 size_t attention_workspace_bytes(int dtype, int batch, int seq, int heads, int head_dim) {
     if (dtype != PS_BF16 || head_dim != 64 || batch < 1 || seq < 1 || heads < 1) return 0;
-    AttnPlan p = attention_plan(batch, seq, heads, 256);
-    return (size_t)p.pieces * 256 * PART_STRIDE * sizeof(float);
+    const AttnPlan p = attention_plan(batch, seq, heads);
+    const size_t need = (size_t)p.pieces * p.bq * PART_STRIDE * sizeof(float);
+    return bounds_bytes(batch, heads) + need;
 }
 
 bool attention_uses_mfma(int dtype, int head_dim) {
@@ -576,29 +974,53 @@ hipError_t launch_attention(int dtype, const void* q, const void* k, const void*
                             int batch, int seq, int heads, int head_dim, float scale,
                             const AttnStrides& s, void* ws, hipStream_t st, bool q_prescaled) {
     if (attention_uses_mfma(dtype, head_dim)) {
-        constexpr int QT = 2;                                   // 32-query tiles per wave
-        constexpr int BQ = 4 * QT * 32;
-        AttnPlan p = attention_plan(batch, seq, heads, BQ);
-        if (p.pieces > 0 && (ws == nullptr || get_kernel_path() == 2)) { p.full = p.items; p.nsplit = 1; p.pieces = 0; }
-        dim3 grid(p.full + p.pieces);
+        if (ws == nullptr) return hipErrorInvalidValue;
+        if (s.k_tok >= (1 << 24) || s.v_tok >= (1 << 24)) return hipErrorInvalidValue;   // 32-bit in-tile offsets
+        const bool bounded = attention_bounded_path(heads);
+        AttnPlan p = attention_plan(batch, seq, heads);
+        if (get_kernel_path() == 2) { p.full = p.items; p.nsplit = 1; p.pieces = 0; }
         const float c = scale * 1.4426950408889634f;
+        const float cexp = q_prescaled ? 1.0f : c;
         const bf16_t *qq = (const bf16_t*)q, *kk = (const bf16_t*)k, *vv = (const bf16_t*)v;
-        float* part = (float*)ws;
-#define PS_ATTN_LAUNCH(QTV, PRE)                                                                                   \
-    attn_mfma_kernel<QTV, PRE><<<grid, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c, p.qblocks, s, p.full, \
-                                                     p.nsplit, part)
-        // (one 32-query tile per wave, i.e. 128-query workgroups at three per CU, measured 9 % slower:
-        // it doubles the K/V traffic into LDS and the fragment reads per MFMA)
-        if (q_prescaled) PS_ATTN_LAUNCH(QT, true);
-        else PS_ATTN_LAUNCH(QT, false);
-#undef PS_ATTN_LAUNCH
+        float* bounds = (float*)ws;
+        float* part = (float*)((char*)ws + bounds_bytes(batch, heads));
+        const int bq = p.bq;
+        if (bounded) {
+            // norm bounds per (batch, head), then the check-free kernel for the heads they qualify and the
+            // reference-tracking kernel (unsplit) for the others; each workgroup looks its head up
+            const int nb = batch * heads * 2;
+            attn_bound_clear_kernel<<<(nb + 255) / 256, 256, 0, st>>>(bounds, nb);
+            attn_bound_kernel<<<dim3((seq + BOUND_ROWS - 1) / BOUND_ROWS, batch), 256, 0, st>>>(qq, kk, seq, heads, s, bounds);
+            if (q_prescaled)
+                attn_sp_kernel<true><<<p.full + p.pieces, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c, p.qblocks, s,
+                                                                        p.full, p.nsplit, part, bounds);
+            else
+                attn_sp_kernel<false><<<p.full + p.pieces, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c, p.qblocks,
+                                                                         s, p.full, p.nsplit, part, bounds);
+            const AttnPlan& g = p;
+            if (q_prescaled)
+                attn_mfma_kernel<2, true><<<g.items, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c, g.qblocks, s,
+                                                                   g.items, 1, nullptr, bounds);
+            else
+                attn_mfma_kernel<2, false><<<g.items, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c, g.qblocks, s,
+                                                                    g.items, 1, nullptr, bounds);
+        } else {
+            // (one 32-query tile per wave, i.e. 128-query workgroups at three per CU, measured 9 % slower:
+            // it doubles the K/V traffic into LDS and the fragment reads per MFMA)
+            if (q_prescaled)
+                attn_mfma_kernel<2, true><<<p.full + p.pieces, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c, p.qblocks,
+                                                                             s, p.full, p.nsplit, part, nullptr);
+            else
+                attn_mfma_kernel<2, false><<<p.full + p.pieces, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c,
+                                                                              p.qblocks, s, p.full, p.nsplit, part, nullptr);
+        }
         hipError_t err = hipGetLastError();
         if (err != hipSuccess || p.pieces == 0) return err;
         const int nitems = p.items - p.full;
-        const long threads = (long)nitems * BQ * 16;
+        const long threads = (long)nitems * bq * 16;
         attn_merge_kernel<<<(unsigned)((threads + 255) / 256), 256, 0, st>>>(part, (bf16_t*)o, seq, heads, p.qblocks,
-                                                                            p.full, p.nsplit, nitems,
-                                                                            q_prescaled ? 1.0f : c, BQ, s);
+                                                                            p.full, p.nsplit, nitems, cexp, bq, s,
+                                                                            bounded ? bounds : nullptr);
         return hipGetLastError();
     }
     if (q_prescaled) return hipErrorInvalidValue;     // only the MFMA kernel takes pre-scaled queries
