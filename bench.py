@@ -84,7 +84,7 @@ def main():
     ap.add_argument("--workload", default="full", choices=["full", "long", "block"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-path", type=lambda v: int(v, 0), default=0, help="tuning hook passed to ps_set_kernel_path")
-    ap.add_argument("--kernel", default=None, choices=["attn3d", "copy", "sampler_step"],
+    ap.add_argument("--kernel", default=None, choices=["attn3d", "dit_linear", "copy", "sampler_step"],
                     help="profiling target: launch only this kernel 3 times at the workload's shape and exit")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -111,6 +111,16 @@ def main():
             for _ in range(3):
                 B.attn3d(q, k, v, cfg.head_dim ** -0.5, out=o)
             what = {"kernel": "attn3d", "tokens": N, "heads": cfg.heads, "flop": 4.0 * N * N * D}
+        elif args.kernel == "dit_linear":         # the four projection shapes of a layer (plain bias / GELU epilogues)
+            shapes = [(3 * D, D, 0), (D, D, 0), (4 * D, D, 1), (D, 4 * D, 0)]
+            for nn, kk, act in shapes:
+                a = torch.randn((N, kk), generator=g, device="cuda").to(torch.bfloat16)
+                w = (torch.randn((nn, kk), generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+                bias = torch.randn((nn,), generator=g, device="cuda")
+                out = torch.empty((N, nn), device="cuda", dtype=torch.bfloat16)
+                for _ in range(3):
+                    B.dit_linear(a, w, bias, act, out=out)
+            what = {"kernel": "dit_linear", "tokens": N, "shapes": shapes}
         elif args.kernel == "copy":               # plain copy of known size: scale for FETCH_SIZE / WRITE_SIZE
             n = 1 << 28
             a, b = torch.randn(n, generator=g, device="cuda"), torch.empty(n, device="cuda")
@@ -187,7 +197,7 @@ def main():
                                f"{cfg.head_dim}, {cfg.video_tokens} video + {cfg.text_tokens} text tokens, "
                                f"DDIM reuse-then-predict window 2, batch 1",
                    "tokens": N, "layers": cfg.layers, "latent": list(cfg.latent_shape)},
-        "roofline": {"kernel": "attn_mfma_kernel", "bound": "mfma", "achieved": round(att_tflops, 1),
+        "roofline": {"kernel": "attn_sp_kernel", "bound": "mfma", "achieved": round(att_tflops, 1),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(att_tflops / PEAK_BF16_TFLOPS, 4),
                      "traffic": ATTN_HBM_BYTES_PER_LAUNCH if args.workload == "full" else None, "avg_ms": round(att_avg, 4), "launches": int(att_n),
                      "flop_per_launch": 4.0 * N * N * D},
