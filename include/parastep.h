@@ -130,8 +130,9 @@ PS_API int dit_linear(const void* a, const void* w, const float* bias, void* out
 
 /* Test and tuning hook: 0 = pick the fastest kernel for each shape (default), 1 = always
  * use the generic fp32-FMA kernels, 2 = bf16 attention without the key-split of its last
- * partial round of workgroups, 0x100|v = force tile variant v of the bf16 MFMA GEMM (1: 256x256, 2: 128x128).  Process-wide;
- * returns the previous value. */
+ * partial round of workgroups, 3 = bf16 head-dim-64 attention always through the kernel that
+ * tracks a softmax reference (no norm-bound shortcut), 0x100|v = force tile variant v of the
+ * bf16 MFMA GEMM (1: 256x256, 2: 128x128).  Process-wide; returns the previous value. */
 PS_API int ps_set_kernel_path(int path);
 
 /* ------------------------------------------------------------- scheduler and metric

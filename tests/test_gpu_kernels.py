@@ -168,6 +168,37 @@ def test_attention_bf16_reference_shifts(case):
     assert_close_bf16(host(o), O.attn3d(q, k, v, scale), 2e-2, max_tol=3e-2)
 
 
+@pytest.mark.parametrize("N", [64, 300, 1000])
+def test_attention_bf16_reference_tracking_kernel_on_ordinary_inputs(N):
+    """Kernel path 3 sends every head through the kernel that keeps a softmax reference (the fallback for
+    unbounded scores); on ordinary inputs it must agree with the oracle like the default path does."""
+    print(f"attn3d bf16 path 3 N={N}", flush=True)
+    q, k, v = I.make_qkv(2, N, 3, 64, dtype="bf16")
+    prev = B.ps_set_kernel_path(3)
+    try:
+        o = B.attn3d(dev(q, torch.bfloat16), dev(k, torch.bfloat16), dev(v, torch.bfloat16), 0.125)
+        torch.cuda.synchronize()
+    finally:
+        B.ps_set_kernel_path(prev)
+    assert_close_bf16(host(o), O.attn3d(q, k, v, 0.125), 2e-2, max_tol=3e-2)
+
+
+def test_attention_bf16_mixed_heads_take_different_kernels():
+    """One head with huge scores (over the norm bound) next to ordinary heads: each head is done by the
+    kernel its bound selects, and both agree with the oracle."""
+    N = 700
+    q, k, v = I.make_qkv(1, N, 3, 64, dtype="bf16")
+    q[:, :, 1, :] *= 16.0
+    k[:, :, 1, :] *= 16.0                             # head 1: exponents ~ N(0, 370^2) at scale 0.125
+    q, k = I.round_to_bf16(q), I.round_to_bf16(k)
+    o = B.attn3d(dev(q, torch.bfloat16), dev(k, torch.bfloat16), dev(v, torch.bfloat16), 0.125)
+    torch.cuda.synchronize()
+    assert torch.isfinite(o).all()
+    ref = O.attn3d(q, k, v, 0.125)
+    for h in range(3):
+        assert_close_bf16(host(o)[:, :, h], ref[:, :, h], 2e-2, max_tol=3e-2)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_attention_invariants(dtype):
     td = torch.float32 if dtype == "f32" else torch.bfloat16
