@@ -63,7 +63,8 @@ def lib():
         "dit_profile_read": (i32, [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
         "attn3d_workspace_bytes": (sz, [i32, i32, i32, i32, i32]),
         "attn3d": (i32, [vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, vp, sz, vp]),
-        "dit_linear": (i32, [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp]),
+        "dit_linear_workspace_bytes": (C.c_size_t, [i32, i32, i32, i32]),
+        "dit_linear": (i32, [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, C.c_size_t, vp]),
         "sampler_step_workspace_bytes": (sz, [sz]),
         "sampler_step": (i32, [vp, vp, vp, vp, C.c_double, C.c_double, sz, vp, vp, sz, vp]),
         "rel_mae_workspace_bytes": (sz, [sz]),
@@ -82,7 +83,7 @@ def lib():
 
 EXPORTED = ("ps_strerror", "ps_set_kernel_path", "dit_num_weights", "dit_create", "dit_destroy",
             "dit_workspace_bytes", "dit_forward", "dit_profile_enable", "dit_profile_read",
-            "attn3d_workspace_bytes", "attn3d", "dit_linear", "sampler_step_workspace_bytes", "sampler_step",
+            "attn3d_workspace_bytes", "attn3d", "dit_linear_workspace_bytes", "dit_linear", "sampler_step_workspace_bytes", "sampler_step",
             "rel_mae_workspace_bytes", "rel_mae", "ddim_coefficients", "sampler_workspace_bytes", "sampler_run")
 
 
@@ -196,13 +197,16 @@ def attn3d(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, scale: float,
 
 
 def dit_linear(a: torch.Tensor, w: torch.Tensor, bias: torch.Tensor, act: int = 0,
-               out: Optional[torch.Tensor] = None) -> torch.Tensor:
+               out: Optional[torch.Tensor] = None, use_workspace: bool = True) -> torch.Tensor:
     M, K = a.shape
     Nn = w.shape[0]
     dt = PS_BF16 if a.dtype == torch.bfloat16 else PS_F32
     if out is None:
         out = torch.empty(M, Nn, dtype=a.dtype, device=a.device)
-    _check(lib().dit_linear(_ptr(a), _ptr(w), _ptr(bias), _ptr(out), M, Nn, K, int(act), dt, _stream()), "dit_linear")
+    nb = lib().dit_linear_workspace_bytes(M, Nn, K, dt) if use_workspace else 0
+    ws = _workspace(nb, a.device)
+    _check(lib().dit_linear(_ptr(a), _ptr(w), _ptr(bias), _ptr(out), M, Nn, K, int(act), dt, _ptr(ws), nb, _stream()),
+           "dit_linear")
     return out
 
 

@@ -1,5 +1,6 @@
 // C ABI: argument validation, the DiT forward schedule, and the reuse-then-predict run
 // (Algorithm 1 with every rank of a cycle simulated on one device).
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -42,7 +43,7 @@ struct dit {
 namespace {
 
 struct WsLayout {
-    size_t X, H, QKV, mod, modf, sinus, hid, cvec, rcos, rsin, attn, total;
+    size_t X, H, QKV, mod, modf, sinus, hid, cvec, rcos, rsin, attn, gemm, gemm_bytes, total;
 };
 
 WsLayout ws_layout(const dit* d, int batch) {
@@ -63,6 +64,15 @@ WsLayout ws_layout(const dit* d, int batch) {
     w.rcos = take((size_t)d->Nv * (c.head_dim / 2) * 4);
     w.rsin = take((size_t)d->Nv * (c.head_dim / 2) * 4);
     w.attn = take(attention_workspace_bytes(c.dtype, batch, d->N, c.heads, c.head_dim));
+    {   // K-split scratch of the projections: the largest need of the four shapes of a layer
+        const int Mi = (int)M, Di = (int)D, Fi = (int)(c.mlp_ratio * D);
+        size_t g = gemm_split_workspace_bytes(c.dtype, Mi, 3 * Di, Di);
+        g = std::max(g, gemm_split_workspace_bytes(c.dtype, Mi, Di, Di));
+        g = std::max(g, gemm_split_workspace_bytes(c.dtype, Mi, Fi, Di));
+        g = std::max(g, gemm_split_workspace_bytes(c.dtype, Mi, Di, Fi));
+        w.gemm_bytes = g;
+        w.gemm = take(g);
+    }
     w.total = off;
     return w;
 }
@@ -139,6 +149,7 @@ int forward_impl(dit* d, const float* x, const void* ctx, const int32_t* t_host,
     float* rcos = (float*)(base + w.rcos);
     float* rsin = (float*)(base + w.rsin);
     void* attn_ws = attention_workspace_bytes(dt, batch, N, c.heads, c.head_dim) ? base + w.attn : nullptr;
+    float* gemm_ws = w.gemm_bytes ? (float*)(base + w.gemm) : nullptr;
     Prof prof{d, st};
     TokenGeom geom{N, c.text_tokens};
     const long mod_bs = (long)L * 12 * D;
@@ -177,6 +188,7 @@ int forward_impl(dit* d, const float* x, const void* ctx, const int32_t* t_host,
         eq.kind = EPI_QKV_ROPE; eq.bias = lw.b_qkv; eq.D = D; eq.geom = geom;
         eq.rope_cos = rcos; eq.rope_sin = rsin; eq.head_dim = c.head_dim;
         eq.q_scale = prescale ? scale * 1.4426950408889634f : 1.0f;
+        eq.split_ws = gemm_ws; eq.split_ws_bytes = w.gemm_bytes;
         PS_TIMED(KC_QKV, launch_gemm(dt, Hb, lw.W_qkv, QKV, M, 3 * D, D, eq, st));
         // o = attention(q, k, v) -> Hb (token-major, heads concatenated)
         const char* qp = (const char*)QKV;
@@ -186,11 +198,13 @@ int forward_impl(dit* d, const float* x, const void* ctx, const int32_t* t_host,
         Epilogue eo{};
         eo.kind = EPI_GATE_RESIDUAL; eo.bias = lw.b_o; eo.resid = X; eo.mod_layer = mod_l;
         eo.mod_batch_stride = mod_bs; eo.gate_chunk = 2; eo.D = D; eo.geom = geom;
+        eo.split_ws = gemm_ws; eo.split_ws_bytes = w.gemm_bytes;
         PS_TIMED(KC_OPROJ, launch_gemm(dt, Hb, lw.W_o, nullptr, M, D, D, eo, st));
         // h2 = LN(X)(1+scale_m)+shift_m ; u = GELU(W_1 h2 + b_1) ; X += gate_m * (W_2 u + b_2)
         PS_TIMED(KC_LN, launch_ln_modulate(dt, X, Hb, M, D, c.ln_eps, mod_l, mod_bs, 3, 4, geom, st));
         Epilogue e1{};
         e1.kind = EPI_BIAS_GELU; e1.bias = lw.b_1;
+        e1.split_ws = gemm_ws; e1.split_ws_bytes = w.gemm_bytes;
         PS_TIMED(KC_FC1, launch_gemm(dt, Hb, lw.W_1, QKV, M, c.mlp_ratio * D, D, e1, st));
         Epilogue e2 = eo;
         e2.bias = lw.b_2; e2.gate_chunk = 5;
@@ -347,16 +361,24 @@ int attn3d(const void* q, const void* k, const void* v, void* o, int batch, int 
     return e == hipSuccess ? PS_OK : PS_ERR_HIP;
 }
 
+size_t dit_linear_workspace_bytes(int m, int n_out, int k, int dtype) {
+    if (m < 1 || n_out < 2 || k < 8 || (dtype != PS_F32 && dtype != PS_BF16)) return 0;
+    return align256(gemm_split_workspace_bytes(dtype, m, n_out, k));
+}
+
 int dit_linear(const void* a, const void* w, const float* bias, void* out, int m, int n_out, int k, int act,
-               int dtype, void* hip_stream) {
+               int dtype, void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (!a || !w || !bias || !out) return PS_ERR_NULL;
     if (dtype != PS_F32 && dtype != PS_BF16) return PS_ERR_DTYPE;
     if (m < 1 || n_out < 2 || k < 8 || (n_out & 1) || (k % 8) || (act != 0 && act != 1)) return PS_ERR_SHAPE;
     if (!aligned(a, 16) || !aligned(w, 16) || !aligned(out, 16) || !aligned(bias, 16) || out == a || out == w)
         return PS_ERR_SHAPE;
+    if (workspace && !aligned(workspace, 256)) return PS_ERR_WORKSPACE;
     Epilogue ep{};
     ep.kind = act ? EPI_BIAS_GELU : EPI_BIAS;
     ep.bias = bias;
+    ep.split_ws = (float*)workspace;                 // used only if large enough for the shape's split
+    ep.split_ws_bytes = workspace ? workspace_bytes : 0;
     hipError_t e = launch_gemm(dtype, a, w, out, m, n_out, k, ep, (hipStream_t)hip_stream);
     return e == hipSuccess ? PS_OK : PS_ERR_HIP;
 }

@@ -52,7 +52,14 @@ struct Epilogue {
     const float* rope_sin;
     int head_dim;
     float q_scale;            // factor applied to the q columns (col < D) after the rotation
+    // optional scratch for the bf16 MFMA kernel: with it, the output tiles of the last, partial round of
+    // workgroups are split along K and their fp32 partial sums pass through this buffer
+    float* split_ws;
+    size_t split_ws_bytes;
 };
+
+// scratch that lets launch_gemm split its last partial round along K (0: the shape does not profit)
+size_t gemm_split_workspace_bytes(int dtype, int M, int Nn, int K);
 
 // ---- launchers (each validates nothing; callers have checked shapes) -----------------
 // C[M, Nn] = A[M, K] * W[Nn, K]^T with epilogue.  A, W, C in `dtype` (C ignored for

@@ -196,7 +196,7 @@ __device__ __forceinline__ void wait_vmcnt() {
 template <int BM, int BN, int WR, int WC, int KIND>
 __global__ void __launch_bounds__(WR * WC * 64, (WR * WC == 4 && BM * BN <= 128 * 128) ? 2 : 1)
 gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf16_t* __restrict__ C,
-                 int M, int Nn, int K, int tiles_m, int tiles_n, Epilogue ep) {
+                 int M, int Nn, int K, int tiles_m, int tiles_n, int full_tiles, int nsplit, Epilogue ep) {
     constexpr int BK = 64, KS = BK / 16;
     constexpr int NW = WR * WC;
     constexpr int WM = BM / WR, WN = BN / WC;
@@ -216,7 +216,20 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
     const int wm = wave / WC, wn = wave % WC;
     // tiles walk column-fastest inside groups of 8 tile rows, so the workgroups resident on
     // one XCD cover a compact block of the output and reuse each other's panels in L2
-    int tile = xcd_remap(blockIdx.x, tiles_m * tiles_n);
+    // The first full_tiles workgroups compute one output tile each.  The tiles beyond them -- the last, partial
+    // round of the chip's workgroup slots -- are each split nsplit ways along K; such a workgroup leaves its
+    // fp32 partial sums in ep.split_ws (in accumulator layout) for gemm_tail_kernel.
+    const int nk = K / BK;
+    int tile, piece = -1, k0 = 0, k1 = nk;
+    if ((int)blockIdx.x < full_tiles) {
+        tile = xcd_remap(blockIdx.x, full_tiles);
+    } else {
+        piece = blockIdx.x - full_tiles;
+        tile = full_tiles + piece / nsplit;
+        const int pi = piece % nsplit;
+        k0 = nk * pi / nsplit;
+        k1 = nk * (pi + 1) / nsplit;
+    }
     int m0, n0;
     {
         constexpr int GM = 8;
@@ -247,9 +260,8 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
         }
     }
     const unsigned lds_base = (unsigned)(size_t)PS_LDS_PTR(lds);
-    const int nk = K / BK;
-    auto issue = [&](int kt) {
-        const int kc = kt < nk ? kt : nk - 1;            // past the end: harmless re-read keeps vmcnt uniform
+    auto issue = [&](int kt) {                           // kt counts from k0; stage parity follows kt
+        const int kc = k0 + kt < k1 ? k0 + kt : k1 - 1;  // past the end: harmless re-read keeps vmcnt uniform
         const unsigned st = lds_base + (kt & 1) * STAGE;
 #pragma unroll
         for (int i = 0; i < GPW; ++i) {
@@ -291,7 +303,7 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
     __syncthreads();
     issue(1);
     load_frags(0, lds, 0);
-    for (int kt = 0; kt < nk; ++kt) {
+    for (int kt = 0; kt < k1 - k0; ++kt) {
         const unsigned char* st = lds + (kt & 1) * STAGE;
         const unsigned char* nx = lds + ((kt + 1) & 1) * STAGE;
 #pragma unroll
@@ -325,6 +337,19 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
     wait_vmcnt<0>();                                     // the look-ahead loads past the end have landed
     __syncthreads();                                     // ... in every wave: the stage memory is free
 
+    if (piece >= 0) {
+        // [piece][wave][i][j][lane][16 accumulator registers]
+        float* pp = ep.split_ws + (((long)piece * NW + wave) * (TM * TN) * 64 + lane) * 16;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int e4 = 0; e4 < 4; ++e4)
+                    *reinterpret_cast<f32x4_t*>(pp + (i * TN + j) * 64 * 16 + e4 * 4) =
+                        f32x4_t{acc[i][j][e4 * 4], acc[i][j][e4 * 4 + 1], acc[i][j][e4 * 4 + 2], acc[i][j][e4 * 4 + 3]};
+        return;
+    }
     float* patch = reinterpret_cast<float*>(lds) + wave * EPI_LDS_FLOATS;
     const bool interior = (m0 + BM <= M) && (n0 + BN <= Nn);
     if (interior)
@@ -333,47 +358,138 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
         wave_epilogue<TM, KIND, true>(acc, ep, C, M, Nn, m0 + wm * WM, n0 + wn * WN, lane, patch);
 }
 
+// Sums the K-split pieces of the tail tiles (fixed order: deterministic) and applies the epilogue; one
+// workgroup per tail tile, same wave layout as gemm_mfma_kernel.
+template <int BM, int BN, int WR, int WC, int KIND>
+__global__ void __launch_bounds__(WR * WC * 64)
+gemm_tail_kernel(bf16_t* __restrict__ C, int M, int Nn, int tiles_m, int tiles_n, int full_tiles, int nsplit,
+                 Epilogue ep) {
+    constexpr int NW = WR * WC;
+    constexpr int WM = BM / WR, WN = BN / WC;
+    constexpr int TM = WM / 32, TN = WN / 32;
+    __shared__ __attribute__((aligned(16))) float patches[NW * EPI_LDS_FLOATS];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave / WC, wn = wave % WC;
+    const int tile = full_tiles + blockIdx.x;
+    int m0, n0;
+    {
+        constexpr int GM = 8;
+        int per_band = GM * tiles_n;
+        int band = tile / per_band, in_band = tile % per_band;
+        int rows_here = min(GM, tiles_m - band * GM);
+        m0 = (band * GM + in_band % rows_here) * BM;
+        n0 = (in_band / rows_here) * BN;
+    }
+    f32x16_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    for (int pi = 0; pi < nsplit; ++pi) {
+        const float* pp = ep.split_ws + ((((long)blockIdx.x * nsplit + pi) * NW + wave) * (TM * TN) * 64 + lane) * 16;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int e4 = 0; e4 < 4; ++e4) {
+                    const f32x4_t v = *reinterpret_cast<const f32x4_t*>(pp + (i * TN + j) * 64 * 16 + e4 * 4);
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) acc[i][j][e4 * 4 + c] += v[c];
+                }
+    }
+    wave_epilogue<TM, KIND, true>(acc, ep, C, M, Nn, m0 + wm * WM, n0 + wn * WN, lane, patches + wave * EPI_LDS_FLOATS);
+}
+
 bool gemm_mfma_supported(int M, int Nn, int K) {
     return K % 64 == 0 && Nn % 4 == 0 && M >= 1 && Nn >= 64 && K >= 64 && (long)M * Nn < (1L << 31);
 }
 
-template <int BM, int BN, int WR, int WC>
-static hipError_t launch_tile(const bf16_t* A, const bf16_t* W, bf16_t* C, int M, int Nn, int K,
-                              const Epilogue& ep, hipStream_t st) {
-    int tm = (M + BM - 1) / BM, tn = (Nn + BN - 1) / BN;
-    dim3 grid(tm * tn), block(WR * WC * 64);
-    switch (ep.kind) {
-        case EPI_BIAS:
-            gemm_mfma_kernel<BM, BN, WR, WC, EPI_BIAS><<<grid, block, 0, st>>>(A, W, C, M, Nn, K, tm, tn, ep);
-            break;
-        case EPI_BIAS_GELU:
-            gemm_mfma_kernel<BM, BN, WR, WC, EPI_BIAS_GELU><<<grid, block, 0, st>>>(A, W, C, M, Nn, K, tm, tn, ep);
-            break;
-        case EPI_GATE_RESIDUAL:
-            gemm_mfma_kernel<BM, BN, WR, WC, EPI_GATE_RESIDUAL><<<grid, block, 0, st>>>(A, W, C, M, Nn, K, tm, tn, ep);
-            break;
-        case EPI_QKV_ROPE:
-            gemm_mfma_kernel<BM, BN, WR, WC, EPI_QKV_ROPE><<<grid, block, 0, st>>>(A, W, C, M, Nn, K, tm, tn, ep);
-            break;
-        default: return hipErrorInvalidValue;
+// How a shape is spread over the chip: which tile variant, how many tiles run whole and how the rest is split.
+struct GemmPlan { int variant, tiles_m, tiles_n, full, nsplit, pieces; size_t ws_bytes; };
+static int gemm_compute_units() {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            cus = 256;
     }
-    return hipGetLastError();
+    return cus;
 }
-
 static int g_gemm_variant = 0;   // tuning hook: 0 auto
 void set_gemm_variant(int v) { g_gemm_variant = v; }
 
-hipError_t launch_gemm_mfma(const bf16_t* A, const bf16_t* W, bf16_t* C, int M, int Nn, int K,
-                            const Epilogue& ep, hipStream_t st) {
-    int v = g_gemm_variant;
-    if (v == 0) {
+static GemmPlan gemm_plan(int M, int Nn, int K, bool allow_split) {
+    GemmPlan p{};
+    p.variant = g_gemm_variant;
+    if (p.variant == 0) {
         // measured at 17776 tokens: wide outputs are better off with the 256x256 tile's lower L2
         // traffic; narrow ones with two co-resident 128x128 workgroups that hide each other's epilogue
-        v = (M >= 1024 && Nn >= 5760) ? 1 : 2;
+        p.variant = (M >= 1024 && Nn >= 5760) ? 1 : 2;
     }
-    switch (v) {
-        case 1: return launch_tile<256, 256, 2, 4>(A, W, C, M, Nn, K, ep, st);   // 8 waves, 128x64 each
-        case 2: return launch_tile<128, 128, 2, 2>(A, W, C, M, Nn, K, ep, st);   // 4 waves, 64x64 each, 2 per CU
+    const int bm = p.variant == 1 ? 256 : 128, bn = bm;
+    p.tiles_m = (M + bm - 1) / bm;
+    p.tiles_n = (Nn + bn - 1) / bn;
+    const int tiles = p.tiles_m * p.tiles_n;
+    p.full = tiles; p.nsplit = 1; p.pieces = 0; p.ws_bytes = 0;
+    // the last partial round: split along K if the partial sums (two passes over tile-size fp32 per piece) and
+    // the second launch cost less than the round they save -- measured at 17776 tokens: true for the 128x128
+    // tile with a long K (fc2: 0.62 -> 0.57 ms), not for K = 1920 (0.188 -> 0.196 ms) nor for the 256x256 tile
+    const int slots = gemm_compute_units() * (p.variant == 1 ? 1 : 2);
+    const int tail = tiles % slots, nk = K / 64;
+    if (allow_split && p.variant == 2 && K >= 4096 && tail > 0 && tiles > slots) {
+        int ns = slots / tail;
+        if (ns > 8) ns = 8;
+        if (ns > nk / 2) ns = nk / 2;
+        if (ns >= 2) {
+            p.full = tiles - tail; p.nsplit = ns; p.pieces = tail * ns;
+            p.ws_bytes = (size_t)p.pieces * bm * bn * sizeof(float);
+        }
+    }
+    return p;
+}
+
+size_t gemm_split_workspace_bytes(int dtype, int M, int Nn, int K) {
+    if (dtype != PS_BF16 || !gemm_mfma_supported(M, Nn, K)) return 0;
+    return gemm_plan(M, Nn, K, true).ws_bytes;
+}
+
+template <int BM, int BN, int WR, int WC, int KIND>
+static hipError_t launch_kind(const bf16_t* A, const bf16_t* W, bf16_t* C, int M, int Nn, int K, const GemmPlan& p,
+                              const Epilogue& ep, hipStream_t st) {
+    dim3 block(WR * WC * 64);
+    gemm_mfma_kernel<BM, BN, WR, WC, KIND><<<p.full + p.pieces, block, 0, st>>>(A, W, C, M, Nn, K, p.tiles_m, p.tiles_n,
+                                                                                p.full, p.nsplit, ep);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || p.pieces == 0) return e;
+    gemm_tail_kernel<BM, BN, WR, WC, KIND><<<p.pieces / p.nsplit, block, 0, st>>>(C, M, Nn, p.tiles_m, p.tiles_n, p.full,
+                                                                                  p.nsplit, ep);
+    return hipGetLastError();
+}
+
+template <int BM, int BN, int WR, int WC>
+static hipError_t launch_tile(const bf16_t* A, const bf16_t* W, bf16_t* C, int M, int Nn, int K, const GemmPlan& p,
+                              const Epilogue& ep, hipStream_t st) {
+    switch (ep.kind) {
+        case EPI_BIAS: return launch_kind<BM, BN, WR, WC, EPI_BIAS>(A, W, C, M, Nn, K, p, ep, st);
+        case EPI_BIAS_GELU: return launch_kind<BM, BN, WR, WC, EPI_BIAS_GELU>(A, W, C, M, Nn, K, p, ep, st);
+        case EPI_GATE_RESIDUAL: return launch_kind<BM, BN, WR, WC, EPI_GATE_RESIDUAL>(A, W, C, M, Nn, K, p, ep, st);
+        case EPI_QKV_ROPE: return launch_kind<BM, BN, WR, WC, EPI_QKV_ROPE>(A, W, C, M, Nn, K, p, ep, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_gemm_mfma(const bf16_t* A, const bf16_t* W, bf16_t* C, int M, int Nn, int K,
+                            const Epilogue& ep, hipStream_t st) {
+    GemmPlan p = gemm_plan(M, Nn, K, ep.split_ws != nullptr && (get_kernel_path() & 0xff) != 4);
+    if (p.ws_bytes > ep.split_ws_bytes) p = gemm_plan(M, Nn, K, false);
+    switch (p.variant) {
+        case 1: return launch_tile<256, 256, 2, 4>(A, W, C, M, Nn, K, p, ep, st);   // 8 waves, 128x64 each
+        case 2: return launch_tile<128, 128, 2, 2>(A, W, C, M, Nn, K, p, ep, st);   // 4 waves, 64x64 each, 2 per CU
         default: return hipErrorInvalidValue;
     }
 }

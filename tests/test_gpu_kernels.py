@@ -302,3 +302,15 @@ def test_linear_full_shapes_sampled_rows(Nn, K, act):
         ref = O.gelu_tanh(ref)
     assert_close_bf16(host(out[torch.from_numpy(rows).to(DEV)]), ref, 5e-3, max_tol=1e-2)
     assert torch.isfinite(out).all()
+    # the long-K shape splits its last partial round of tiles along K when given scratch (the sampled rows M-129
+    # and M-1 lie in those tiles); without scratch the same product is computed unsplit
+    nb = B.lib().dit_linear_workspace_bytes(M, Nn, K, 1)
+    if K == 7680:
+        assert nb > 0
+    if nb:
+        out2 = B.dit_linear(dev(a, torch.bfloat16), dev(w, torch.bfloat16), dev(bias), act, use_workspace=False)
+        torch.cuda.synchronize()
+        assert_close_bf16(host(out2[torch.from_numpy(rows).to(DEV)]), ref, 5e-3, max_tol=1e-2)
+        d = (out2.float() - out.float()).abs()
+        assert float(d.max()) <= 2.0 ** -6 * float(out.float().abs().max())      # a bf16 rounding step at most
+        assert float((d > 0).float().mean()) < 0.02                              # and only in the split tiles

@@ -137,6 +137,25 @@ def test_attn3d_validation():
     assert L.attn3d_workspace_bytes(0, 100, 2, 16, 0) == 0
 
 
+def test_dit_linear_validation_and_workspace_size():
+    L = B.lib()
+    A, W, BI, OUT, WS = 0x1000, 0x2000, 0x3000, 0x4000, 0x10000
+    f = lambda **k: L.dit_linear(k.get("a", A), W, k.get("bias", BI), k.get("out", OUT), k.get("m", 8), k.get("n", 64),
+                                 k.get("k", 64), k.get("act", 0), k.get("dt", 1), k.get("ws", None), k.get("wsb", 0), None)
+    assert f(a=None) == -1 and f(bias=None) == -1 and f(out=None) == -1
+    assert f(dt=7) == -3
+    assert f(m=0) == -2 and f(n=63) == -2 and f(k=60) == -2 and f(act=2) == -2
+    assert f(out=A) == -2 and f(a=A + 2) == -2 and f(bias=BI + 4) == -2
+    assert f(ws=WS + 16, wsb=1 << 20) == -4
+    # scratch is only asked for where the K-split of the last partial round of tiles pays: 17776 x 1920 x 7680
+    # leaves 37 of 2085 tiles of 128 x 128 for a 5th round on 512 workgroup slots; they are split 8 ways
+    assert L.dit_linear_workspace_bytes(17776, 1920, 7680, 1) == 37 * 8 * 128 * 128 * 4
+    assert L.dit_linear_workspace_bytes(17776, 1920, 1920, 1) == 0       # short K
+    assert L.dit_linear_workspace_bytes(17776, 7680, 1920, 1) == 0       # 256 x 256 tiles
+    assert L.dit_linear_workspace_bytes(17776, 1920, 7680, 0) == 0       # fp32 runs on the generic kernel
+    assert L.dit_linear_workspace_bytes(100, 64, 64, 1) == 0
+
+
 def test_sampler_step_and_rel_mae_validation():
     L = B.lib()
     X, E, P, WS = 0x1000, 0x2000, 0x3000, 0x10000
