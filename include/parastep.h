@@ -169,6 +169,21 @@ PS_API int rel_mae(const float* a, const float* b, size_t n, float* out3,
 PS_API int ddim_coefficients(int train_steps, double beta_start, double beta_end, int steps,
                       int32_t* timesteps_out, double* a_out, double* b_out);
 
+/* Host-only tables of two other deterministic schedulers the paper runs its method under; both
+ * are x' = a*x + b*eps for the same fused kernel and the same loop.
+ * euler_discrete_coefficients: the Euler step in sigma space (the scheduler Section 4.2 names
+ * for SVD), for samples held as x = x0 + sigma*eps: on the DDIM grid tau_i, with
+ * sigma_t = sqrt((1 - abar_t) / abar_t) and sigma = 0 after the last step,
+ * a_i = 1, b_i = sigma_next - sigma_tau_i.
+ * flow_euler_coefficients: Flow Matching's discretised ODE (Preliminaries, "Flow Matching"),
+ * z_{t+dt} = z_t + dt*v(z_t, t), t from 0 (reference sample) to 1 on a uniform grid:
+ * a_i = 1, b_i = 1/steps; the predictor is given the time index floor(i*train_steps/steps),
+ * which ascends.  Outputs are HOST arrays of length `steps`. */
+PS_API int euler_discrete_coefficients(int train_steps, double beta_start, double beta_end, int steps,
+                                int32_t* timesteps_out, double* a_out, double* b_out);
+PS_API int flow_euler_coefficients(int train_steps, int steps, int32_t* timesteps_out, double* a_out,
+                            double* b_out);
+
 /* ------------------------------------------------------------- reuse-then-predict run
  * Algorithm 1 with all ranks of a cycle simulated on one device.
  *   warmup     first `warmup` steps run the original process; must be >= 1 unless
@@ -180,7 +195,7 @@ PS_API int ddim_coefficients(int train_steps, double beta_start, double beta_end
  *   mode       0 reuse-then-predict, 1 direct reuse (predict only in round 0) */
 typedef struct {
     int steps;
-    const int32_t* timesteps;   /* HOST [steps], descending */
+    const int32_t* timesteps;   /* HOST [steps], strictly monotonic (descending for diffusion grids) */
     const double* coef_a;       /* HOST [steps] */
     const double* coef_b;       /* HOST [steps] */
     int warmup;
@@ -196,9 +211,13 @@ PS_API size_t sampler_workspace_bytes(const dit* d, const sampler_schedule* s);
  * ctx as in dit_forward with B = 1 (it is shared by all ranks).
  * step_sums: DEVICE fp32 [steps][4] or NULL; row i holds sampler_step's sums4 for the
  * update rank 0 takes at step i (row 0's eps_prev terms are 0, sum|eps|).
+ * trajectory_out: DEVICE fp32 [steps][C,F,H,W] or NULL; slice i receives the sample after
+ * step i (rank 0's, i.e. the one the run returns at the end), so that two runs can be
+ * compared step by step with rel_mae (the deviation curves of Section 3.1's comparison of
+ * direct reuse with reuse-then-predict).  It must not overlap x_T or x0_out.
  * calls_out: HOST, optional; receives the number of predictor launches. */
 PS_API int sampler_run(dit* d, const sampler_schedule* s, const float* x_T, const void* ctx,
-                float* x0_out, float* step_sums, int* calls_out,
+                float* x0_out, float* step_sums, float* trajectory_out, int* calls_out,
                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
 #ifdef __cplusplus

@@ -81,6 +81,29 @@ def ddim_coefficients(train_steps=1000, beta_start=1e-4, beta_end=2e-2, steps=50
     return tau, a, b
 
 
+def euler_discrete_coefficients(train_steps=1000, beta_start=1e-4, beta_end=2e-2, steps=50):
+    """Deterministic Euler step in sigma space, the scheduler Section 4.2 names for SVD.  Samples are held
+    as x = x0 + sigma*eps with sigma_t = sqrt((1-abar_t)/abar_t); along the DDIM grid, with sigma = 0
+    after the last step:  x' = x + (sigma_next - sigma_t) * eps,  i.e. a = 1, b = sigma_next - sigma_t."""
+    abar = ddim_alphas_cumprod(train_steps, beta_start, beta_end)
+    tau = ddim_timesteps(train_steps, steps)
+    sigma = np.sqrt((1.0 - abar) / abar)
+    a = np.ones(steps, dtype=F64)
+    b = np.empty(steps, dtype=F64)
+    for i in range(steps):
+        s_next = sigma[tau[i + 1]] if i + 1 < steps else 0.0
+        b[i] = s_next - sigma[tau[i]]
+    return tau, a, b
+
+
+def flow_euler_coefficients(train_steps=1000, steps=50):
+    """Flow Matching (Preliminaries): z_{t+dt} = z_t + dt * v(z_t, t), integrated from t = 0 (reference
+    sample) to t = 1 on a uniform grid: dt = 1/steps, a = 1, b = dt.  The predictor is given the integer
+    time index floor(t_i * train_steps) with t_i = i/steps."""
+    tau = np.array([(i * train_steps) // steps for i in range(steps)], dtype=np.int64)
+    return tau, np.ones(steps, dtype=F64), np.full(steps, 1.0 / steps, dtype=F64)
+
+
 def sampler_step(x, eps, a, b):
     """x_{t-1} = Scheduler(x_t, t, eps_t) for DDIM: a*x + b*eps, element-wise."""
     return F64(a) * np.asarray(x, dtype=F64) + F64(b) * np.asarray(eps, dtype=F64)

@@ -71,8 +71,12 @@ def lib():
         "rel_mae": (i32, [vp, vp, sz, vp, vp, sz, vp]),
         "ddim_coefficients": (i32, [i32, C.c_double, C.c_double, i32, C.POINTER(C.c_int32),
                                     C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+        "euler_discrete_coefficients": (i32, [i32, C.c_double, C.c_double, i32, C.POINTER(C.c_int32),
+                                              C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+        "flow_euler_coefficients": (i32, [i32, i32, C.POINTER(C.c_int32), C.POINTER(C.c_double),
+                                          C.POINTER(C.c_double)]),
         "sampler_workspace_bytes": (sz, [vp, C.POINTER(_Schedule)]),
-        "sampler_run": (i32, [vp, C.POINTER(_Schedule), vp, vp, vp, vp, C.POINTER(i32), vp, sz, vp]),
+        "sampler_run": (i32, [vp, C.POINTER(_Schedule), vp, vp, vp, vp, vp, C.POINTER(i32), vp, sz, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -84,7 +88,8 @@ def lib():
 EXPORTED = ("ps_strerror", "ps_set_kernel_path", "dit_num_weights", "dit_create", "dit_destroy",
             "dit_workspace_bytes", "dit_forward", "dit_profile_enable", "dit_profile_read",
             "attn3d_workspace_bytes", "attn3d", "dit_linear_workspace_bytes", "dit_linear", "sampler_step_workspace_bytes", "sampler_step",
-            "rel_mae_workspace_bytes", "rel_mae", "ddim_coefficients", "sampler_workspace_bytes", "sampler_run")
+            "rel_mae_workspace_bytes", "rel_mae", "ddim_coefficients", "euler_discrete_coefficients",
+            "flow_euler_coefficients", "sampler_workspace_bytes", "sampler_run")
 
 
 def _check(status: int, where: str):
@@ -241,6 +246,23 @@ def ddim_coefficients(steps: int, train_steps: int = 1000, beta_start: float = 1
     return (np.array(ts[:], dtype=np.int32), np.array(a[:], dtype=np.float64), np.array(b[:], dtype=np.float64))
 
 
+def euler_discrete_coefficients(steps: int, train_steps: int = 1000, beta_start: float = 1e-4, beta_end: float = 2e-2):
+    ts = (C.c_int32 * steps)()
+    a = (C.c_double * steps)()
+    b = (C.c_double * steps)()
+    _check(lib().euler_discrete_coefficients(train_steps, beta_start, beta_end, steps, ts, a, b),
+           "euler_discrete_coefficients")
+    return (np.array(ts[:], dtype=np.int32), np.array(a[:], dtype=np.float64), np.array(b[:], dtype=np.float64))
+
+
+def flow_euler_coefficients(steps: int, train_steps: int = 1000):
+    ts = (C.c_int32 * steps)()
+    a = (C.c_double * steps)()
+    b = (C.c_double * steps)()
+    _check(lib().flow_euler_coefficients(train_steps, steps, ts, a, b), "flow_euler_coefficients")
+    return (np.array(ts[:], dtype=np.int32), np.array(a[:], dtype=np.float64), np.array(b[:], dtype=np.float64))
+
+
 # ------------------------------------------------------------------ reuse-then-predict
 class Schedule:
     """Host arrays behind a `sampler_schedule` (kept alive while the struct is in use)."""
@@ -257,8 +279,9 @@ class Schedule:
                            int(batched), int(mode))
 
 
-def sampler_run(d: Dit, sched: Schedule, x_T: torch.Tensor, ctx: Optional[torch.Tensor]):
-    """Returns (x0, step_sums [steps,4], predictor launches)."""
+def sampler_run(d: Dit, sched: Schedule, x_T: torch.Tensor, ctx: Optional[torch.Tensor],
+                want_trajectory: bool = False):
+    """Returns (x0, step_sums [steps,4], predictor launches), plus the per-step samples [steps, ...] if asked."""
     L = lib()
     nb = L.sampler_workspace_bytes(d.handle, C.byref(sched.c))
     if nb == 0:
@@ -266,9 +289,13 @@ def sampler_run(d: Dit, sched: Schedule, x_T: torch.Tensor, ctx: Optional[torch.
     ws = _workspace(nb, x_T.device)
     x0 = torch.empty_like(x_T)
     sums = torch.zeros(len(sched.ts), 4, dtype=torch.float32, device=x_T.device)
+    traj = (torch.empty((len(sched.ts),) + tuple(x_T.shape), dtype=torch.float32, device=x_T.device)
+            if want_trajectory else None)
     calls = C.c_int(0)
-    _check(L.sampler_run(d.handle, C.byref(sched.c), _ptr(x_T), _ptr(ctx), _ptr(x0), _ptr(sums), C.byref(calls),
-                         _ptr(ws), nb, _stream()), "sampler_run")
+    _check(L.sampler_run(d.handle, C.byref(sched.c), _ptr(x_T), _ptr(ctx), _ptr(x0), _ptr(sums), _ptr(traj),
+                         C.byref(calls), _ptr(ws), nb, _stream()), "sampler_run")
+    if want_trajectory:
+        return x0, sums, calls.value, traj
     return x0, sums, calls.value
 
 

@@ -433,6 +433,40 @@ int ddim_coefficients(int train_steps, double beta_start, double beta_end, int s
     return PS_OK;
 }
 
+int euler_discrete_coefficients(int train_steps, double beta_start, double beta_end, int steps,
+                                int32_t* timesteps_out, double* a_out, double* b_out) {
+    if (!timesteps_out || !a_out || !b_out) return PS_ERR_NULL;
+    if (train_steps < 2 || steps < 1 || steps > train_steps) return PS_ERR_SCHEDULE;
+    if (!(beta_start > 0.0) || !(beta_end >= beta_start) || !(beta_end < 1.0)) return PS_ERR_SCHEDULE;
+    std::vector<double> sigma(train_steps);
+    double prod = 1.0;
+    for (int k = 0; k < train_steps; ++k) {
+        double beta = beta_start + (double)k * (beta_end - beta_start) / (double)(train_steps - 1);
+        prod *= 1.0 - beta;
+        sigma[k] = std::sqrt((1.0 - prod) / prod);
+    }
+    int stride = train_steps / steps;
+    for (int i = 0; i < steps; ++i) {
+        int tau = (steps - 1 - i) * stride;
+        double s_next = i + 1 < steps ? sigma[(steps - 2 - i) * stride] : 0.0;
+        timesteps_out[i] = tau;
+        a_out[i] = 1.0;
+        b_out[i] = s_next - sigma[tau];
+    }
+    return PS_OK;
+}
+
+int flow_euler_coefficients(int train_steps, int steps, int32_t* timesteps_out, double* a_out, double* b_out) {
+    if (!timesteps_out || !a_out || !b_out) return PS_ERR_NULL;
+    if (train_steps < 2 || steps < 1 || steps > train_steps) return PS_ERR_SCHEDULE;
+    for (int i = 0; i < steps; ++i) {
+        timesteps_out[i] = (int32_t)(((long)i * train_steps) / steps);
+        a_out[i] = 1.0;
+        b_out[i] = 1.0 / (double)steps;
+    }
+    return PS_OK;
+}
+
 }  // extern "C"
 
 // ----------------------------------------------------------------- reuse-then-predict run
@@ -451,7 +485,9 @@ int plan_schedule(const sampler_schedule* s, RunPlan* plan) {
     if (s->batched && s->mode == 1) return PS_ERR_SCHEDULE;
     for (int i = 0; i < s->steps; ++i) {
         if (s->timesteps[i] < 0 || s->timesteps[i] >= 100000) return PS_ERR_SCHEDULE;
-        if (i > 0 && s->timesteps[i] >= s->timesteps[i - 1]) return PS_ERR_SCHEDULE;
+        if (i > 0 && s->timesteps[i] == s->timesteps[i - 1]) return PS_ERR_SCHEDULE;
+        if (i > 1 && (s->timesteps[i] > s->timesteps[i - 1]) != (s->timesteps[1] > s->timesteps[0]))
+            return PS_ERR_SCHEDULE;                           // strictly monotonic, either way
     }
     plan->warm = s->warmup < s->steps ? s->warmup : s->steps;
     int left = s->steps - plan->warm;
@@ -502,13 +538,16 @@ size_t sampler_workspace_bytes(const dit* d, const sampler_schedule* s) {
 }
 
 int sampler_run(dit* d, const sampler_schedule* s, const float* x_T, const void* ctx, float* x0_out,
-                float* step_sums, int* calls_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+                float* step_sums, float* trajectory_out, int* calls_out, void* workspace, size_t workspace_bytes,
+                void* hip_stream) {
     if (!d || !s || !x_T || !x0_out) return PS_ERR_NULL;
     if (d->cfg.text_tokens > 0 && !ctx) return PS_ERR_NULL;
     RunPlan plan;
     int rc = plan_schedule(s, &plan);
     if (rc != PS_OK) return rc;
     if (!aligned(x_T, 16) || !aligned(x0_out, 16) || (step_sums && !aligned(step_sums, 16))) return PS_ERR_SHAPE;
+    if (trajectory_out && (!aligned(trajectory_out, 16) || trajectory_out == x_T || trajectory_out == x0_out))
+        return PS_ERR_SHAPE;
     RunWs w = run_layout(d, s, plan);
     if (!workspace || !aligned(workspace, 256) || workspace_bytes < w.total) return PS_ERR_WORKSPACE;
 
@@ -530,6 +569,8 @@ int sampler_run(dit* d, const sampler_schedule* s, const float* x_T, const void*
     auto step = [&](const float* x, const float* e, const float* eprev, float* xo, int i, bool record) -> int {
         float* sums = (record && step_sums) ? step_sums + 4 * (size_t)i : nullptr;
         hipError_t err = launch_sampler_step(x, e, eprev, xo, s->coef_a[i], s->coef_b[i], n, sums, red, st);
+        if (err == hipSuccess && record && trajectory_out)       // rank 0's sample after step i
+            err = hipMemcpyAsync(trajectory_out + (size_t)i * n, xo, n * 4, hipMemcpyDeviceToDevice, st);
         return err == hipSuccess ? PS_OK : PS_ERR_HIP;
     };
     auto copy = [&](float* dst, const float* src) -> int {

@@ -43,6 +43,26 @@ def test_ddim_table_matches_oracle(S):
     np.testing.assert_allclose(b, bo, rtol=1e-12)
 
 
+@pytest.mark.parametrize("S", [5, 8, 50])
+def test_euler_and_flow_tables_match_oracle(S):
+    ts, a, b = B.euler_discrete_coefficients(S)
+    tau, ao, bo = O.euler_discrete_coefficients(steps=S)
+    np.testing.assert_array_equal(ts, tau)
+    np.testing.assert_array_equal(a, ao)
+    np.testing.assert_allclose(b, bo, rtol=1e-12)
+    ts, a, b = B.flow_euler_coefficients(S)
+    tau, ao, bo = O.flow_euler_coefficients(steps=S)
+    np.testing.assert_array_equal(ts, tau)
+    np.testing.assert_array_equal(a, ao)
+    np.testing.assert_array_equal(b, bo)
+    L = B.lib()
+    t4 = (C.c_int32 * 4)(); a4 = (C.c_double * 4)(); b4 = (C.c_double * 4)()
+    assert L.euler_discrete_coefficients(1000, 1e-4, 2e-2, 4, t4, None, b4) == -1
+    assert L.euler_discrete_coefficients(1000, 1e-4, 2e-2, 0, t4, a4, b4) == -5
+    assert L.flow_euler_coefficients(1000, 4, None, a4, b4) == -1
+    assert L.flow_euler_coefficients(3, 4, t4, a4, b4) == -5
+
+
 def test_ddim_table_rejects_bad_arguments():
     L = B.lib()
     ts = (C.c_int32 * 4)(); a = (C.c_double * 4)(); b = (C.c_double * 4)()
@@ -189,19 +209,23 @@ def test_schedule_validation():
         _sched(cyc=(2, 0, 4)),                    # zero-length cycle
         _sched(cyc=(17,)),                        # beyond the batch limit
         _sched(mode=2), _sched(batched=1, mode=1), _sched(warmup=-1),
-        _sched(ts=[875, 750, 625, 625, 375, 250, 125, 0]),     # not strictly descending
+        _sched(ts=[875, 750, 625, 625, 375, 250, 125, 0]),     # not strictly monotonic
+        _sched(ts=[875, 750, 625, 700, 375, 250, 125, 0]),     # changes direction
     ]
     for s in bad:
         assert L.sampler_workspace_bytes(h, C.byref(s.c)) == 0
-        assert L.sampler_run(h, C.byref(s.c), 0x1000, None, 0x2000, None, None, 0x10000, 1 << 40, None) == -5
+        assert L.sampler_run(h, C.byref(s.c), 0x1000, None, 0x2000, None, None, None, 0x10000, 1 << 40, None) == -5
+    # an ascending time index (flow matching integrates t from 0 to 1) is as valid as a descending one
+    assert L.sampler_workspace_bytes(h, C.byref(_sched(ts=[0, 125, 250, 375, 500, 625, 750, 875]).c)) > 0
     # window 1 needs no warm-up; all-warm-up needs no cycles
     assert L.sampler_workspace_bytes(h, C.byref(_sched(warmup=0, cyc=[1] * 8).c)) > 0
     assert L.sampler_workspace_bytes(h, C.byref(_sched(warmup=8, cyc=[]).c)) > 0
     # pointer and workspace checks
     need = L.sampler_workspace_bytes(h, C.byref(ok.c))
-    assert L.sampler_run(h, C.byref(ok.c), None, None, 0x2000, None, None, 0x10000, need, None) == -1
-    assert L.sampler_run(h, C.byref(ok.c), 0x1000, None, 0x2000, None, None, 0x10000, need - 1, None) == -4
-    assert L.sampler_run(h, C.byref(ok.c), 0x1000, None, 0x2000, None, None, None, need, None) == -4
+    assert L.sampler_run(h, C.byref(ok.c), None, None, 0x2000, None, None, None, 0x10000, need, None) == -1
+    assert L.sampler_run(h, C.byref(ok.c), 0x1000, None, 0x2000, None, None, None, 0x10000, need - 1, None) == -4
+    assert L.sampler_run(h, C.byref(ok.c), 0x1000, None, 0x2000, None, None, None, None, need, None) == -4
+    assert L.sampler_run(h, C.byref(ok.c), 0x1000, None, 0x2000, None, 0x1000, None, 0x10000, need, None) == -2   # trajectory aliases x_T
     L.dit_destroy(h)
 
 

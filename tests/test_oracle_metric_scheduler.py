@@ -142,3 +142,57 @@ def test_point_mass_data_trajectory():
             ref = x * math.sqrt(1 - ab[tau[i + 1]]) / math.sqrt(1 - ab[tau[0]])
             np.testing.assert_allclose(xx, ref, rtol=0, atol=1e-12)
     np.testing.assert_allclose(xx, 0.0, atol=1e-12)
+
+
+# ------------------------------------------------------------- other deterministic schedulers
+@pytest.mark.parametrize("S", [5, 8, 50])
+def test_euler_discrete_is_ddim_in_sigma_space(S):
+    """Dividing a DDIM sample by sqrt(abar) gives x0 + sigma*eps, and the DDIM update becomes an Euler step in
+    sigma: b_ddim = sqrt(abar_next) * b_euler, a_ddim = sqrt(abar_next / abar_t) (Section 4.2's scheduler
+    against the DDIM of the preliminaries).  A plausible slip (sigma of the wrong grid point, sign) breaks it."""
+    ab = O.ddim_alphas_cumprod()
+    tau, a, b = O.ddim_coefficients(steps=S)
+    tau_e, a_e, b_e = O.euler_discrete_coefficients(steps=S)
+    np.testing.assert_array_equal(tau, tau_e)
+    np.testing.assert_array_equal(a_e, np.ones(S))
+    ab_next = np.array([ab[tau[i + 1]] if i + 1 < S else 1.0 for i in range(S)])
+    np.testing.assert_allclose(b, np.sqrt(ab_next) * b_e, rtol=1e-12, atol=1e-15)
+    assert np.all(b_e < 0)                                    # sigma decreases to 0
+    np.testing.assert_allclose(b_e.sum(), -math.sqrt((1 - ab[tau[0]]) / ab[tau[0]]), rtol=1e-12)   # telescopes
+
+
+def test_euler_discrete_trajectory_equals_scaled_ddim_trajectory():
+    """Same predictor, the two parameterisations: x_euler,i = x_ddim,i / sqrt(abar_i) at every step, and
+    both end at the same x0."""
+    S = 8
+    rng = np.random.default_rng(5)
+    ab = O.ddim_alphas_cumprod()
+    tau, a, b = O.ddim_coefficients(steps=S)
+    _, a_e, b_e = O.euler_discrete_coefficients(steps=S)
+    f = lambda u, t: np.tanh(u) * (1.0 + 0.001 * t)           # a predictor of the sigma-space sample
+    x = rng.standard_normal(16)
+    xe = x / math.sqrt(ab[tau[0]])
+    for i in range(S):
+        x = O.sampler_step(x, f(x / math.sqrt(ab[tau[i]]), tau[i]), a[i], b[i])
+        xe = O.sampler_step(xe, f(xe, tau[i]), a_e[i], b_e[i])
+        ab_next = ab[tau[i + 1]] if i + 1 < S else 1.0
+        np.testing.assert_allclose(xe, x / math.sqrt(ab_next), rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("S", [4, 10, 50])
+def test_flow_euler_closed_forms(S):
+    """Constant velocity moves the sample by exactly that velocity over t in [0, 1]; the straight path of
+    rectified flow (v = z1 - z0) is integrated exactly; v = z gives (1 + 1/S)^S, Euler's approximation of e."""
+    tau, a, b = O.flow_euler_coefficients(steps=S)
+    assert tau[0] == 0 and np.all(np.diff(tau) > 0) and tau[-1] == ((S - 1) * 1000) // S
+    np.testing.assert_array_equal(a, np.ones(S))
+    np.testing.assert_allclose(b.sum(), 1.0, rtol=1e-14)
+    rng = np.random.default_rng(6)
+    z0, z1 = rng.standard_normal(8), rng.standard_normal(8)
+    z = z0.copy()
+    g = z0.copy()
+    for i in range(S):
+        z = O.sampler_step(z, z1 - z0, a[i], b[i])
+        g = O.sampler_step(g, g, a[i], b[i])
+    np.testing.assert_allclose(z, z1, rtol=0, atol=1e-13)
+    np.testing.assert_allclose(g, z0 * (1.0 + 1.0 / S) ** S, rtol=1e-13)
