@@ -193,23 +193,28 @@ __device__ __forceinline__ void wait_vmcnt() {
 }
 
 // One BM x BN output tile per workgroup, WR x WC waves of (BM/WR) x 64 outputs each.
-template <int BM, int BN, int WR, int WC, int KIND>
+// BK: K depth of an LDS stage (64 or 32 bf16 = 128- or 64-byte rows); NST: ring depth.
+template <int BM, int BN, int WR, int WC, int BK, int NST, int KIND>
 __global__ void __launch_bounds__(WR * WC * 64, (WR * WC == 4 && BM * BN <= 128 * 128) ? 2 : 1)
 gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf16_t* __restrict__ C,
                  int M, int Nn, int K, int tiles_m, int tiles_n, int full_tiles, int nsplit, Epilogue ep) {
-    constexpr int BK = 64, KS = BK / 16;
+    static_assert(BK == 64 || BK == 32, "stage depth");
+    constexpr int KS = BK / 16;
     constexpr int NW = WR * WC;
     constexpr int WM = BM / WR, WN = BN / WC;
     constexpr int TM = WM / 32, TN = WN / 32;
     constexpr int ROWB = BK * 2;                         // bytes per LDS row
-    constexpr int GROUPS = (BM + BN) / 8;                // one wave instruction fills 8 rows
+    constexpr int RPI = 1024 / ROWB;                     // rows filled by one wave instruction (8 or 16)
+    constexpr int CPR = ROWB / 16;                       // 16-byte chunks per row (8 or 4)
+    constexpr int GROUPS = (BM + BN) / RPI;
     constexpr int GPW = GROUPS / NW;                     // load instructions per wave per stage
     constexpr int STAGE = (BM + BN) * ROWB;
     static_assert(TN == 2, "the epilogue handles strips of 64 columns per wave");
     static_assert(GROUPS % NW == 0, "rows must split evenly over waves");
-    static_assert(BM % 8 == 0, "a load group must not straddle the A/W boundary");
-    static_assert(NW * EPI_LDS_FLOATS * 4 <= 2 * STAGE, "epilogue patches reuse the stage memory");
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * STAGE];
+    static_assert(BM % RPI == 0, "a load group must not straddle the A/W boundary");
+    static_assert((NST - 1) * GPW <= 63, "vmcnt range");
+    static_assert(NW * EPI_LDS_FLOATS * 4 <= NST * STAGE, "epilogue patches reuse the stage memory");
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * STAGE];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -240,15 +245,16 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
         n0 = (in_band / rows_here) * BN;
     }
 
-    // direct loads: lane j of load group g lands at group base + 16j = row 8g + j/8, slot j%8;
-    // the slot holds chunk (j%8) ^ ((row>>1)&7) of the row (swizzle applied on the global side)
-    const int lr = lane >> 3;
+    // direct loads: lane j of load group g lands at group base + 16j = row RPI*g + j/CPR, slot j%CPR; the slot
+    // holds chunk (j%CPR) ^ swizzle(row) of the row (applied on the global side):
+    //   128-byte rows: slot p of row r holds chunk p ^ ((r>>1)&7);  64-byte rows: chunk p ^ ((r>>2)&3)
+    const int lr = lane / CPR;
     const bf16_t* gp[GPW];
 #pragma unroll
     for (int i = 0; i < GPW; ++i) {
         const int g = wave + NW * i;
-        const int row = g * 8 + lr;                      // row within [A rows | W rows]
-        const int lc = (lane & 7) ^ ((row >> 1) & 7);
+        const int row = g * RPI + lr;                    // row within [A rows | W rows]
+        const int lc = BK == 64 ? ((lane & 7) ^ ((row >> 1) & 7)) : ((lane & 3) ^ ((row >> 2) & 3));
         if (row < BM) {
             int r = m0 + row;
             r = r < M ? r : M - 1;
@@ -260,9 +266,9 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
         }
     }
     const unsigned lds_base = (unsigned)(size_t)PS_LDS_PTR(lds);
-    auto issue = [&](int kt) {                           // kt counts from k0; stage parity follows kt
+    auto issue = [&](int kt) {                           // kt counts from k0; ring slot kt % NST
         const int kc = k0 + kt < k1 ? k0 + kt : k1 - 1;  // past the end: harmless re-read keeps vmcnt uniform
-        const unsigned st = lds_base + (kt & 1) * STAGE;
+        const unsigned st = lds_base + (kt % NST) * STAGE;
 #pragma unroll
         for (int i = 0; i < GPW; ++i) {
             const int g = wave + NW * i;
@@ -284,7 +290,7 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
     for (int i = 0; i < TM; ++i) aoff[i] = (wm * WM + i * 32 + frow) * ROWB;
 #pragma unroll
     for (int j = 0; j < TN; ++j) boff[j] = (BM + wn * WN + j * 32 + frow) * ROWB;
-    const int sw = (frow >> 1) & 7;
+    const int sw = BK == 64 ? ((frow >> 1) & 7) : ((frow >> 2) & 3);
 
     // Fragments are double-buffered in registers: the LDS reads of k-step s+1 are issued among
     // the MFMAs of step s, and the reads of the next stage's first step follow the one barrier
@@ -298,22 +304,23 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
 #pragma unroll
         for (int j = 0; j < TN; ++j) fb[buf][j] = *reinterpret_cast<const bf16x8_t*>(st + boff[j] + slot);
     };
-    issue(0);
-    wait_vmcnt<0>();
+#pragma unroll
+    for (int p = 0; p < NST - 1; ++p) issue(p);
+    wait_vmcnt<(NST - 2) * GPW>();                       // own share of stage 0
     __syncthreads();
-    issue(1);
+    issue(NST - 1);
     load_frags(0, lds, 0);
     for (int kt = 0; kt < k1 - k0; ++kt) {
-        const unsigned char* st = lds + (kt & 1) * STAGE;
-        const unsigned char* nx = lds + ((kt + 1) & 1) * STAGE;
+        const unsigned char* st = lds + (kt % NST) * STAGE;
+        const unsigned char* nx = lds + ((kt + 1) % NST) * STAGE;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             if (ks + 1 < KS) {
                 load_frags((ks + 1) & 1, st, ks + 1);
             } else {
-                wait_vmcnt<0>();                         // own share of stage kt+1 has landed
+                wait_vmcnt<(NST - 2) * GPW>();           // own share of stage kt+1 has landed
                 __syncthreads();                         // ... everyone's; and stage kt is in registers everywhere
-                issue(kt + 2);                           // into the buffer stage kt occupied
+                issue(kt + NST);                         // into the slot stage kt occupied
                 load_frags((ks + 1) & 1, nx, 0);
                 __builtin_amdgcn_sched_barrier(0);       // hand-over code stays ahead of the MFMAs
             }
@@ -431,7 +438,8 @@ static GemmPlan gemm_plan(int M, int Nn, int K, bool allow_split) {
         // traffic; narrow ones with two co-resident 128x128 workgroups that hide each other's epilogue
         p.variant = (M >= 1024 && Nn >= 5760) ? 1 : 2;
     }
-    const int bm = p.variant == 1 ? 256 : 128, bn = bm;
+    const bool big = p.variant == 1;
+    const int bm = big ? 256 : 128, bn = bm;
     p.tiles_m = (M + bm - 1) / bm;
     p.tiles_n = (Nn + bn - 1) / bn;
     const int tiles = p.tiles_m * p.tiles_n;
@@ -439,9 +447,9 @@ static GemmPlan gemm_plan(int M, int Nn, int K, bool allow_split) {
     // the last partial round: split along K if the partial sums (two passes over tile-size fp32 per piece) and
     // the second launch cost less than the round they save -- measured at 17776 tokens: true for the 128x128
     // tile with a long K (fc2: 0.62 -> 0.57 ms), not for K = 1920 (0.188 -> 0.196 ms) nor for the 256x256 tile
-    const int slots = gemm_compute_units() * (p.variant == 1 ? 1 : 2);
+    const int slots = gemm_compute_units() * (big ? 1 : 2);
     const int tail = tiles % slots, nk = K / 64;
-    if (allow_split && p.variant == 2 && K >= 4096 && tail > 0 && tiles > slots) {
+    if (allow_split && !big && K >= 4096 && tail > 0 && tiles > slots) {
         int ns = slots / tail;
         if (ns > 8) ns = 8;
         if (ns > nk / 2) ns = nk / 2;
@@ -458,11 +466,11 @@ size_t gemm_split_workspace_bytes(int dtype, int M, int Nn, int K) {
     return gemm_plan(M, Nn, K, true).ws_bytes;
 }
 
-template <int BM, int BN, int WR, int WC, int KIND>
+template <int BM, int BN, int WR, int WC, int BK, int NST, int KIND>
 static hipError_t launch_kind(const bf16_t* A, const bf16_t* W, bf16_t* C, int M, int Nn, int K, const GemmPlan& p,
                               const Epilogue& ep, hipStream_t st) {
     dim3 block(WR * WC * 64);
-    gemm_mfma_kernel<BM, BN, WR, WC, KIND><<<p.full + p.pieces, block, 0, st>>>(A, W, C, M, Nn, K, p.tiles_m, p.tiles_n,
+    gemm_mfma_kernel<BM, BN, WR, WC, BK, NST, KIND><<<p.full + p.pieces, block, 0, st>>>(A, W, C, M, Nn, K, p.tiles_m, p.tiles_n,
                                                                                 p.full, p.nsplit, ep);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.pieces == 0) return e;
@@ -471,14 +479,14 @@ static hipError_t launch_kind(const bf16_t* A, const bf16_t* W, bf16_t* C, int M
     return hipGetLastError();
 }
 
-template <int BM, int BN, int WR, int WC>
+template <int BM, int BN, int WR, int WC, int BK, int NST>
 static hipError_t launch_tile(const bf16_t* A, const bf16_t* W, bf16_t* C, int M, int Nn, int K, const GemmPlan& p,
                               const Epilogue& ep, hipStream_t st) {
     switch (ep.kind) {
-        case EPI_BIAS: return launch_kind<BM, BN, WR, WC, EPI_BIAS>(A, W, C, M, Nn, K, p, ep, st);
-        case EPI_BIAS_GELU: return launch_kind<BM, BN, WR, WC, EPI_BIAS_GELU>(A, W, C, M, Nn, K, p, ep, st);
-        case EPI_GATE_RESIDUAL: return launch_kind<BM, BN, WR, WC, EPI_GATE_RESIDUAL>(A, W, C, M, Nn, K, p, ep, st);
-        case EPI_QKV_ROPE: return launch_kind<BM, BN, WR, WC, EPI_QKV_ROPE>(A, W, C, M, Nn, K, p, ep, st);
+        case EPI_BIAS: return launch_kind<BM, BN, WR, WC, BK, NST, EPI_BIAS>(A, W, C, M, Nn, K, p, ep, st);
+        case EPI_BIAS_GELU: return launch_kind<BM, BN, WR, WC, BK, NST, EPI_BIAS_GELU>(A, W, C, M, Nn, K, p, ep, st);
+        case EPI_GATE_RESIDUAL: return launch_kind<BM, BN, WR, WC, BK, NST, EPI_GATE_RESIDUAL>(A, W, C, M, Nn, K, p, ep, st);
+        case EPI_QKV_ROPE: return launch_kind<BM, BN, WR, WC, BK, NST, EPI_QKV_ROPE>(A, W, C, M, Nn, K, p, ep, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -488,8 +496,10 @@ hipError_t launch_gemm_mfma(const bf16_t* A, const bf16_t* W, bf16_t* C, int M, 
     GemmPlan p = gemm_plan(M, Nn, K, ep.split_ws != nullptr && (get_kernel_path() & 0xff) != 4);
     if (p.ws_bytes > ep.split_ws_bytes) p = gemm_plan(M, Nn, K, false);
     switch (p.variant) {
-        case 1: return launch_tile<256, 256, 2, 4>(A, W, C, M, Nn, K, p, ep, st);   // 8 waves, 128x64 each
-        case 2: return launch_tile<128, 128, 2, 2>(A, W, C, M, Nn, K, p, ep, st);   // 4 waves, 64x64 each, 2 per CU
+        case 1: return launch_tile<256, 256, 2, 4, 64, 2>(A, W, C, M, Nn, K, p, ep, st);   // 8 waves, 128x64 each
+        case 2: return launch_tile<128, 128, 2, 2, 64, 2>(A, W, C, M, Nn, K, p, ep, st);   // 4 waves, 64x64 each, 2 per CU
+        // (32-deep stages in rings of 3 or 4 measured 5-25 % slower on every shape: twice the barriers, and the
+        // two-stage ring's look-ahead of one 64-deep stage already covers the load latency)
         default: return hipErrorInvalidValue;
     }
 }
