@@ -59,12 +59,13 @@ typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
 constexpr int EPI_LDS_STRIDE = 72;                       // floats per row of a wave's 32 x 64 patch
 constexpr int EPI_LDS_FLOATS = 32 * EPI_LDS_STRIDE;
 
-// Epilogue of one wave: TM strips of 32 rows x 64 columns.  wrow0 / wcol0: first row and
-// column of the wave's outputs; patch: the wave's private LDS area (EPI_LDS_FLOATS floats).
+// Epilogue of 64 columns of one wave (accumulator tiles J0, J0+1 of each of its TM tile rows): TM strips of
+// 32 rows x 64 columns.  wrow0 / wcol0: first row and column of these outputs; patch: the wave's private LDS
+// area (EPI_LDS_FLOATS floats).
 // Offsets are 32-bit element indices from the uniform base pointers (the launcher
 // guarantees M*Nn < 2^31); Nn % 4 == 0, so a lane's 4 columns are inside or outside together.
-template <int TM, int KIND, bool CHECK>
-__device__ __forceinline__ void wave_epilogue(f32x16_t (&acc)[TM][2], const Epilogue& ep, bf16_t* __restrict__ C,
+template <int TM, int TN, int J0, int KIND, bool CHECK>
+__device__ __forceinline__ void wave_epilogue(f32x16_t (&acc)[TM][TN], const Epilogue& ep, bf16_t* __restrict__ C,
                                               int M, int Nn, int wrow0, int wcol0, int lane, float* patch) {
     const int frow = lane & 31, fhalf = lane >> 5;       // accumulator side: column, row offset 4*fhalf
     const int rr = lane >> 4, cc = (lane & 15) * 4;      // row-contiguous side: row within 4, first column
@@ -134,7 +135,7 @@ __device__ __forceinline__ void wave_epilogue(f32x16_t (&acc)[TM][2], const Epil
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e)
-                patch[(8 * (e >> 2) + 4 * fhalf + (e & 3)) * EPI_LDS_STRIDE + j * 32 + frow] = acc[i][j][e];
+                patch[(8 * (e >> 2) + 4 * fhalf + (e & 3)) * EPI_LDS_STRIDE + j * 32 + frow] = acc[i][J0 + j][e];
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // LDS is in order per wave; this pins the compiler too
         f32x4_t v[8];
 #pragma unroll
@@ -209,7 +210,7 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
     constexpr int GROUPS = (BM + BN) / RPI;
     constexpr int GPW = GROUPS / NW;                     // load instructions per wave per stage
     constexpr int STAGE = (BM + BN) * ROWB;
-    static_assert(TN == 2, "the epilogue handles strips of 64 columns per wave");
+    static_assert(TN == 2 || TN == 4, "the epilogue handles strips of 64 columns");
     static_assert(GROUPS % NW == 0, "rows must split evenly over waves");
     static_assert(BM % RPI == 0, "a load group must not straddle the A/W boundary");
     static_assert((NST - 1) * GPW <= 63, "vmcnt range");
@@ -359,10 +360,15 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
     }
     float* patch = reinterpret_cast<float*>(lds) + wave * EPI_LDS_FLOATS;
     const bool interior = (m0 + BM <= M) && (n0 + BN <= Nn);
-    if (interior)
-        wave_epilogue<TM, KIND, false>(acc, ep, C, M, Nn, m0 + wm * WM, n0 + wn * WN, lane, patch);
-    else
-        wave_epilogue<TM, KIND, true>(acc, ep, C, M, Nn, m0 + wm * WM, n0 + wn * WN, lane, patch);
+    if (interior) {
+        wave_epilogue<TM, TN, 0, KIND, false>(acc, ep, C, M, Nn, m0 + wm * WM, n0 + wn * WN, lane, patch);
+        if constexpr (TN == 4)
+            wave_epilogue<TM, TN, 2, KIND, false>(acc, ep, C, M, Nn, m0 + wm * WM, n0 + wn * WN + 64, lane, patch);
+    } else {
+        wave_epilogue<TM, TN, 0, KIND, true>(acc, ep, C, M, Nn, m0 + wm * WM, n0 + wn * WN, lane, patch);
+        if constexpr (TN == 4)
+            wave_epilogue<TM, TN, 2, KIND, true>(acc, ep, C, M, Nn, m0 + wm * WM, n0 + wn * WN + 64, lane, patch);
+    }
 }
 
 // Sums the K-split pieces of the tail tiles (fixed order: deterministic) and applies the epilogue; one
@@ -408,7 +414,10 @@ gemm_tail_kernel(bf16_t* __restrict__ C, int M, int Nn, int tiles_m, int tiles_n
                     for (int c = 0; c < 4; ++c) acc[i][j][e4 * 4 + c] += v[c];
                 }
     }
-    wave_epilogue<TM, KIND, true>(acc, ep, C, M, Nn, m0 + wm * WM, n0 + wn * WN, lane, patches + wave * EPI_LDS_FLOATS);
+    wave_epilogue<TM, TN, 0, KIND, true>(acc, ep, C, M, Nn, m0 + wm * WM, n0 + wn * WN, lane, patches + wave * EPI_LDS_FLOATS);
+    if constexpr (TN == 4)
+        wave_epilogue<TM, TN, 2, KIND, true>(acc, ep, C, M, Nn, m0 + wm * WM, n0 + wn * WN + 64, lane,
+                                             patches + wave * EPI_LDS_FLOATS);
 }
 
 bool gemm_mfma_supported(int M, int Nn, int K) {
@@ -498,8 +507,11 @@ hipError_t launch_gemm_mfma(const bf16_t* A, const bf16_t* W, bf16_t* C, int M, 
     switch (p.variant) {
         case 1: return launch_tile<256, 256, 2, 4, 64, 2>(A, W, C, M, Nn, K, p, ep, st);   // 8 waves, 128x64 each
         case 2: return launch_tile<128, 128, 2, 2, 64, 2>(A, W, C, M, Nn, K, p, ep, st);   // 4 waves, 64x64 each, 2 per CU
-        // (32-deep stages in rings of 3 or 4 measured 5-25 % slower on every shape: twice the barriers, and the
-        // two-stage ring's look-ahead of one 64-deep stage already covers the load latency)
+        // Measured and dropped: 4 waves of 128x128 outputs on the 256x256 tile (fewer LDS reads per MFMA, but one
+        // wave per SIMD issues an MFMA only every ~48 cycles: 5-15 % slower); 32-deep stages in rings of 3 or 4
+        // (5-25 % slower: twice the barriers).  With the loads of the loop taken out (timing probe) both tiles
+        // reach 1.3-1.4 PFLOP/s, with every tile loading the same L2-resident panels only 4-10 % more than now:
+        // the global->LDS path itself, not the memory behind L2, is what the loop waits for.
         default: return hipErrorInvalidValue;
     }
 }
