@@ -189,11 +189,16 @@ int forward_impl(dit* d, const float* x, const void* ctx, const int32_t* t_host,
         eq.rope_cos = rcos; eq.rope_sin = rsin; eq.head_dim = c.head_dim;
         eq.q_scale = prescale ? scale * 1.4426950408889634f : 1.0f;
         eq.split_ws = gemm_ws; eq.split_ws_bytes = w.gemm_bytes;
+        // the projection's epilogue leaves the per-head maxima of |q|^2 and |k|^2 the attention kernel selects on
+        const bool fused_bounds = c.head_dim == 64 && gemm_uses_mfma(dt, M, 3 * D, D);
+        eq.norm_bounds = fused_bounds ? attention_norm_bounds(dt, batch, c.heads, c.head_dim, attn_ws, st) : nullptr;
+        eq.heads = c.heads;
         PS_TIMED(KC_QKV, launch_gemm(dt, Hb, lw.W_qkv, QKV, M, 3 * D, D, eq, st));
         // o = attention(q, k, v) -> Hb (token-major, heads concatenated)
         const char* qp = (const char*)QKV;
         PS_TIMED(KC_ATTN, launch_attention(dt, qp, qp + (size_t)D * es, qp + (size_t)2 * D * es, Hb, batch, N,
-                                           c.heads, c.head_dim, scale, as, attn_ws, st, prescale));
+                                           c.heads, c.head_dim, scale, as, attn_ws, st, prescale,
+                                           eq.norm_bounds != nullptr));
         // X += gate_a * (W_o o + b_o)
         Epilogue eo{};
         eo.kind = EPI_GATE_RESIDUAL; eo.bias = lw.b_o; eo.resid = X; eo.mod_layer = mod_l;
@@ -210,8 +215,19 @@ int forward_impl(dit* d, const float* x, const void* ctx, const int32_t* t_host,
         e2.bias = lw.b_2; e2.gate_chunk = 5;
         PS_TIMED(KC_FC2, launch_gemm(dt, QKV, lw.W_2, nullptr, M, D, c.mlp_ratio * D, e2, st));
     }
-    PS_TIMED(KC_OTHER, launch_final_proj(dt, X, modf, d->W_out, d->b_out, eps_out, batch, c.in_channels, c.frames,
-                                         c.height, c.width, c.patch, c.text_tokens, D, c.ln_eps, st));
+    // eps = unpatchify(W_out (LN(X)(1+scale_f)+shift_f) + b_out) over the video tokens
+    const int P = c.in_channels * c.patch * c.patch;
+    if (gemm_uses_mfma(dt, M, P, D)) {
+        // as every other projection: normalised rows in bf16 (text rows included, dropped by the epilogue)
+        PS_TIMED(KC_LN, launch_ln_modulate(dt, X, Hb, M, D, c.ln_eps, modf, 2L * D, 0, 1, TokenGeom{N, 0}, st));
+        Epilogue ef{};
+        ef.kind = EPI_UNPATCHIFY; ef.bias = d->b_out; ef.resid = eps_out; ef.geom = geom;
+        ef.pg = PatchGeom{c.in_channels, c.frames, c.height, c.width, c.patch};
+        PS_TIMED(KC_OTHER, launch_gemm(dt, Hb, d->W_out, nullptr, M, P, D, ef, st));
+    } else {
+        PS_TIMED(KC_OTHER, launch_final_proj(dt, X, modf, d->W_out, d->b_out, eps_out, batch, c.in_channels,
+                                             c.frames, c.height, c.width, c.patch, c.text_tokens, D, c.ln_eps, st));
+    }
     return PS_OK;
 }
 

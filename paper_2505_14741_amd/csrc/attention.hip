@@ -970,9 +970,16 @@ bool attention_uses_mfma(int dtype, int head_dim) {
     return dtype == PS_BF16 && head_dim == 64 && get_kernel_path() != 1;
 }
 
+float* attention_norm_bounds(int dtype, int batch, int heads, int head_dim, void* ws, hipStream_t st) {
+    if (!ws || !attention_uses_mfma(dtype, head_dim) || !attention_bounded_path(heads)) return nullptr;
+    const int nb = batch * heads * 2;
+    attn_bound_clear_kernel<<<(nb + 255) / 256, 256, 0, st>>>((float*)ws, nb);
+    return hipGetLastError() == hipSuccess ? (float*)ws : nullptr;
+}
+
 hipError_t launch_attention(int dtype, const void* q, const void* k, const void* v, void* o,
                             int batch, int seq, int heads, int head_dim, float scale,
-                            const AttnStrides& s, void* ws, hipStream_t st, bool q_prescaled) {
+                            const AttnStrides& s, void* ws, hipStream_t st, bool q_prescaled, bool bounds_ready) {
     if (attention_uses_mfma(dtype, head_dim)) {
         if (ws == nullptr) return hipErrorInvalidValue;
         if (s.k_tok >= (1 << 24) || s.v_tok >= (1 << 24)) return hipErrorInvalidValue;   // 32-bit in-tile offsets
@@ -988,9 +995,12 @@ hipError_t launch_attention(int dtype, const void* q, const void* k, const void*
         if (bounded) {
             // norm bounds per (batch, head), then the check-free kernel for the heads they qualify and the
             // reference-tracking kernel (unsplit) for the others; each workgroup looks its head up
-            const int nb = batch * heads * 2;
-            attn_bound_clear_kernel<<<(nb + 255) / 256, 256, 0, st>>>(bounds, nb);
-            attn_bound_kernel<<<dim3((seq + BOUND_ROWS - 1) / BOUND_ROWS, batch), 256, 0, st>>>(qq, kk, seq, heads, s, bounds);
+            if (!bounds_ready) {
+                const int nb = batch * heads * 2;
+                attn_bound_clear_kernel<<<(nb + 255) / 256, 256, 0, st>>>(bounds, nb);
+                attn_bound_kernel<<<dim3((seq + BOUND_ROWS - 1) / BOUND_ROWS, batch), 256, 0, st>>>(qq, kk, seq, heads, s,
+                                                                                                 bounds);
+            }
             if (q_prescaled)
                 attn_sp_kernel<true><<<p.full + p.pieces, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c, p.qblocks, s,
                                                                         p.full, p.nsplit, part, bounds);

@@ -35,7 +35,9 @@ struct TokenGeom {
 };
 
 // ---- GEMM epilogues ------------------------------------------------------------------
-enum EpiKind { EPI_BIAS = 0, EPI_BIAS_GELU = 1, EPI_GATE_RESIDUAL = 2, EPI_QKV_ROPE = 3 };
+enum EpiKind { EPI_BIAS = 0, EPI_BIAS_GELU = 1, EPI_GATE_RESIDUAL = 2, EPI_QKV_ROPE = 3, EPI_UNPATCHIFY = 4 };
+
+struct PatchGeom { int C, F, H, W, patch; };   // latent [C, F, H, W], patch x patch pixels per video token
 
 struct Epilogue {
     int kind;
@@ -52,6 +54,13 @@ struct Epilogue {
     const float* rope_sin;
     int head_dim;
     float q_scale;            // factor applied to the q columns (col < D) after the rotation
+    // EPI_QKV_ROPE, bf16 MFMA kernel, head_dim 64, optional: [batch*heads][2] running maxima of the squared norms
+    // of the stored q and k rows per (batch, head), raised with atomic max (the caller zeroes them)
+    float* norm_bounds;
+    int heads;
+    // EPI_UNPATCHIFY (bf16 MFMA kernel only): columns are (c, dy, dx) of a video token's patch; rows of text
+    // tokens are dropped; resid is the fp32 output latent [B, C, F, H, W]
+    PatchGeom pg;
     // optional scratch for the bf16 MFMA kernel: with it, the output tiles of the last, partial round of
     // workgroups are split along K and their fp32 partial sums pass through this buffer
     float* split_ws;
@@ -60,6 +69,8 @@ struct Epilogue {
 
 // scratch that lets launch_gemm split its last partial round along K (0: the shape does not profit)
 size_t gemm_split_workspace_bytes(int dtype, int M, int Nn, int K);
+// whether launch_gemm sends a bf16 shape to the MFMA kernel (EPI_UNPATCHIFY exists only there)
+bool gemm_uses_mfma(int dtype, int M, int Nn, int K);
 
 // ---- launchers (each validates nothing; callers have checked shapes) -----------------
 // C[M, Nn] = A[M, K] * W[Nn, K]^T with epilogue.  A, W, C in `dtype` (C ignored for
@@ -74,9 +85,15 @@ struct AttnStrides { long q_tok, q_head, q_batch, k_tok, k_head, k_batch, v_tok,
 size_t attention_workspace_bytes(int dtype, int batch, int seq, int heads, int head_dim);
 // q_prescaled: q already carries scale*log2(e) (only valid when attention_uses_mfma()).
 bool attention_uses_mfma(int dtype, int head_dim);
+// bounds_ready: the per-(batch, head) norm maxima at the head of `ws` are already in place (see
+// attention_norm_bounds()), so the pass over q and k that finds them is skipped.
 hipError_t launch_attention(int dtype, const void* q, const void* k, const void* v, void* o,
                             int batch, int seq, int heads, int head_dim, float scale,
-                            const AttnStrides& s, void* ws, hipStream_t st, bool q_prescaled = false);
+                            const AttnStrides& s, void* ws, hipStream_t st, bool q_prescaled = false,
+                            bool bounds_ready = false);
+// Where a producer of q and k may leave those maxima itself: zeroes [batch*heads][2] floats at the head of `ws`
+// on the stream and returns their address; nullptr if this shape's attention does not use them.
+float* attention_norm_bounds(int dtype, int batch, int heads, int head_dim, void* ws, hipStream_t st);
 void set_kernel_path(int p);
 int get_kernel_path();
 

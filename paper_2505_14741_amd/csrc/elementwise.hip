@@ -42,7 +42,8 @@ hipError_t launch_sinusoid(const int32_t* t_host, float* out, int batch, int D, 
     return hipGetLastError();
 }
 
-// One wave per output row; weights stream once from HBM, inputs stay in cache.
+// One wave per output row; weights stream once from HBM (16 bytes per lane and load when the row length
+// allows), inputs stay in cache.
 template <typename T, int MAXB>
 __global__ void gemv_kernel(const T* __restrict__ W, const float* __restrict__ bias,
                             const float* __restrict__ in, float* __restrict__ out, int rows,
@@ -54,11 +55,38 @@ __global__ void gemv_kernel(const T* __restrict__ W, const float* __restrict__ b
     float acc[MAXB];
 #pragma unroll
     for (int b = 0; b < MAXB; ++b) acc[b] = 0.f;
-    for (int c = lane; c < cols; c += WAVE) {
-        float wv = to_f32(w[c]);
+    constexpr int VEC = 16 / sizeof(T);                      // elements per 16-byte load
+    if (cols % VEC == 0 && in_bs % 4 == 0) {
+        for (int c = lane * VEC; c < cols; c += WAVE * VEC) {
+            float wv[VEC];
+            if constexpr (sizeof(T) == 2) {
+                typedef __attribute__((ext_vector_type(8))) __bf16 b8;
+                const b8 v = *reinterpret_cast<const b8*>(w + c);
 #pragma unroll
-        for (int b = 0; b < MAXB; ++b)
-            if (b < batch) acc[b] += wv * in[b * in_bs + c];
+                for (int e = 0; e < VEC; ++e) wv[e] = (float)v[e];
+            } else {
+                const float4 v = *reinterpret_cast<const float4*>(w + c);
+                wv[0] = v.x; wv[1] = v.y; wv[2] = v.z; wv[3] = v.w;
+            }
+#pragma unroll
+            for (int b = 0; b < MAXB; ++b) {
+                if (b < batch) {
+                    const float* ip = in + b * in_bs + c;
+#pragma unroll
+                    for (int e4 = 0; e4 < VEC; e4 += 4) {
+                        const float4 x = *reinterpret_cast<const float4*>(ip + e4);
+                        acc[b] += (wv[e4] * x.x + wv[e4 + 1] * x.y) + (wv[e4 + 2] * x.z + wv[e4 + 3] * x.w);
+                    }
+                }
+            }
+        }
+    } else {
+        for (int c = lane; c < cols; c += WAVE) {
+            float wv = to_f32(w[c]);
+#pragma unroll
+            for (int b = 0; b < MAXB; ++b)
+                if (b < batch) acc[b] += wv * in[b * in_bs + c];
+        }
     }
 #pragma unroll
     for (int b = 0; b < MAXB; ++b) {

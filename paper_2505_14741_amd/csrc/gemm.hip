@@ -86,9 +86,14 @@ bool gemm_mfma_supported(int M, int Nn, int K);
 hipError_t launch_gemm_mfma(const bf16_t* A, const bf16_t* W, bf16_t* C, int M, int Nn, int K,
                             const Epilogue& ep, hipStream_t st);
 
+bool gemm_uses_mfma(int dtype, int M, int Nn, int K) {
+    return dtype == PS_BF16 && g_kernel_path != 1 && gemm_mfma_supported(M, Nn, K);
+}
+
 hipError_t launch_gemm(int dtype, const void* A, const void* W, void* C, int M, int Nn, int K,
                        const Epilogue& epi, hipStream_t st) {
     if (M <= 0 || Nn <= 0 || K <= 0 || (Nn & 1)) return hipErrorInvalidValue;
+    if (epi.kind == EPI_UNPATCHIFY && !gemm_uses_mfma(dtype, M, Nn, K)) return hipErrorInvalidValue;
     if (dtype == PS_BF16) {
         if (g_kernel_path != 1 && gemm_mfma_supported(M, Nn, K))
             return launch_gemm_mfma((const bf16_t*)A, (const bf16_t*)W, (bf16_t*)C, M, Nn, K, epi, st);

@@ -93,10 +93,17 @@ __device__ __forceinline__ void wave_epilogue(f32x16_t (&acc)[TM][TN], const Epi
         gate_v = *reinterpret_cast<const f32x4_t*>(g + ep.gate_chunk * ep.D);
         gate_t = *reinterpret_cast<const f32x4_t*>(g + (ep.gate_chunk + 6) * ep.D);
     }
+    // norm maxima for the attention kernel (q and k columns; a wave's 64 columns are one head of 64)
+    bool track_norms = false;
+    int norm_head = 0, norm_which = 0;
+    float norm_max = 0.f;
     if constexpr (KIND == EPI_QKV_ROPE) {
         rot = col < 2 * ep.D;                            // q and k columns rotate, v columns do not
         pr = (colc % ep.head_dim) >> 1;                  // first of the lane's two (even, odd) pairs
         qs = col < ep.D ? ep.q_scale : 1.0f;
+        track_norms = ep.norm_bounds != nullptr && wcol0 < 2 * ep.D && wcol0 < Nn;
+        norm_which = wcol0 < ep.D ? 0 : 1;
+        norm_head = (wcol0 - norm_which * ep.D) / 64;
     }
 
     // operands the strip needs from memory besides the accumulators (one 16-byte value per
@@ -159,8 +166,49 @@ __device__ __forceinline__ void wave_epilogue(f32x16_t (&acc)[TM][TN], const Epi
                 // t = (cos0, cos1, sin0, sin1); identity for text tokens and v columns
                 x = f32x4_t{x[0] * t[0] - x[1] * t[2], x[1] * t[0] + x[0] * t[2],
                             x[2] * t[1] - x[3] * t[3], x[3] * t[1] + x[2] * t[3]} * qs;
+                if (track_norms) {
+                    // this lane's 4 columns of the row; the values are stored as bf16, which moves a norm by at
+                    // most 2^-8 relative: covered by a factor on the final maximum
+                    const float ss = (x[0] * x[0] + x[1] * x[1]) + (x[2] * x[2] + x[3] * x[3]);
+                    if (one_batch) {
+                        // per-lane maximum over the rows; the sum of the 16 lanes' maxima bounds the largest row
+                        // norm from above (max of sums <= sum of maxes), which is all the consumer needs
+                        norm_max = fmaxf(norm_max, (ss < INFINITY) ? ss : INFINITY);   // NaN -> inf
+                    } else {
+                        float row = ss;
+                        row += __shfl_xor(row, 1);
+                        row += __shfl_xor(row, 2);
+                        row += __shfl_xor(row, 4);
+                        row += __shfl_xor(row, 8);
+                        row = (row < INFINITY) ? row * 1.01f : INFINITY;
+                        if ((lane & 15) == 0 && (!CHECK || m < M)) {
+                            int b;
+                            token_of(m, b);
+                            atomicMax(reinterpret_cast<unsigned*>(ep.norm_bounds + 2 * (b * ep.heads + norm_head) + norm_which),
+                                      __float_as_uint(row));
+                        }
+                    }
+                }
             }
             if (CHECK && (m >= M || !col_ok)) continue;
+            if constexpr (KIND == EPI_UNPATCHIFY) {
+                // token m -> (batch, frame, patch row, patch column); column o -> (channel, dy, dx)
+                int b;
+                const int n = token_of(m, b);
+                if (n < text) continue;
+                const PatchGeom& g = ep.pg;
+                const int Hp = g.H / g.patch, Wp = g.W / g.patch;
+                const int nv = n - text;
+                const int pj = nv % Wp, pi = (nv / Wp) % Hp, f = nv / (Wp * Hp);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const int o = col + c;
+                    const int dx = o % g.patch, dy = (o / g.patch) % g.patch, ch = o / (g.patch * g.patch);
+                    ep.resid[((((long)b * g.C + ch) * g.F + f) * g.H + (pi * g.patch + dy)) * g.W + (pj * g.patch + dx)] =
+                        x[c];
+                }
+                continue;
+            }
             const unsigned off = (unsigned)(m * Nn + col);
             if constexpr (KIND == EPI_GATE_RESIDUAL) {
                 // X[m, col] += gate[batch(m), stream(m), col] * (acc + bias)
@@ -176,6 +224,20 @@ __device__ __forceinline__ void wave_epilogue(f32x16_t (&acc)[TM][TN], const Epi
                 *reinterpret_cast<bf16x4_t*>(reinterpret_cast<unsigned short*>(C) + off) =
                     __builtin_convertvector(x, bf16x4_t);
             }
+        }
+    }
+    if constexpr (KIND == EPI_QKV_ROPE) {
+        if (track_norms && one_batch) {                  // one atomic per wave: non-negative floats order like their bits
+            norm_max += __shfl_xor(norm_max, 1);         // the 16 lanes that share rows ...
+            norm_max += __shfl_xor(norm_max, 2);
+            norm_max += __shfl_xor(norm_max, 4);
+            norm_max += __shfl_xor(norm_max, 8);
+            norm_max = fmaxf(norm_max, __shfl_xor(norm_max, 16));   // ... and the 4 row groups
+            norm_max = fmaxf(norm_max, __shfl_xor(norm_max, 32));
+            norm_max = (norm_max < INFINITY) ? norm_max * 1.01f : INFINITY;
+            if (lane == 0)
+                atomicMax(reinterpret_cast<unsigned*>(ep.norm_bounds + 2 * (b_first * ep.heads + norm_head) + norm_which),
+                          __float_as_uint(norm_max));
         }
     }
 }
@@ -496,6 +558,7 @@ static hipError_t launch_tile(const bf16_t* A, const bf16_t* W, bf16_t* C, int M
         case EPI_BIAS_GELU: return launch_kind<BM, BN, WR, WC, BK, NST, EPI_BIAS_GELU>(A, W, C, M, Nn, K, p, ep, st);
         case EPI_GATE_RESIDUAL: return launch_kind<BM, BN, WR, WC, BK, NST, EPI_GATE_RESIDUAL>(A, W, C, M, Nn, K, p, ep, st);
         case EPI_QKV_ROPE: return launch_kind<BM, BN, WR, WC, BK, NST, EPI_QKV_ROPE>(A, W, C, M, Nn, K, p, ep, st);
+        case EPI_UNPATCHIFY: return launch_kind<BM, BN, WR, WC, BK, NST, EPI_UNPATCHIFY>(A, W, C, M, Nn, K, p, ep, st);
         default: return hipErrorInvalidValue;
     }
 }
