@@ -92,6 +92,24 @@ def test_reduced_forward_generic_and_mfma_paths_agree():
     assert O.rel_mae(slow, fast)[2] < 1e-2
 
 
+def test_reduced_forward_bf16_batch_of_three():
+    """Batch 3 with different timesteps on the MFMA kernels: 3 x 112 token rows, so 128-row tiles straddle
+    samples (per-row batch index in the gated-residual, rotary and norm-maximum epilogues).  Every sample
+    against the oracle, and against the same sample run alone (bitwise: rows do not interact)."""
+    cfg, W, d = setup("reduced", "unit", cfg=I.CONFIGS["reduced"].with_(layers=2))
+    x, ctx = I.make_latent(cfg, 3), I.make_context(cfg, 3)
+    t = [900, 500, 20]
+    xd, cd = dev(x), dev(ctx, torch.bfloat16)
+    eps = B.dit_forward(d, xd, cd, t)
+    ref = O.dit_forward(cfg, W, x, ctx, t)
+    for b in range(3):
+        r = O.rel_mae(ref[b], host(eps[b]))[2]
+        print(f"  sample {b} rel-MAE {r:.3e}", flush=True)
+        assert r <= 2e-2
+        one = B.dit_forward(d, xd[b:b + 1].contiguous(), cd[b:b + 1].contiguous(), t[b:b + 1])
+        assert torch.equal(one[0], eps[b]), b
+
+
 @pytest.mark.parametrize("init", ["std002", "unit"])
 def test_block_forward_bf16_whole(init):
     """One block at CogVideoX-2b width, 4290 video + 226 text tokens, whole output vs oracle."""
