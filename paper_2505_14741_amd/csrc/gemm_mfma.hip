@@ -95,8 +95,8 @@ __device__ __forceinline__ void wave_epilogue(f32x16_t (&acc)[TM][TN], const Epi
     }
     // norm maxima for the attention kernel (q and k columns; a wave's 64 columns are one head of 64)
     bool track_norms = false;
-    int norm_head = 0, norm_which = 0;
-    float norm_max = 0.f;
+    int norm_head = 0, norm_which = 0, norm_split = 0;
+    unsigned nmax1 = 0u, nmax2 = 0u;
     if constexpr (KIND == EPI_QKV_ROPE) {
         rot = col < 2 * ep.D;                            // q and k columns rotate, v columns do not
         pr = (colc % ep.head_dim) >> 1;                  // first of the lane's two (even, odd) pairs
@@ -104,6 +104,7 @@ __device__ __forceinline__ void wave_epilogue(f32x16_t (&acc)[TM][TN], const Epi
         track_norms = ep.norm_bounds != nullptr && wcol0 < 2 * ep.D && wcol0 < Nn;
         norm_which = wcol0 < ep.D ? 0 : 1;
         norm_head = (wcol0 - norm_which * ep.D) / 64;
+        norm_split = (b_first + 1) * tokens;             // first row of the next sample
     }
 
     // operands the strip needs from memory besides the accumulators (one 16-byte value per
@@ -167,27 +168,15 @@ __device__ __forceinline__ void wave_epilogue(f32x16_t (&acc)[TM][TN], const Epi
                 x = f32x4_t{x[0] * t[0] - x[1] * t[2], x[1] * t[0] + x[0] * t[2],
                             x[2] * t[1] - x[3] * t[3], x[3] * t[1] + x[2] * t[3]} * qs;
                 if (track_norms) {
-                    // this lane's 4 columns of the row; the values are stored as bf16, which moves a norm by at
-                    // most 2^-8 relative: covered by a factor on the final maximum
-                    const float ss = (x[0] * x[0] + x[1] * x[1]) + (x[2] * x[2] + x[3] * x[3]);
-                    if (one_batch) {
-                        // per-lane maximum over the rows; the sum of the 16 lanes' maxima bounds the largest row
-                        // norm from above (max of sums <= sum of maxes), which is all the consumer needs
-                        norm_max = fmaxf(norm_max, (ss < INFINITY) ? ss : INFINITY);   // NaN -> inf
-                    } else {
-                        float row = ss;
-                        row += __shfl_xor(row, 1);
-                        row += __shfl_xor(row, 2);
-                        row += __shfl_xor(row, 4);
-                        row += __shfl_xor(row, 8);
-                        row = (row < INFINITY) ? row * 1.01f : INFINITY;
-                        if ((lane & 15) == 0 && (!CHECK || m < M)) {
-                            int b;
-                            token_of(m, b);
-                            atomicMax(reinterpret_cast<unsigned*>(ep.norm_bounds + 2 * (b * ep.heads + norm_head) + norm_which),
-                                      __float_as_uint(row));
-                        }
-                    }
+                    // this lane's 4 columns of the row (the values are stored as bf16, which moves a norm by at
+                    // most 2^-8 relative: covered by a factor on the final maximum).  Per-lane maxima over the
+                    // rows; the sum of the 16 lanes' maxima bounds the largest row norm from above (max of sums
+                    // <= sum of maxes), which is all the consumer needs.  Maxima are taken on the bit patterns
+                    // (non-negative floats order like unsigned integers; NaN orders above inf and ends as inf).
+                    // nmax1 covers every row of the wave, nmax2 only those of the sample after the first.
+                    const unsigned ss = __float_as_uint((x[0] * x[0] + x[1] * x[1]) + (x[2] * x[2] + x[3] * x[3]));
+                    nmax1 = max(nmax1, ss);
+                    if (!one_batch) nmax2 = max(nmax2, m >= norm_split ? ss : 0u);
                 }
             }
             if (CHECK && (m >= M || !col_ok)) continue;
@@ -227,17 +216,32 @@ __device__ __forceinline__ void wave_epilogue(f32x16_t (&acc)[TM][TN], const Epi
         }
     }
     if constexpr (KIND == EPI_QKV_ROPE) {
-        if (track_norms && one_batch) {                  // one atomic per wave: non-negative floats order like their bits
-            norm_max += __shfl_xor(norm_max, 1);         // the 16 lanes that share rows ...
-            norm_max += __shfl_xor(norm_max, 2);
-            norm_max += __shfl_xor(norm_max, 4);
-            norm_max += __shfl_xor(norm_max, 8);
-            norm_max = fmaxf(norm_max, __shfl_xor(norm_max, 16));   // ... and the 4 row groups
-            norm_max = fmaxf(norm_max, __shfl_xor(norm_max, 32));
-            norm_max = (norm_max < INFINITY) ? norm_max * 1.01f : INFINITY;
-            if (lane == 0)
-                atomicMax(reinterpret_cast<unsigned*>(ep.norm_bounds + 2 * (b_first * ep.heads + norm_head) + norm_which),
-                          __float_as_uint(norm_max));
+        if (track_norms) {
+            // one or two atomics per wave (non-negative floats order like their bit patterns); a wave whose rows
+            // reach into a third sample (fewer tokens per sample than rows per wave) marks those samples' head
+            // as unbounded instead, which only sends it to the kernel that needs no bound
+            auto reduce = [&](unsigned bits) {
+                float v = __uint_as_float(bits);
+                v = (v < INFINITY) ? v : INFINITY;       // NaN -> inf
+                v += __shfl_xor(v, 1);                   // the 16 lanes that share rows ...
+                v += __shfl_xor(v, 2);
+                v += __shfl_xor(v, 4);
+                v += __shfl_xor(v, 8);
+                v = fmaxf(v, __shfl_xor(v, 16));         // ... and the 4 row groups
+                v = fmaxf(v, __shfl_xor(v, 32));
+                return (v < INFINITY) ? v * 1.01f : INFINITY;
+            };
+            const float n1 = reduce(nmax1), n2 = reduce(nmax2);
+            if (lane == 0) {
+                float* dst = ep.norm_bounds + 2 * (b_first * ep.heads + norm_head) + norm_which;
+                atomicMax(reinterpret_cast<unsigned*>(dst), __float_as_uint(n1));
+                const int b_last = row_last / tokens;
+                if (b_last > b_first)
+                    atomicMax(reinterpret_cast<unsigned*>(dst + 2 * ep.heads),
+                              __float_as_uint(b_last > b_first + 1 ? INFINITY : n2));
+                for (int b = b_first + 2; b <= b_last; ++b)
+                    atomicMax(reinterpret_cast<unsigned*>(dst + 2 * (b - b_first) * ep.heads), __float_as_uint(INFINITY));
+            }
         }
     }
 }
@@ -280,7 +284,8 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
     __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * STAGE];
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform values stay in scalar registers
     const int wm = wave / WC, wn = wave % WC;
     // tiles walk column-fastest inside groups of 8 tile rows, so the workgroups resident on
     // one XCD cover a compact block of the output and reuse each other's panels in L2
