@@ -664,7 +664,7 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
 // A wave that alternates long MFMA-only and ALU-only blocks (the other kernel) leaves the matrix pipe
 // idle during its ALU blocks even with a second wave on the SIMD, because both waves drift into phase;
 // a homogeneous stream keeps both units busy.  Measured on a register-only replica: 1.77 vs 1.37-1.43
-// PFLOP/s-equivalent.
+// PFLOP/s-equivalent.  (Workgroups of 8 such waves sharing each K/V tile, one per CU, measured 2-3 % slower.)
 // Steps of iteration j (tile j = halves a, b):
 //   A: S(j,b)    | softmax(j,a)  | PV(j-1,b)
 //   B: S(j+1,a)  | softmax(j,b)  | PV(j,a)
