@@ -361,7 +361,7 @@ hipError_t launch_final_proj(int dtype, const float* X, const float* modf, const
 // 16-byte accesses, two independent float4 per tensor in flight per thread, and a grid of
 // up to 32768 short workgroups (measured on MI355X: many short workgroups balance the HBM
 // channels better than a few long ones); each workgroup leaves its partial sums in the
-// workspace.  Stage 2 (one workgroup) adds the partials in a fixed order in double.
+// workspace.  Stage 2 (one workgroup of 1024) adds the partials in a fixed order in double.
 static constexpr int RED_THREADS = 256;
 static constexpr int RED_MAX_BLOCKS = 32768;
 static constexpr int RED_UNROLL = 2;
@@ -407,15 +407,29 @@ __device__ __forceinline__ void block_store_partials(double (&acc)[NS], double* 
     }
 }
 
-// stage 2: NS sums over nblocks partials; thread k of 256 adds partials k, k+256, ... and the
-// 256 results are combined in a fixed tree, so the result does not depend on timing
+// stage 2: NS sums over nblocks partials with one workgroup of FIN_THREADS; thread k adds
+// partials k, k+FIN_THREADS, ... (four rows in flight, added in index order) and the per-thread
+// results are combined in a fixed tree, so the result does not depend on timing
+static constexpr int FIN_THREADS = 1024;
 template <int NS>
 __device__ __forceinline__ void reduce_partials(const double* __restrict__ part, int nblocks, double (&out)[NS]) {
-    __shared__ double sm2[NS][RED_THREADS / WAVE];
+    __shared__ double sm2[NS][FIN_THREADS / WAVE];
     double acc[NS];
 #pragma unroll
     for (int k = 0; k < NS; ++k) acc[k] = 0.0;
-    for (int b = threadIdx.x; b < nblocks; b += RED_THREADS)
+    int b = threadIdx.x;
+    for (; b + 3 * FIN_THREADS < nblocks; b += 4 * FIN_THREADS) {
+        double v[4][NS];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int k = 0; k < NS; ++k) v[u][k] = part[(long)(b + u * FIN_THREADS) * NS + k];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int k = 0; k < NS; ++k) acc[k] += v[u][k];
+    }
+    for (; b < nblocks; b += FIN_THREADS)
 #pragma unroll
         for (int k = 0; k < NS; ++k) acc[k] += part[(long)b * NS + k];
     int lane = threadIdx.x % WAVE, wave = threadIdx.x / WAVE;
@@ -428,7 +442,7 @@ __device__ __forceinline__ void reduce_partials(const double* __restrict__ part,
 #pragma unroll
     for (int k = 0; k < NS; ++k) {
         double t = 0.0;
-        for (int w = 0; w < RED_THREADS / WAVE; ++w) t += sm2[k][w];
+        for (int w = 0; w < FIN_THREADS / WAVE; ++w) t += sm2[k][w];
         out[k] = t;
     }
 }
@@ -491,7 +505,7 @@ sampler_step_kernel(const float* x, const float* __restrict__ e, const float* __
     }
 }
 
-__global__ void __launch_bounds__(RED_THREADS)
+__global__ void __launch_bounds__(FIN_THREADS)
 finish_sums4_kernel(const double* __restrict__ part, int nblocks, float* __restrict__ out) {
     double t[4];
     reduce_partials<4>(part, nblocks, t);
@@ -501,7 +515,7 @@ finish_sums4_kernel(const double* __restrict__ part, int nblocks, float* __restr
 hipError_t launch_sampler_step(const float* x, const float* e, const float* e_prev, float* x_out,
                                double a, double b, size_t n, float* sums4, void* ws, hipStream_t st) {
     if (n == 0) {
-        if (sums4) finish_sums4_kernel<<<1, RED_THREADS, 0, st>>>((const double*)ws, 0, sums4);   // four zeros
+        if (sums4) finish_sums4_kernel<<<1, FIN_THREADS, 0, st>>>((const double*)ws, 0, sums4);   // four zeros
         return hipGetLastError();
     }
     int blocks = red_blocks(n);
@@ -515,7 +529,7 @@ hipError_t launch_sampler_step(const float* x, const float* e, const float* e_pr
         sampler_step_kernel<true, false><<<blocks, RED_THREADS, 0, st>>>(x, e, nullptr, x_out, am1, bf, n, part);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    if (sums4) finish_sums4_kernel<<<1, RED_THREADS, 0, st>>>(part, blocks, sums4);
+    if (sums4) finish_sums4_kernel<<<1, FIN_THREADS, 0, st>>>(part, blocks, sums4);
     return hipGetLastError();
 }
 
@@ -546,7 +560,7 @@ rel_mae_kernel(const float* __restrict__ a, const float* __restrict__ b, size_t 
     block_store_partials<2>(acc, part);
 }
 
-__global__ void __launch_bounds__(RED_THREADS)
+__global__ void __launch_bounds__(FIN_THREADS)
 finish_rel_mae_kernel(const double* __restrict__ part, int nblocks, float* __restrict__ out3) {
     double t[2];
     reduce_partials<2>(part, nblocks, t);
@@ -565,7 +579,7 @@ hipError_t launch_rel_mae(const float* a, const float* b, size_t n, float* out3,
         hipError_t err = hipGetLastError();
         if (err != hipSuccess) return err;
     }
-    finish_rel_mae_kernel<<<1, RED_THREADS, 0, st>>>(part, blocks, out3);
+    finish_rel_mae_kernel<<<1, FIN_THREADS, 0, st>>>(part, blocks, out3);
     return hipGetLastError();
 }
 
