@@ -308,7 +308,8 @@ def expand_cycles(steps: int, warmup: int, cycle_len: Sequence[int]) -> List[int
 
 
 def run_sampler(predict: Callable, x_T, tau, a, b, warmup: int, cycle_len: Sequence[int],
-                mode: str = "reuse_then_predict", trace: Optional[list] = None):
+                mode: str = "reuse_then_predict", trace: Optional[list] = None,
+                reuse_trace: Optional[list] = None):
     """Denoising loop of Algorithm 1 with every rank simulated on one host.
 
     predict(x, tau) -> eps is the noise predictor for one sample.  Every rank r keeps
@@ -322,13 +323,21 @@ def run_sampler(predict: Callable, x_T, tau, a, b, warmup: int, cycle_len: Seque
     mode="direct_reuse" is the direct reuse process: the predictor is evaluated only
     in round 0 of a cycle and the same eps is applied in the remaining rounds.
 
+    mode="latest_eps" is a variant of Algorithm 1 in which, whenever rank 0's sample is
+    copied to all ranks at the end of a cycle, the eps rank 0 applied in that last step
+    is copied to every rank's cache as well (Algorithm 1 itself never sends eps to a
+    non-root rank), so the reuse updates of the next cycle use an eps that is 1..r
+    steps old instead of the rank's own older prediction.  With cycles of length 2 the
+    two coincide.
+
     Returns dict(x0, xs=[x after each step on rank 0], eps=[eps applied by rank 0],
     rx=[rel_mae(x_{i+1}, x_i)], re=[rel_mae(eps_i, eps_{i-1}), nan for i=0], calls).
     `trace`, if a list, receives (step, evaluating rank or -1, rank whose eps rank 0
-    applies) tuples.
+    applies) tuples; `reuse_trace`, if a list, receives (step, rank, step at which the
+    eps that rank reuses was predicted) for every reuse update of a non-root rank.
     """
     S = len(tau)
-    if mode not in ("reuse_then_predict", "direct_reuse"):
+    if mode not in ("reuse_then_predict", "direct_reuse", "latest_eps"):
         raise ValueError(mode)
     cycles = expand_cycles(S, warmup, cycle_len) if warmup < S else []
     if warmup < 1 and any(p > 1 for p in cycles):
@@ -336,6 +345,7 @@ def run_sampler(predict: Callable, x_T, tau, a, b, warmup: int, cycle_len: Seque
     pmax = max(cycles) if cycles else 1
     x = [np.asarray(x_T, dtype=F64).copy() for _ in range(pmax)]
     cache = [None] * pmax
+    born = [None] * pmax                 # step at which cache[r] was predicted
     xs, eps_used, rx, re = [], [], [], []
     calls = 0
     cyc, rnd = 0, 0
@@ -346,20 +356,24 @@ def run_sampler(predict: Callable, x_T, tau, a, b, warmup: int, cycle_len: Seque
             calls += 1
             for r in range(pmax):
                 cache[r] = e
+                born[r] = i
                 x[r] = sampler_step(x[r], e, a[i], b[i])
             applied = e
             if trace is not None:
                 trace.append((i, 0, 0))
         else:
             p = cycles[cyc]
-            if mode == "reuse_then_predict":
+            if mode != "direct_reuse":
                 master = rnd
                 e_m = predict(x[master], int(tau[i]))
                 calls += 1
                 cache[master] = e_m
+                born[master] = i
                 applied = e_m
                 for r in range(p):
                     e_r = e_m if (r == master or r == 0) else cache[r]
+                    if reuse_trace is not None and r > master:
+                        reuse_trace.append((i, r, born[r]))
                     x[r] = sampler_step(x[r], e_r, a[i], b[i])
                 if trace is not None:
                     trace.append((i, master, master))
@@ -374,6 +388,9 @@ def run_sampler(predict: Callable, x_T, tau, a, b, warmup: int, cycle_len: Seque
             if rnd == p - 1:
                 for r in range(1, pmax):
                     x[r] = x[0].copy()
+                    if mode == "latest_eps":
+                        cache[r] = applied
+                        born[r] = i
                 cyc += 1
                 rnd = 0
             else:
@@ -386,7 +403,7 @@ def run_sampler(predict: Callable, x_T, tau, a, b, warmup: int, cycle_len: Seque
 
 
 def run_sampler_batched(predict_batch: Callable, x_T, tau, a, b, warmup: int,
-                        cycle_len: Sequence[int]):
+                        cycle_len: Sequence[int], mode: str = "reuse_then_predict"):
     """Single-device batched form (BatchStep): at the start of a cycle of length p the
     inputs of all p predictor evaluations are known -- rank r's input is the current
     sample advanced r times with that rank's cached eps -- so they are evaluated as one
@@ -394,9 +411,12 @@ def run_sampler_batched(predict_batch: Callable, x_T, tau, a, b, warmup: int,
     true trajectory in order.
 
     predict_batch(xb [B,...], taus [B]) -> eps [B,...].  Returns the same dict as
-    run_sampler; its results must equal run_sampler's for the same schedule.
+    run_sampler; its results must equal run_sampler's for the same schedule and mode
+    ("reuse_then_predict" or "latest_eps").
     """
     S = len(tau)
+    if mode not in ("reuse_then_predict", "latest_eps"):
+        raise ValueError(mode)
     cycles = expand_cycles(S, warmup, cycle_len) if warmup < S else []
     if warmup < 1 and any(p > 1 for p in cycles):
         raise ValueError("eps_cache is undefined without a warm-up step")
@@ -437,6 +457,9 @@ def run_sampler_batched(predict_batch: Callable, x_T, tau, a, b, warmup: int,
             x_new = sampler_step(x0, eb[r], a[i + r], b[i + r])
             record(x_new, x0, eb[r])
             x0 = x_new
+        if mode == "latest_eps":
+            for r in range(pmax):
+                cache[r] = eb[n - 1]
         i += n
     return dict(x0=x0, xs=xs, eps=eps_used, rx=rx, re=re, calls=calls)
 

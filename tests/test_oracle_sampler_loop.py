@@ -132,6 +132,76 @@ def test_batched_form_equals_the_rank_simulation(S, m, cyc):
     assert out["calls"] == m + len(O.expand_cycles(S, m, cyc))
 
 
+def test_reuse_ages_own_cache_and_latest_eps():
+    """How old the reused eps is, from the structure of Algorithm 1 alone.  A cycle of
+    length p starts at step c; rank r (1 <= r < p) makes reuse updates at steps c..c+r-1.
+    With its own cache the eps was predicted at step c-p+r (the previous cycle's round
+    r), or at the last warm-up step in the first cycle.  In the latest-eps variant it is
+    the eps of step c-1, whatever the rank."""
+    S, m, p = 11, 2, 3
+    tau, a, b = O.ddim_coefficients(steps=S)
+    own, latest = [], []
+    O.run_sampler(scalar_predictor, np.array([0.1]), tau, a, b, m, [p] * 3, reuse_trace=own)
+    O.run_sampler(scalar_predictor, np.array([0.1]), tau, a, b, m, [p] * 3, mode="latest_eps", reuse_trace=latest)
+    exp_own, exp_latest = [], []
+    for c in (2, 5, 8):
+        for j in range(p):                    # round j: ranks j+1..p-1 reuse at step c+j
+            for r in range(j + 1, p):
+                exp_own.append((c + j, r, m - 1 if c == m else c - p + r))
+                exp_latest.append((c + j, r, c - 1))
+    assert sorted(own) == sorted(exp_own)
+    assert sorted(latest) == sorted(exp_latest)
+
+
+def test_latest_eps_straight_line_script_S7_m1_p3():
+    """Loop-free script of the latest-eps variant: the first cycle is that of Algorithm 1
+    (every cache holds e0); in the second cycle ranks 1 and 2 advance with E3, the eps of
+    the step before the cycle, instead of E2 and E3."""
+    f = scalar_predictor
+    tau, a, b = O.ddim_coefficients(steps=7)
+    st = lambda i, x, e: a[i] * x + b[i] * e
+    xT = np.array([0.3, -1.1, 2.0])
+    e0 = f(xT, tau[0]);  X1 = st(0, xT, e0)
+    E1 = f(X1, tau[1]);  X2 = st(1, X1, E1);  Y2 = st(1, X1, e0)
+    E2 = f(Y2, tau[2]);  X3 = st(2, X2, E2);  Z3 = st(2, Y2, e0)
+    E3 = f(Z3, tau[3]);  X4 = st(3, X3, E3)
+    E4 = f(X4, tau[4]);  X5 = st(4, X4, E4);  Y5 = st(4, X4, E3);  Z5 = st(4, X4, E3)
+    E5 = f(Y5, tau[5]);  X6 = st(5, X5, E5);  Z6 = st(5, Z5, E3)
+    E6 = f(Z6, tau[6]);  X7 = st(6, X6, E6)
+    out = O.run_sampler(f, xT, tau, a, b, warmup=1, cycle_len=[3, 3], mode="latest_eps")
+    for got, ref in zip(out["xs"], [X1, X2, X3, X4, X5, X6, X7]):
+        np.testing.assert_allclose(got, ref, rtol=0, atol=1e-12)
+    for got, ref in zip(out["eps"], [e0, E1, E2, E3, E4, E5, E6]):
+        np.testing.assert_allclose(got, ref, rtol=0, atol=1e-12)
+    own = O.run_sampler(f, xT, tau, a, b, warmup=1, cycle_len=[3, 3])
+    assert np.abs(out["x0"] - own["x0"]).max() > 1e-6          # the two variants differ at p = 3
+
+
+@pytest.mark.parametrize("S,m", [(9, 1), (10, 2)])
+def test_latest_eps_equals_algorithm_1_for_cycles_of_two(S, m):
+    """With p = 2 the only reuse update is rank 1's at round 0, and its own cache is the
+    eps of the step before the cycle: both variants are the same process."""
+    tau, a, b = O.ddim_coefficients(steps=S)
+    xT = np.random.default_rng(5).standard_normal(6)
+    r0 = O.run_sampler(scalar_predictor, xT, tau, a, b, m, [2] * S)
+    r1 = O.run_sampler(scalar_predictor, xT, tau, a, b, m, [2] * S, mode="latest_eps")
+    np.testing.assert_array_equal(r0["x0"], r1["x0"])
+    np.testing.assert_array_equal(np.stack(r0["xs"]), np.stack(r1["xs"]))
+
+
+@pytest.mark.parametrize("S,m,cyc", [(7, 1, [3, 3]), (9, 2, [4, 4]), (10, 1, [1, 2, 4, 2]), (12, 2, [2, 4, 8]),
+                                     (11, 3, [8])])
+def test_latest_eps_batched_form_equals_the_rank_simulation(S, m, cyc):
+    tau, a, b = O.ddim_coefficients(steps=S)
+    xT = np.random.default_rng(3).standard_normal(4)
+    ref = O.run_sampler(scalar_predictor, xT, tau, a, b, warmup=m, cycle_len=cyc, mode="latest_eps")
+    fb = lambda xb, ts: np.stack([scalar_predictor(xb[i], int(ts[i])) for i in range(len(ts))])
+    out = O.run_sampler_batched(fb, xT, tau, a, b, warmup=m, cycle_len=cyc, mode="latest_eps")
+    np.testing.assert_allclose(out["x0"], ref["x0"], rtol=0, atol=1e-13)
+    np.testing.assert_allclose(out["rx"], ref["rx"], rtol=1e-12)
+    assert out["calls"] == m + len(O.expand_cycles(S, m, cyc))
+
+
 def test_direct_reuse_is_the_plain_loop_on_the_coarser_grid():
     """Stride-2 direct reuse after one warm-up step equals DDIM whose steps 1.. are
     merged in pairs (jump consistency of the update)."""
