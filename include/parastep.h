@@ -192,7 +192,12 @@ PS_API int flow_euler_coefficients(int train_steps, int steps, int32_t* timestep
  *              warm-up; they must cover steps - warmup; the last may be cut short
  *   batched    0: one predictor call per step (rank == round evaluates);
  *              1: one call per cycle with batch = cycle length (Section 3.3)
- *   mode       0 reuse-then-predict, 1 direct reuse (predict only in round 0) */
+ *   mode       0 reuse-then-predict (Algorithm 1: a rank reuses the eps it predicted itself),
+ *              1 direct reuse (predict only in round 0; not with batched),
+ *              2 reuse-then-predict in which every rank's cache is refreshed, at the end of
+ *                each cycle, with the eps rank 0 applied in the cycle's last step (what a
+ *                single device, or ranks that also exchange eps, can do; equals mode 0 when
+ *                every cycle has length <= 2) */
 typedef struct {
     int steps;
     const int32_t* timesteps;   /* HOST [steps], strictly monotonic (descending for diffusion grids) */

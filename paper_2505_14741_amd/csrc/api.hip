@@ -497,7 +497,7 @@ struct RunPlan {
 int plan_schedule(const sampler_schedule* s, RunPlan* plan) {
     if (!s) return PS_ERR_NULL;
     if (s->steps < 1 || !s->timesteps || !s->coef_a || !s->coef_b) return s->steps < 1 ? PS_ERR_SCHEDULE : PS_ERR_NULL;
-    if (s->warmup < 0 || (s->mode != 0 && s->mode != 1) || (s->batched != 0 && s->batched != 1)) return PS_ERR_SCHEDULE;
+    if (s->warmup < 0 || (s->mode < 0 || s->mode > 2) || (s->batched != 0 && s->batched != 1)) return PS_ERR_SCHEDULE;
     if (s->batched && s->mode == 1) return PS_ERR_SCHEDULE;
     for (int i = 0; i < s->steps; ++i) {
         if (s->timesteps[i] < 0 || s->timesteps[i] >= 100000) return PS_ERR_SCHEDULE;
@@ -573,7 +573,10 @@ int sampler_run(dit* d, const sampler_schedule* s, const float* x_T, const void*
     char* base = (char*)workspace;
     const int P = plan.pmax;
     auto xbuf = [&](int r) { return (float*)(base + w.xbuf + nb * r); };
-    auto cache = [&](int r) { return (float*)(base + w.cache + nb * r); };
+    // mode 2 (latest eps): every rank reuses the eps applied in the step before the cycle;
+    // it is kept in slot 0, which Algorithm 1 never reads (rank 0 has no reuse update)
+    const bool latest = s->mode == 2;
+    auto cache = [&](int r) { return (float*)(base + w.cache + nb * (latest ? 0 : r)); };
     auto pp = [&](int i) { return (float*)(base + w.pp + nb * i); };
     auto xb = [&](int r) { return (float*)(base + w.xb + n * 4 * r); };     // contiguous [p, n]
     auto eb = [&](int r) { return (float*)(base + w.eb + n * 4 * r); };
@@ -610,8 +613,10 @@ int sampler_run(dit* d, const sampler_schedule* s, const float* x_T, const void*
                 PS_RC(forward_impl(d, xbuf(0), ctx, &t, e, 1, dws, st)); ++calls;
                 PS_RC(step(xbuf(0), e, eprev, xbuf(0), i, true));
                 eprev = e;
-                if (i == plan.warm - 1)
-                    for (int r = 1; r < P; ++r) PS_RC(copy(cache(r), e));   // eps_cache of every rank
+                if (i == plan.warm - 1) {                                   // eps_cache of every rank
+                    if (latest) PS_RC(copy(cache(0), e));
+                    else for (int r = 1; r < P; ++r) PS_RC(copy(cache(r), e));
+                }
                 continue;
             }
             const int p = plan.cycles[cyc];
@@ -627,7 +632,7 @@ int sampler_run(dit* d, const sampler_schedule* s, const float* x_T, const void*
             } else {
                 const int master = rnd;
                 float* e;
-                if (master == 0) { e = pp(toggle); toggle ^= 1; } else { e = cache(master); }
+                if (master == 0 || latest) { e = pp(toggle); toggle ^= 1; } else { e = cache(master); }
                 PS_RC(forward_impl(d, xbuf(src[master]), ctx, &t, e, 1, dws, st)); ++calls;
                 // ranks that still have to predict in this cycle advance with their own cache;
                 // they may read rank 0's buffer, so they go before rank 0's in-place update
@@ -640,6 +645,7 @@ int sampler_run(dit* d, const sampler_schedule* s, const float* x_T, const void*
             }
             if (rnd == p - 1) {                      // broadcast rank 0's sample
                 for (int r = 1; r < P; ++r) src[r] = 0;
+                if (latest && P > 1) PS_RC(copy(cache(0), eprev));
                 ++cyc; rnd = 0;
             } else {
                 ++rnd;
@@ -660,7 +666,7 @@ int sampler_run(dit* d, const sampler_schedule* s, const float* x_T, const void*
             PS_RC(copy(eprev_buf, eb(0)));
             have_prev = true;
             if (i == plan.warm - 1)
-                for (int r = 0; r < P; ++r) PS_RC(copy(cache(r), eb(0)));
+                for (int r = 0; r < (latest ? 1 : P); ++r) PS_RC(copy(cache(r), eb(0)));
         }
         for (size_t c = 0; c < plan.cycles.size() && i < s->steps; ++c) {
             int p = plan.cycles[c];
@@ -678,7 +684,8 @@ int sampler_run(dit* d, const sampler_schedule* s, const float* x_T, const void*
                 const float* prev = r == 0 ? (have_prev ? eprev_buf : nullptr) : eb(r - 1);
                 PS_RC(step(xbuf(0), eb(r), prev, xbuf(0), i + r, true));
             }
-            for (int r = 0; r < nn; ++r) PS_RC(copy(cache(r), eb(r)));
+            if (latest) PS_RC(copy(cache(0), eb(nn - 1)));
+            else for (int r = 0; r < nn; ++r) PS_RC(copy(cache(r), eb(r)));
             PS_RC(copy(eprev_buf, eb(nn - 1)));
             have_prev = true;
             i += nn;

@@ -196,6 +196,49 @@ def test_direct_reuse_matches_oracle():
     np.testing.assert_allclose(s[:, 0] / s[:, 1], ref["rx"], rtol=1e-4)
 
 
+@pytest.mark.parametrize("S,m,cyc", [(7, 1, [3, 3]), (10, 1, [1, 2, 4, 2]), (12, 2, [2, 4, 8])])
+def test_latest_eps_variant_matches_oracle_and_batched_is_bitwise(S, m, cyc):
+    """mode 2: the caches of all ranks are refreshed with the last applied eps at the end of a cycle."""
+    print(f"sampler_run latest-eps S={S} m={m} cyc={cyc}", flush=True)
+    cfg, W, d = setup("tiny_text", "unit")
+    x_T, ctx = I.make_latent(cfg, 1), I.make_context(cfg, 1)
+    ref = oracle_run(cfg, W, x_T, ctx, S, m, cyc, mode="latest_eps")
+    own = oracle_run(cfg, W, x_T, ctx, S, m, cyc)
+    assert np.abs(ref["x0"] - own["x0"]).max() > 1e-6 * np.abs(own["x0"]).max()   # the variants really differ
+    x0, sums, calls = gpu_run(d, dev(x_T), dev(ctx), S, m, cyc, mode=2)
+    assert calls == S
+    close_fp32(host(x0)[0], ref["x0"])
+    s = host(sums)
+    np.testing.assert_allclose(s[:, 0] / s[:, 1], ref["rx"], rtol=1e-4)
+    np.testing.assert_allclose(s[1:, 2] / s[1:, 3], ref["re"][1:], rtol=1e-4, atol=1e-7)
+    x0b, sb, cb = gpu_run(d, dev(x_T), dev(ctx), S, m, cyc, batched=True, mode=2)
+    assert torch.equal(x0b, x0) and torch.equal(sb, sums)
+    assert cb == m + len(O.expand_cycles(S, m, cyc))
+
+
+def test_latest_eps_equals_mode_0_for_cycles_of_two_bitwise():
+    cfg, W, d = setup("tiny", "unit")
+    x_T = dev(I.make_latent(cfg, 1))
+    x0a, sa, _ = gpu_run(d, x_T, None, 9, 1, [2] * 4, mode=0)
+    x0b, sb, _ = gpu_run(d, x_T, None, 9, 1, [2] * 4, mode=2)
+    assert torch.equal(x0a, x0b) and torch.equal(sa, sb)
+
+
+def test_cycle_of_eight_batched_matches_oracle():
+    """One predictor call over a batch of eight per cycle (the widest BatchStep setting of Section 4.3)."""
+    cfg, W, d = setup("tiny_text", "unit")
+    x_T, ctx = I.make_latent(cfg, 1), I.make_context(cfg, 1)
+    S, m, cyc = 19, 2, [8, 8, 8]                  # the last cycle is cut to one step
+    ref = oracle_run(cfg, W, x_T, ctx, S, m, cyc)
+    x0, sums, calls = gpu_run(d, dev(x_T), dev(ctx), S, m, cyc, batched=True)
+    assert calls == 2 + 3
+    close_fp32(host(x0)[0], ref["x0"])
+    s = host(sums)
+    np.testing.assert_allclose(s[:, 0] / s[:, 1], ref["rx"], rtol=1e-4)
+    x0u, su, cu = gpu_run(d, dev(x_T), dev(ctx), S, m, cyc, batched=False)
+    assert torch.equal(x0u, x0) and torch.equal(su, sums) and cu == S
+
+
 def test_reduced_30_layer_reuse_run_bf16():
     """Six DDIM steps, window 2, 30 layers at width 1920 on 112 tokens, vs the oracle."""
     print("sampler_run reduced", flush=True)

@@ -203,12 +203,14 @@ def test_schedule_validation():
     ok = _sched()
     assert L.sampler_workspace_bytes(h, C.byref(ok.c)) > 0
     assert L.sampler_workspace_bytes(h, C.byref(_sched(batched=1).c)) > L.sampler_workspace_bytes(h, C.byref(ok.c))
+    assert L.sampler_workspace_bytes(h, C.byref(_sched(mode=2).c)) == L.sampler_workspace_bytes(h, C.byref(ok.c))
+    assert L.sampler_workspace_bytes(h, C.byref(_sched(mode=2, batched=1).c)) > 0
     bad = [
         _sched(warmup=0),                         # eps_cache undefined: no warm-up, window 2
         _sched(cyc=(2, 2)),                       # cycles do not cover steps - warmup
         _sched(cyc=(2, 0, 4)),                    # zero-length cycle
         _sched(cyc=(17,)),                        # beyond the batch limit
-        _sched(mode=2), _sched(batched=1, mode=1), _sched(warmup=-1),
+        _sched(mode=3), _sched(mode=-1), _sched(batched=1, mode=1), _sched(warmup=-1),
         _sched(ts=[875, 750, 625, 625, 375, 250, 125, 0]),     # not strictly monotonic
         _sched(ts=[875, 750, 625, 700, 375, 250, 125, 0]),     # changes direction
     ]
