@@ -100,6 +100,7 @@ static hipError_t launch_generic_attn(const T* q, const T* k, const T* v, T* o, 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(4))) short s16x4_t;
 typedef __attribute__((ext_vector_type(2))) int i32x2_t;
 
@@ -658,7 +659,7 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
 // Check-free kernel for heads with bounded exponents (see attn_bound_kernel): p = 2^(c s), no reference.
 // Work split and LDS layout as in attn_mfma_kernel (4 waves x 64 queries, K/V tiles of 64 keys straight into
 // an LDS ring, two workgroups per CU), but the loop is software-pipelined over 32-key half tiles.  In
-// every step a wave issues the 8 MFMAs of S^T for the NEXT half, the exp2 / pack / row-sum instructions of
+// every step a wave issues the 8 MFMAs of S^T for the NEXT half, the exp2 / pack instructions (and the row-sum MFMAs) of
 // the CURRENT half and the 8 MFMAs of O^T += V^T P^T for the PREVIOUS half.  The three are independent,
 // so the compiler interleaves them and the instruction stream is a steady mix of MFMA and vector ALU work.
 // A wave that alternates long MFMA-only and ALU-only blocks (the other kernel) leaves the matrix pipe
@@ -731,9 +732,21 @@ attn_sp_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const
         for (int t = 0; t < QT; ++t)
 #pragma unroll
             for (int e = 0; e < 16; ++e) oacc[d][t][e] = 0.f;
-    float lsum[QT];
+    // Row sums on the matrix pipe.  A P^T fragment (16 keys x 32 queries, lane = query % 32 with 8 keys, the
+    // other 8 in lane + 32) read as the B operand of the 16x16x32 product puts queries 0-15 into k-groups 0
+    // and 2 and queries 16-31 into k-groups 1 and 3 of column lane % 16.  With an A operand whose row 0 is
+    // one over the even groups and row 1 one over the odd groups, rows 0 and 1 of the 16x16 result are the
+    // key sums of queries 0-15 and 16-31: one MFMA replaces four v_dot2c and the adds that follow.
+    f32x4_t lacc[QT];
 #pragma unroll
-    for (int t = 0; t < QT; ++t) lsum[t] = 0.f;
+    for (int t = 0; t < QT; ++t) lacc[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    bf16x8_t sel;
+    {
+        const int r16 = lane & 15, grp = lane >> 4;
+        const bool on = (r16 == 0 && (grp & 1) == 0) || (r16 == 1 && (grp & 1) == 1);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sel[e] = on ? (__bf16)1.0f : (__bf16)0.0f;
+    }
 
     // loads: per tile 8 K + 8 V row groups of 8 rows; wave w takes groups w and w+4 of each
     const int lr = lane >> 3;
@@ -813,7 +826,6 @@ attn_sp_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const
         }
 #pragma unroll
         for (int t = 0; t < QT; ++t) {
-            float rs = 0.f;
 #pragma unroll
             for (int g = 0; g < 2; ++g) {          // k16-step inside the 32-key half
                 bf16x8_t pk;
@@ -823,9 +835,8 @@ attn_sp_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const
                     pk[e] = (__bf16)__builtin_amdgcn_exp2f(PRESCALED ? a : a * cexp);
                 }
                 pf[t][g] = pk;
-                rs = rowsum_bf16x8(pk, rs);
+                lacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sel, pk, lacc[t], 0, 0, 0);
             }
-            lsum[t] += rs;
         }
     };
     // O^T += V^T P^T for half hh of the tile in ring slot `slot`; k-slot (half, e) of step g is key
@@ -843,6 +854,12 @@ attn_sp_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const
                 for (int t = 0; t < QT; ++t)
                     oacc[dt][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[t][g], oacc[dt][t], 0, 0, 0);
             }
+    };
+
+    // key sum of this lane's query: row n / 16, column n % 16 of the small product = register n / 16 of lane n % 16
+    auto rowsum_of = [&](int t) -> float {
+        const float lo = __shfl(lacc[t][0], col & 15, 64), hi = __shfl(lacc[t][1], col & 15, 64);
+        return col < 16 ? lo : hi;
     };
 
     f32x16_t sa[QT], sb[QT];
@@ -890,7 +907,7 @@ attn_sp_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const
         float* pp = part + (long)piece * BQ * PART_STRIDE;
 #pragma unroll
         for (int t = 0; t < QT; ++t) {
-            const float l = sum_across_halves(lsum[t]);
+            const float l = rowsum_of(t);
             float* pr = pp + (long)(wave * (QT * 32) + t * 32 + col) * PART_STRIDE;
 #pragma unroll
             for (int dt = 0; dt < 2; ++dt)
@@ -905,7 +922,7 @@ attn_sp_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const
     }
 #pragma unroll
     for (int t = 0; t < QT; ++t) {
-        float l = sum_across_halves(lsum[t]);
+        float l = rowsum_of(t);
         float inv = 1.0f / l;
         int qi = q0 + t * 32 + col;
         if (qi < seq) {
