@@ -296,6 +296,12 @@ attn_merge_kernel(const float* __restrict__ part, bf16_t* __restrict__ o, int se
 // global->LDS load of 16 bytes per lane: lane j's bytes land at lds_addr + 16*j (lds_addr
 // wave-uniform, passed through M0).  _base: scalar 64-bit base + per-lane 32-bit byte offset;
 // _ptr: per-lane 64-bit address.
+// XOR applied to the 16-byte chunk index of V row r in LDS (low three bits of r matter): bits 0-1 = r & 3,
+// bit 2 = bit 1 of r.  A transposing fragment read covers rows 4m..4m+3 with 32 lanes per cycle; rows r and
+// r + 2 start in the same bank, and the flipped bit 2 keeps their 64-byte windows apart (with r & 7 instead
+// every such read took twice as long: measured as LDS bank conflict cycles).
+__device__ __forceinline__ int v_swizzle(int r) { return (r & 3) | ((r & 2) << 1); }
+
 __device__ __forceinline__ void lds_dma16_base(unsigned voff, const void* sbase, unsigned lds_addr) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_addr)
                  : "memory", "m0");
@@ -407,7 +413,9 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
     // at base + 16j), so the XOR swizzles are applied on the global side.  LDS has 64
     // four-byte banks.  K fragments are 16-byte reads of 16 consecutive rows per cycle:
     // slot p of row r holds chunk p ^ ((r>>1)&7).  V fragments are transposing 8-byte
-    // reads that touch 8 consecutive rows x 64 bytes: slot p of row r holds chunk p ^ (r&7).
+    // reads, 32 lanes per cycle, that touch 4 consecutive rows x 64 bytes: slot p of row r
+    // holds chunk p ^ v_swizzle(r), which sends rows r and r+2 (same 32 banks) to different
+    // 64-byte halves.
     // Per stage: 8 K groups + 8 V groups; wave w takes K groups w, w+4 and V groups w, w+4.
     // The loads are issued from inline asm (the compiler then never orders LDS reads of other
     // stages behind them; the explicit vmcnt waits and barriers below publish a stage).  A tile
@@ -415,7 +423,7 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
     // offset fixed for the whole kernel, so the loop spends no vector instruction on addresses;
     // the last, ragged tile and the look-ahead tiles past the end clamp their rows per lane.
     const int lr = lane >> 3;
-    const int lc_v = (lane & 7) ^ lr;
+    const int lc_v = (lane & 7) ^ v_swizzle(lr);
     const unsigned lds_base = (unsigned)(size_t)PS_LDS_PTR(lds);
     unsigned koff[2], voff[2];
 #pragma unroll
@@ -458,8 +466,8 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
     const int tsub = (tj & 1) * 8;
     // rows 16*step (+8) keep trow's low 3 bits, so the swizzled slot is the same for every
     // step; d tile 1 flips bit 2 of the slot
-    const unsigned voff0 = KV * 128 + trow * 128 + ((tchunk ^ (trow & 7)) << 4) + tsub;
-    const unsigned voff1 = KV * 128 + trow * 128 + (((4 + tchunk) ^ (trow & 7)) << 4) + tsub;
+    const unsigned voff0 = KV * 128 + trow * 128 + ((tchunk ^ v_swizzle(trow)) << 4) + tsub;
+    const unsigned voff1 = KV * 128 + trow * 128 + (((4 + tchunk) ^ v_swizzle(trow)) << 4) + tsub;
 
     issue(jt0, 0);
     issue(jt0 + 1, 1);                             // tiles past the end are harmless re-reads
@@ -750,7 +758,7 @@ attn_sp_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const
 
     // loads: per tile 8 K + 8 V row groups of 8 rows; wave w takes groups w and w+4 of each
     const int lr = lane >> 3;
-    const int lc_v = (lane & 7) ^ lr;
+    const int lc_v = (lane & 7) ^ v_swizzle(lr);
     const unsigned lds_base = (unsigned)(size_t)PS_LDS_PTR(lds);
     unsigned koff[2], voff[2];
 #pragma unroll
@@ -789,8 +797,8 @@ attn_sp_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const
     const int trow = 4 * (tg >> 1) + (tj >> 2);
     const int tchunk = 2 * (tg & 1) + ((tj & 3) >> 1);
     const int tsub = (tj & 1) * 8;
-    const int vad0 = KV * 128 + trow * 128 + ((tchunk ^ (trow & 7)) << 4) + tsub;
-    const int vad1 = KV * 128 + trow * 128 + (((4 + tchunk) ^ (trow & 7)) << 4) + tsub;
+    const int vad0 = KV * 128 + trow * 128 + ((tchunk ^ v_swizzle(trow)) << 4) + tsub;
+    const int vad1 = KV * 128 + trow * 128 + (((4 + tchunk) ^ v_swizzle(trow)) << 4) + tsub;
     // K fragment addressing: key row 32*hh + col, chunk (2 ks + half) ^ ((row >> 1) & 7); the row term of
     // the XOR is the same for both halves of a tile (32 rows = 16 * 2)
     const int ksw = (col >> 1) & 7;
