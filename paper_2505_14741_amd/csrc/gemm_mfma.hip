@@ -56,7 +56,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(2))) float f32x2_t;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
 
-constexpr int EPI_LDS_STRIDE = 72;                       // floats per row of a wave's 32 x 64 patch
+constexpr int EPI_LDS_STRIDE = 68;                       // floats per row of a wave's 32 x 64 patch (68 * 4 rows = 16 banks mod 64)
 constexpr int EPI_LDS_FLOATS = 32 * EPI_LDS_STRIDE;
 
 // Epilogue of 64 columns of one wave (accumulator tiles J0, J0+1 of each of its TM tile rows): TM strips of
@@ -65,9 +65,9 @@ constexpr int EPI_LDS_FLOATS = 32 * EPI_LDS_STRIDE;
 // Offsets are 32-bit element indices from the uniform base pointers (the launcher
 // guarantees M*Nn < 2^31); Nn % 4 == 0, so a lane's 4 columns are inside or outside together.
 template <int TM, int TN, int J0, int KIND, bool CHECK>
-__device__ __forceinline__ void wave_epilogue(f32x16_t (&acc)[TM][TN], const Epilogue& ep, bf16_t* __restrict__ C,
+__device__ __forceinline__ void wave_epilogue(f32x4_t (&acc)[TM][TN][4], const Epilogue& ep, bf16_t* __restrict__ C,
                                               int M, int Nn, int wrow0, int wcol0, int lane, float* patch) {
-    const int frow = lane & 31, fhalf = lane >> 5;       // accumulator side: column, row offset 4*fhalf
+    const int fcol = lane & 15, fgrp = lane >> 4;        // accumulator side: column within 16, row offset 4*fgrp
     const int rr = lane >> 4, cc = (lane & 15) * 4;      // row-contiguous side: row within 4, first column
     const int col = wcol0 + cc;
     const bool col_ok = !CHECK || col < Nn;
@@ -138,12 +138,15 @@ __device__ __forceinline__ void wave_epilogue(f32x16_t (&acc)[TM][TN], const Epi
     }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-        // accumulators -> patch (a store instruction covers 2 rows x 32 columns: 64 banks)
+        // accumulators -> patch (a store instruction covers 4 rows x 16 columns; the row stride puts rows 4
+        // apart 16 banks apart: 64 banks)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e)
-                patch[(8 * (e >> 2) + 4 * fhalf + (e & 3)) * EPI_LDS_STRIDE + j * 32 + frow] = acc[i][J0 + j][e];
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    patch[(16 * (q >> 1) + 4 * fgrp + e) * EPI_LDS_STRIDE + j * 32 + 16 * (q & 1) + fcol] = acc[i][J0 + j][q][e];
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // LDS is in order per wave; this pins the compiler too
         f32x4_t v[8];
 #pragma unroll
@@ -344,67 +347,75 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
         }
     };
 
-    f32x16_t acc[TM][TN];
+    // Accumulators: every 32 x 32 block of the wave's outputs is four 16 x 16 products (q = 2 * row half + column
+    // half) of v_mfma_f32_16x16x32_bf16, which sustains a higher rate than the 32x32x16 form on this chip
+    // (2.1 against 1.85 PFLOP/s in a loop of nothing else).  Lane l of a 16 x 16 result holds column l % 16, rows
+    // 4 * (l / 16) .. + 3; of an operand fragment row (or column) l % 16, k = 8 * (l / 16) .. + 7 of a 32-deep step.
+    f32x4_t acc[TM][TN][4];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+            for (int q = 0; q < 4; ++q) acc[i][j][q] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-    const int frow = lane & 31, fhalf = lane >> 5;
-    int aoff[TM], boff[TN];
+    constexpr int FA = 2 * TM, FB = 2 * TN;              // 16-row fragments of A and of W per k-step
+    static_assert(BK == 64, "two 32-deep k-steps per stage");
+    static_assert(FA >= FB, "the W fragments of the next step are read in the first FB fragment rounds");
+    const int l16 = lane & 15, kgrp = lane >> 4;
+    int aoff[FA], boff[FB];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) aoff[i] = (wm * WM + i * 32 + frow) * ROWB;
+    for (int x = 0; x < FA; ++x) aoff[x] = (wm * WM + x * 16 + l16) * ROWB;
 #pragma unroll
-    for (int j = 0; j < TN; ++j) boff[j] = (BM + wn * WN + j * 32 + frow) * ROWB;
-    const int sw = BK == 64 ? ((frow >> 1) & 7) : ((frow >> 2) & 3);
+    for (int y = 0; y < FB; ++y) boff[y] = (BM + wn * WN + y * 16 + l16) * ROWB;
+    const int sw = (l16 >> 1) & 7;                       // the row offsets above are multiples of 16
+    auto slot_of = [&](int ks) { return ((ks * 4 + kgrp) ^ sw) << 4; };
 
-    // Fragments are double-buffered in registers: the LDS reads of k-step s+1 are issued among
-    // the MFMAs of step s, and the reads of the next stage's first step follow the one barrier
-    // per stage, which sits in front of the last step's MFMAs (those already have their
-    // operands, so the matrix pipe keeps running while the stage hand-over completes).
-    bf16x8_t fa[2][TM], fb[2][TN];
-    auto load_frags = [&](int buf, const unsigned char* st, int ks) {
-        const int slot = ((ks * 2 + fhalf) ^ sw) << 4;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) fa[buf][i] = *reinterpret_cast<const bf16x8_t*>(st + aoff[i] + slot);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) fb[buf][j] = *reinterpret_cast<const bf16x8_t*>(st + boff[j] + slot);
-    };
+    // A fragments live in one register set: fragment x is read again, for the next k-step, right after the FB
+    // MFMAs that consume it (a full k-step before its next use).  W fragments are used by every round of a
+    // step, so they are double-buffered.  The one barrier per stage sits in front of the stage's last step,
+    // whose operands are already in registers.
+    bf16x8_t fa[FA], fb[2][FB];
 #pragma unroll
     for (int p = 0; p < NST - 1; ++p) issue(p);
     wait_vmcnt<(NST - 2) * GPW>();                       // own share of stage 0
     __syncthreads();
     issue(NST - 1);
-    load_frags(0, lds, 0);
+    {
+        const int slot = slot_of(0);
+#pragma unroll
+        for (int x = 0; x < FA; ++x) fa[x] = *reinterpret_cast<const bf16x8_t*>(lds + aoff[x] + slot);
+#pragma unroll
+        for (int y = 0; y < FB; ++y) fb[0][y] = *reinterpret_cast<const bf16x8_t*>(lds + boff[y] + slot);
+    }
     for (int kt = 0; kt < k1 - k0; ++kt) {
         const unsigned char* st = lds + (kt % NST) * STAGE;
         const unsigned char* nx = lds + ((kt + 1) % NST) * STAGE;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            if (ks + 1 < KS) {
-                load_frags((ks + 1) & 1, st, ks + 1);
-            } else {
+        for (int ks = 0; ks < 2; ++ks) {
+            const unsigned char* src = st;               // where the next step's fragments come from
+            if (ks == 1) {
                 wait_vmcnt<(NST - 2) * GPW>();           // own share of stage kt+1 has landed
-                __syncthreads();                         // ... everyone's; and stage kt is in registers everywhere
+                __syncthreads();                         // ... everyone's; and nobody reads stage kt any more
                 issue(kt + NST);                         // into the slot stage kt occupied
-                load_frags((ks + 1) & 1, nx, 0);
+                src = nx;
                 __builtin_amdgcn_sched_barrier(0);       // hand-over code stays ahead of the MFMAs
             }
+            const int slot = slot_of(ks ^ 1);
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+            for (int x = 0; x < FA; ++x) {
+                if (x < FB) fb[ks ^ 1][x] = *reinterpret_cast<const bf16x8_t*>(src + boff[x] + slot);
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
-            if (ks + 1 < KS) {
-                // one LDS read in the shadow of each MFMA, then the remaining MFMAs
+                for (int y = 0; y < FB; ++y)
+                    acc[x >> 1][y >> 1][(x & 1) * 2 + (y & 1)] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        fa[x], fb[ks][y], acc[x >> 1][y >> 1][(x & 1) * 2 + (y & 1)], 0, 0, 0);
+                fa[x] = *reinterpret_cast<const bf16x8_t*>(src + aoff[x] + slot);
+            }
 #pragma unroll
-                for (int r = 0; r < TM + TN; ++r) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                }
-                __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - TM - TN > 0 ? TM * TN - TM - TN : 0, 0);
+            for (int x = 0; x < FA; ++x) {
+                __builtin_amdgcn_sched_group_barrier(0x008, FB, 0);
+                if (x < FB) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -420,9 +431,8 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int e4 = 0; e4 < 4; ++e4)
-                    *reinterpret_cast<f32x4_t*>(pp + (i * TN + j) * 64 * 16 + e4 * 4) =
-                        f32x4_t{acc[i][j][e4 * 4], acc[i][j][e4 * 4 + 1], acc[i][j][e4 * 4 + 2], acc[i][j][e4 * 4 + 3]};
+                for (int q = 0; q < 4; ++q)
+                    *reinterpret_cast<f32x4_t*>(pp + (i * TN + j) * 64 * 16 + q * 4) = acc[i][j][q];
         return;
     }
     float* patch = reinterpret_cast<float*>(lds) + wave * EPI_LDS_FLOATS;
@@ -461,13 +471,13 @@ gemm_tail_kernel(bf16_t* __restrict__ C, int M, int Nn, int tiles_m, int tiles_n
         m0 = (band * GM + in_band % rows_here) * BM;
         n0 = (in_band / rows_here) * BN;
     }
-    f32x16_t acc[TM][TN];
+    f32x4_t acc[TM][TN][4];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+            for (int q = 0; q < 4; ++q) acc[i][j][q] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     for (int pi = 0; pi < nsplit; ++pi) {
         const float* pp = ep.split_ws + ((((long)blockIdx.x * nsplit + pi) * NW + wave) * (TM * TN) * 64 + lane) * 16;
 #pragma unroll
@@ -475,11 +485,8 @@ gemm_tail_kernel(bf16_t* __restrict__ C, int M, int Nn, int tiles_m, int tiles_n
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int e4 = 0; e4 < 4; ++e4) {
-                    const f32x4_t v = *reinterpret_cast<const f32x4_t*>(pp + (i * TN + j) * 64 * 16 + e4 * 4);
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) acc[i][j][e4 * 4 + c] += v[c];
-                }
+                for (int q = 0; q < 4; ++q)
+                    acc[i][j][q] += *reinterpret_cast<const f32x4_t*>(pp + (i * TN + j) * 64 * 16 + q * 4);
     }
     wave_epilogue<TM, TN, 0, KIND, true>(acc, ep, C, M, Nn, m0 + wm * WM, n0 + wn * WN, lane, patches + wave * EPI_LDS_FLOATS);
     if constexpr (TN == 4)
