@@ -2,12 +2,14 @@
 //
 // Both operands are K-contiguous, so each lane's MFMA fragment (8 consecutive k of one
 // row) is a single 16-byte LDS read.  A workgroup computes a BM x BN tile with WR x WC
-// waves, every wave owning (BM/WR) x 64 outputs as 32x32 v_mfma_f32_32x32x16_bf16 tiles.
+// waves, every wave owning (BM/WR) x (BN/WC) outputs as 16x16 v_mfma_f32_16x16x32_bf16 products
+// (a loop of nothing but these sustains 2.1 PFLOP/s on MI355X, the 32x32x16 form 1.85).
 // K is consumed 64 at a time through a two-stage LDS ring filled by direct global->LDS
 // loads (global_load_lds_dwordx4: no staging registers, no ds_write): the loads of slice
-// k+1 are in flight while slice k is multiplied, one barrier per slice.  Fragments are
-// double-buffered in registers, each LDS read issued in the shadow of an MFMA of the
-// previous 16-deep step.
+// k+1 are in flight while slice k is multiplied, one barrier per slice.  The A fragments
+// of the next 32-deep step are read into the registers of the current ones as soon as
+// their MFMAs are issued, the W fragments are double-buffered; LDS reads sit in the
+// shadow of the MFMAs.
 //
 // LDS rows are 128 bytes (64 bf16).  A direct load writes lane j's 16 bytes at
 // base + 16*j, so one wave instruction fills 8 rows.  LDS has 64 four-byte banks and a
@@ -17,9 +19,9 @@
 // swizzle is applied on the global side: lane j of row group g fetches chunk
 // (j%8) ^ (4*(g%2) + j/16) of row 8g + j/8.
 //
-// Epilogue: the 32x32 accumulator gives lane l column l%32 and rows 8*(i/4) + 4*(l/32) + i%4,
+// Epilogue: a 16x16 accumulator gives lane l column l%16 and rows 4*(l/16) + i,
 // which would make every store a 2-byte scatter.  Each wave instead passes its tiles, 32 rows
-// x 64 columns at a time, through a private LDS patch (row stride 72 floats: conflict-free
+// x 64 columns at a time, through a private LDS patch (row stride 68 floats: conflict-free
 // both ways) and reads them back row-contiguous, 4 consecutive columns per lane and 16
 // lanes per row.  Bias, GELU, the gated residual update and the rotary rotation then work
 // on 16-byte pieces: one 8-byte bf16 store (or 16-byte fp32 store) per 4 outputs, whole
@@ -582,8 +584,10 @@ hipError_t launch_gemm_mfma(const bf16_t* A, const bf16_t* W, bf16_t* C, int M, 
     switch (p.variant) {
         case 1: return launch_tile<256, 256, 2, 4, 64, 2>(A, W, C, M, Nn, K, p, ep, st);   // 8 waves, 128x64 each
         case 2: return launch_tile<128, 128, 2, 2, 64, 2>(A, W, C, M, Nn, K, p, ep, st);   // 4 waves, 64x64 each, 2 per CU
-        // Measured and dropped: 4 waves of 128x128 outputs on the 256x256 tile (fewer LDS reads per MFMA, but one
-        // wave per SIMD issues an MFMA only every ~48 cycles: 5-15 % slower); 32-deep stages in rings of 3 or 4
+        // Measured and dropped: 4 waves of 128x128 outputs on the 256x256 tile (fewer LDS reads per MFMA; with the
+        // 32x32x16 MFMA one wave per SIMD issued one only every ~48 cycles: 5-15 % slower; with 16x16x32 the 256
+        // accumulator registers per lane make the compiler shuttle values between the two register files, 3-4
+        // copies per MFMA: 30 % slower); 32-deep stages in rings of 3 or 4
         // (5-25 % slower: twice the barriers).  With the loads of the loop taken out (timing probe) both tiles
         // reach 1.3-1.4 PFLOP/s, with every tile loading the same L2-resident panels only 4-10 % more than now:
         // the global->LDS path itself, not the memory behind L2, is what the loop waits for (a stand-alone stream
