@@ -22,8 +22,8 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # HBM bytes per launch of the dominant attention kernel at the `full` shape, from rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE scaled by a plain 1 GiB copy (profiles/attn3d_full_hbm_traffic.md): 490 MB fetched + 96 MB written
-ATTN_HBM_BYTES_PER_LAUNCH = 5.86e8
+# WRITE_SIZE scaled by a plain 1 GiB copy (profiles/attn3d_full_hbm_traffic.md): 502 MB fetched + 108 MB written
+ATTN_HBM_BYTES_PER_LAUNCH = 6.10e8
 
 
 def device_weights(cfg, torch, seed):
