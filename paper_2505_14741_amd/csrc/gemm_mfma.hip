@@ -264,14 +264,14 @@ __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-// One BM x BN output tile per workgroup, WR x WC waves of (BM/WR) x 64 outputs each.
-// BK: K depth of an LDS stage (64 or 32 bf16 = 128- or 64-byte rows); NST: ring depth.
+// One BM x BN output tile (rows m0.., columns n0..), k-tiles k0..k1-1 of 64, by the WR x WC waves of a workgroup,
+// each owning (BM/WR) x (BN/WC) outputs.  piece >= 0: a K-split piece, accumulators go to ep.split_ws.
+// BK: K depth of an LDS stage; NST: ring depth; lds: NST * (BM + BN) * 2 * BK bytes, 1024-aligned.
 template <int BM, int BN, int WR, int WC, int BK, int NST, int KIND>
-__global__ void __launch_bounds__(WR * WC * 64, (WR * WC == 4 && BM * BN <= 128 * 128) ? 2 : 1)
-gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf16_t* __restrict__ C,
-                 int M, int Nn, int K, int tiles_m, int tiles_n, int full_tiles, int nsplit, Epilogue ep) {
+__device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf16_t* __restrict__ C,
+                                          int M, int Nn, int K, int m0, int n0, int k0, int k1, int piece,
+                                          const Epilogue& ep, unsigned char* lds) {
     static_assert(BK == 64 || BK == 32, "stage depth");
-    constexpr int KS = BK / 16;
     constexpr int NW = WR * WC;
     constexpr int WM = BM / WR, WN = BN / WC;
     constexpr int TM = WM / 32, TN = WN / 32;
@@ -286,37 +286,11 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
     static_assert(BM % RPI == 0, "a load group must not straddle the A/W boundary");
     static_assert((NST - 1) * GPW <= 63, "vmcnt range");
     static_assert(NW * EPI_LDS_FLOATS * 4 <= NST * STAGE, "epilogue patches reuse the stage memory");
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * STAGE];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform values stay in scalar registers
     const int wm = wave / WC, wn = wave % WC;
-    // tiles walk column-fastest inside groups of 8 tile rows, so the workgroups resident on
-    // one XCD cover a compact block of the output and reuse each other's panels in L2
-    // The first full_tiles workgroups compute one output tile each.  The tiles beyond them -- the last, partial
-    // round of the chip's workgroup slots -- are each split nsplit ways along K; such a workgroup leaves its
-    // fp32 partial sums in ep.split_ws (in accumulator layout) for gemm_tail_kernel.
-    const int nk = K / BK;
-    int tile, piece = -1, k0 = 0, k1 = nk;
-    if ((int)blockIdx.x < full_tiles) {
-        tile = xcd_remap(blockIdx.x, full_tiles);
-    } else {
-        piece = blockIdx.x - full_tiles;
-        tile = full_tiles + piece / nsplit;
-        const int pi = piece % nsplit;
-        k0 = nk * pi / nsplit;
-        k1 = nk * (pi + 1) / nsplit;
-    }
-    int m0, n0;
-    {
-        constexpr int GM = 8;
-        int per_band = GM * tiles_n;
-        int band = tile / per_band, in_band = tile % per_band;
-        int rows_here = min(GM, tiles_m - band * GM);
-        m0 = (band * GM + in_band % rows_here) * BM;
-        n0 = (in_band / rows_here) * BN;
-    }
 
     // direct loads: lane j of load group g lands at group base + 16j = row RPI*g + j/CPR, slot j%CPR; the slot
     // holds chunk (j%CPR) ^ swizzle(row) of the row (applied on the global side):
@@ -450,6 +424,52 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
     }
 }
 
+// The first full_tiles workgroups compute one BM x BN output tile each.  The tiles beyond them -- the last, partial
+// round of the chip's workgroup slots -- are shared out so that the round is shorter:
+//   rsplit == 2: two workgroups per tile, each computing BM/2 of its rows (no reduction; the wide tile's way);
+//   nsplit  > 1: nsplit workgroups per tile along K, fp32 partial sums to ep.split_ws (in accumulator layout)
+//                for gemm_tail_kernel (the narrow tile's way, where K is long).
+// Tiles walk column-fastest inside bands of 8 tile rows, so the workgroups resident on one XCD cover a compact
+// block of the output and reuse each other's panels in L2.
+template <int BM, int BN, int WR, int WC, int BK, int NST, int KIND>
+__global__ void __launch_bounds__(WR * WC * 64, (WR * WC == 4 && BM * BN <= 128 * 128) ? 2 : 1)
+gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf16_t* __restrict__ C,
+                 int M, int Nn, int K, int tiles_m, int tiles_n, int full_tiles, int nsplit, int rsplit, Epilogue ep) {
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * (BM + BN) * BK * 2];
+    const int nk = K / BK;
+    int tile, piece = -1, part = 0, k0 = 0, k1 = nk;
+    if ((int)blockIdx.x < full_tiles) {
+        tile = xcd_remap(blockIdx.x, full_tiles);
+    } else if (rsplit == 2) {
+        const int t = blockIdx.x - full_tiles;
+        tile = full_tiles + (t >> 1);
+        part = t & 1;
+    } else {
+        piece = blockIdx.x - full_tiles;
+        tile = full_tiles + piece / nsplit;
+        const int pi = piece % nsplit;
+        k0 = nk * pi / nsplit;
+        k1 = nk * (pi + 1) / nsplit;
+    }
+    int m0, n0;
+    {
+        constexpr int GM = 8;
+        int per_band = GM * tiles_n;
+        int band = tile / per_band, in_band = tile % per_band;
+        int rows_here = min(GM, tiles_m - band * GM);
+        m0 = (band * GM + in_band % rows_here) * BM;
+        n0 = (in_band / rows_here) * BN;
+    }
+    if constexpr (BM == 256 && WR == 2) {
+        if (rsplit == 2 && (int)blockIdx.x >= full_tiles) {       // uniform over the workgroup
+            m0 += part * (BM / 2);
+            if (m0 < M) gemm_tile<BM / 2, BN, WR, WC, BK, NST, KIND>(A, W, C, M, Nn, K, m0, n0, k0, k1, -1, ep, lds);
+            return;
+        }
+    }
+    gemm_tile<BM, BN, WR, WC, BK, NST, KIND>(A, W, C, M, Nn, K, m0, n0, k0, k1, piece, ep, lds);
+}
+
 // Sums the K-split pieces of the tail tiles (fixed order: deterministic) and applies the epilogue; one
 // workgroup per tail tile, same wave layout as gemm_mfma_kernel.
 template <int BM, int BN, int WR, int WC, int KIND>
@@ -501,7 +521,7 @@ bool gemm_mfma_supported(int M, int Nn, int K) {
 }
 
 // How a shape is spread over the chip: which tile variant, how many tiles run whole and how the rest is split.
-struct GemmPlan { int variant, tiles_m, tiles_n, full, nsplit, pieces; size_t ws_bytes; };
+struct GemmPlan { int variant, tiles_m, tiles_n, full, nsplit, rsplit, pieces; size_t ws_bytes; };
 static int gemm_compute_units() {
     static int cus = 0;
     if (cus == 0) {
@@ -515,7 +535,7 @@ static int gemm_compute_units() {
 static int g_gemm_variant = 0;   // tuning hook: 0 auto
 void set_gemm_variant(int v) { g_gemm_variant = v; }
 
-static GemmPlan gemm_plan(int M, int Nn, int K, bool allow_split) {
+static GemmPlan gemm_plan(int M, int Nn, int K, bool allow_split, bool allow_rows = true) {
     GemmPlan p{};
     p.variant = g_gemm_variant;
     if (p.variant == 0) {
@@ -528,12 +548,18 @@ static GemmPlan gemm_plan(int M, int Nn, int K, bool allow_split) {
     p.tiles_m = (M + bm - 1) / bm;
     p.tiles_n = (Nn + bn - 1) / bn;
     const int tiles = p.tiles_m * p.tiles_n;
-    p.full = tiles; p.nsplit = 1; p.pieces = 0; p.ws_bytes = 0;
+    p.full = tiles; p.nsplit = 1; p.rsplit = 1; p.pieces = 0; p.ws_bytes = 0;
     // the last partial round: split along K if the partial sums (two passes over tile-size fp32 per piece) and
     // the second launch cost less than the round they save -- measured at 17776 tokens: true for the 128x128
     // tile with a long K (fc2: 0.62 -> 0.57 ms), not for K = 1920 (0.188 -> 0.196 ms) nor for the 256x256 tile
     const int slots = gemm_compute_units() * (big ? 1 : 2);
     const int tail = tiles % slots, nk = K / 64;
+    // the wide tile: the tiles of the last partial round are computed by two workgroups each (upper and lower
+    // half of the rows) when that fits the slots, which roughly halves the round
+    if (allow_rows && big && tail > 0 && 2 * tail <= slots && tiles > slots) {
+        p.full = tiles - tail; p.rsplit = 2; p.pieces = 2 * tail;
+        return p;
+    }
     if (allow_split && !big && K >= 4096 && tail > 0 && tiles > slots) {
         int ns = slots / tail;
         if (ns > 8) ns = 8;
@@ -556,9 +582,9 @@ static hipError_t launch_kind(const bf16_t* A, const bf16_t* W, bf16_t* C, int M
                               const Epilogue& ep, hipStream_t st) {
     dim3 block(WR * WC * 64);
     gemm_mfma_kernel<BM, BN, WR, WC, BK, NST, KIND><<<p.full + p.pieces, block, 0, st>>>(A, W, C, M, Nn, K, p.tiles_m, p.tiles_n,
-                                                                                p.full, p.nsplit, ep);
+                                                                                p.full, p.nsplit, p.rsplit, ep);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || p.pieces == 0) return e;
+    if (e != hipSuccess || p.pieces == 0 || p.rsplit != 1) return e;
     gemm_tail_kernel<BM, BN, WR, WC, KIND><<<p.pieces / p.nsplit, block, 0, st>>>(C, M, Nn, p.tiles_m, p.tiles_n, p.full,
                                                                                   p.nsplit, ep);
     return hipGetLastError();
@@ -579,8 +605,9 @@ static hipError_t launch_tile(const bf16_t* A, const bf16_t* W, bf16_t* C, int M
 
 hipError_t launch_gemm_mfma(const bf16_t* A, const bf16_t* W, bf16_t* C, int M, int Nn, int K,
                             const Epilogue& ep, hipStream_t st) {
-    GemmPlan p = gemm_plan(M, Nn, K, ep.split_ws != nullptr && (get_kernel_path() & 0xff) != 4);
-    if (p.ws_bytes > ep.split_ws_bytes) p = gemm_plan(M, Nn, K, false);
+    const bool tails = (get_kernel_path() & 0xff) != 4;
+    GemmPlan p = gemm_plan(M, Nn, K, ep.split_ws != nullptr && tails, tails);
+    if (p.ws_bytes > ep.split_ws_bytes) p = gemm_plan(M, Nn, K, false, tails);
     switch (p.variant) {
         case 1: return launch_tile<256, 256, 2, 4, 64, 2>(A, W, C, M, Nn, K, p, ep, st);   // 8 waves, 128x64 each
         case 2: return launch_tile<128, 128, 2, 2, 64, 2>(A, W, C, M, Nn, K, p, ep, st);   // 4 waves, 64x64 each, 2 per CU
