@@ -673,7 +673,9 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
 // A wave that alternates long MFMA-only and ALU-only blocks (the other kernel) leaves the matrix pipe
 // idle during its ALU blocks even with a second wave on the SIMD, because both waves drift into phase;
 // a homogeneous stream keeps both units busy.  Measured on a register-only replica: 1.77 vs 1.37-1.43
-// PFLOP/s-equivalent.  (Workgroups of 8 such waves sharing each K/V tile, one per CU, measured 2-3 % slower.)
+// PFLOP/s-equivalent.  (Workgroups of 8 such waves sharing each K/V tile, one per CU, measured 2-3 % slower.
+// The same loop on v_mfma_f32_16x16x32_bf16 -- query blocks of 16, the eight exponentials of a lane again the B
+// fragment of the second product -- measured +1.5 % at 17776 keys, -2.4 % at 33976, -2 to -7 % below 5000: dropped.)
 // Steps of iteration j (tile j = halves a, b):
 //   A: S(j,b)    | softmax(j,a)  | PV(j-1,b)
 //   B: S(j+1,a)  | softmax(j,b)  | PV(j,a)
