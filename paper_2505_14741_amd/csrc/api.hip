@@ -43,7 +43,7 @@ struct dit {
 namespace {
 
 struct WsLayout {
-    size_t X, H, QKV, mod, modf, sinus, hid, cvec, rcos, rsin, attn, gemm, gemm_bytes, total;
+    size_t X, H, QKV, mod, modf, sinus, hid, cvec, rope, attn, gemm, gemm_bytes, total;
 };
 
 WsLayout ws_layout(const dit* d, int batch) {
@@ -61,8 +61,7 @@ WsLayout ws_layout(const dit* d, int batch) {
     w.sinus = take((size_t)batch * D * 4);
     w.hid = take((size_t)batch * c.time_embed_dim * 4);
     w.cvec = take((size_t)batch * c.time_embed_dim * 4);
-    w.rcos = take((size_t)d->Nv * (c.head_dim / 2) * 4);
-    w.rsin = take((size_t)d->Nv * (c.head_dim / 2) * 4);
+    w.rope = take((size_t)d->Nv * (c.head_dim / 2) * 8);      // (cos, sin) per video token and pair
     w.attn = take(attention_workspace_bytes(c.dtype, batch, d->N, c.heads, c.head_dim));
     {   // K-split scratch of the projections: the largest need of the four shapes of a layer
         const int Mi = (int)M, Di = (int)D, Fi = (int)(c.mlp_ratio * D);
@@ -146,8 +145,7 @@ int forward_impl(dit* d, const float* x, const void* ctx, const int32_t* t_host,
     float* sinus = (float*)(base + w.sinus);
     float* hid = (float*)(base + w.hid);
     float* cvec = (float*)(base + w.cvec);
-    float* rcos = (float*)(base + w.rcos);
-    float* rsin = (float*)(base + w.rsin);
+    float* rope = (float*)(base + w.rope);
     void* attn_ws = attention_workspace_bytes(dt, batch, N, c.heads, c.head_dim) ? base + w.attn : nullptr;
     float* gemm_ws = w.gemm_bytes ? (float*)(base + w.gemm) : nullptr;
     Prof prof{d, st};
@@ -162,7 +160,7 @@ int forward_impl(dit* d, const float* x, const void* ctx, const int32_t* t_host,
         PS_TIMED(KC_OTHER, launch_gemv(dt, d->layers[l].W_mod, d->layers[l].b_mod, cvec, mod + (long)l * 12 * D,
                                        12 * D, Dt, batch, Dt, mod_bs, 0, st));
     PS_TIMED(KC_OTHER, launch_gemv(dt, d->W_fm, d->b_fm, cvec, modf, 2 * D, Dt, batch, Dt, 2 * D, 0, st));
-    PS_TIMED(KC_OTHER, launch_rope_table(rcos, rsin, c.frames, d->Hp, d->Wp, c.head_dim, c.rope_theta, st));
+    PS_TIMED(KC_OTHER, launch_rope_table(rope, c.frames, d->Hp, d->Wp, c.head_dim, c.rope_theta, st));
     PS_TIMED(KC_OTHER, launch_patch_embed(dt, x, ctx, d->W_pe, d->b_pe, X, batch, c.in_channels, c.frames,
                                           c.height, c.width, c.patch, c.text_tokens, D,
                                           ctx_shared ? 0L : (long)c.text_tokens * D, st));
@@ -186,7 +184,7 @@ int forward_impl(dit* d, const float* x, const void* ctx, const int32_t* t_host,
         // [q|k|v] = W_qkv h + b, rotary on video q,k
         Epilogue eq{};
         eq.kind = EPI_QKV_ROPE; eq.bias = lw.b_qkv; eq.D = D; eq.geom = geom;
-        eq.rope_cos = rcos; eq.rope_sin = rsin; eq.head_dim = c.head_dim;
+        eq.rope_cs = rope; eq.head_dim = c.head_dim;
         eq.q_scale = prescale ? scale * 1.4426950408889634f : 1.0f;
         eq.split_ws = gemm_ws; eq.split_ws_bytes = w.gemm_bytes;
         // the projection's epilogue leaves the per-head maxima of |q|^2 and |k|^2 the attention kernel selects on

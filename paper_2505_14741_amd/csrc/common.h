@@ -50,8 +50,7 @@ struct Epilogue {
     int D;                    // hidden
     TokenGeom geom;
     // EPI_QKV_ROPE: rotate pairs of q and k columns of video tokens
-    const float* rope_cos;    // fp32 [N_v, d/2]
-    const float* rope_sin;
+    const float* rope_cs;     // fp32 [N_v, d/2, 2]: (cos, sin) per video token and pair
     int head_dim;
     float q_scale;            // factor applied to the q columns (col < D) after the rotation
     // EPI_QKV_ROPE, bf16 MFMA kernel, head_dim 64, optional: [batch*heads][2] running maxima of the squared norms
@@ -102,7 +101,7 @@ hipError_t launch_sinusoid(const int32_t* t_host, float* out, int batch, int D, 
 hipError_t launch_gemv(int dtype, const void* W, const float* bias, const float* in, float* out,
                        int rows, int cols, int batch, long in_bstride, long out_bstride, int act,
                        hipStream_t st);
-hipError_t launch_rope_table(float* cosb, float* sinb, int F, int Hp, int Wp, int head_dim,
+hipError_t launch_rope_table(float* table, int F, int Hp, int Wp, int head_dim,
                              float theta, hipStream_t st);
 hipError_t launch_patch_embed(int dtype, const float* x, const void* ctx, const void* W_pe,
                               const float* b_pe, float* X, int batch, int C, int F, int H, int Wd,

@@ -116,9 +116,10 @@ hipError_t launch_gemv(int dtype, const void* W, const float* bias, const float*
 }
 
 // ------------------------------------------------------------------------- 3D RoPE table
-// cos/sin of pos_A * theta^(-2m/d_A) for every video token and pair; axis widths
+// (cos, sin) of pos_A * theta^(-2m/d_A) for every video token and pair, interleaved: table[token][pair] =
+// (cos, sin), so the two pairs behind four consecutive columns are one 16-byte load; axis widths
 // d/4, 3d/8, 3d/8 over (frame, row, col).  Double precision angles.
-__global__ void rope_table_kernel(float* __restrict__ cosb, float* __restrict__ sinb, int F, int Hp,
+__global__ void rope_table_kernel(float2* __restrict__ table, int F, int Hp,
                                   int Wp, int head_dim, float theta) {
     int half = head_dim / 2;
     long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -136,16 +137,15 @@ __global__ void rope_table_kernel(float* __restrict__ cosb, float* __restrict__ 
     else if (pair < p0 + p1) { pos = i; m = pair - p0; dA = 2 * p1; }
     else { pos = j; m = pair - p0 - p1; dA = 2 * p1; }
     double ang = (double)pos * exp(-2.0 * (double)m / (double)dA * log((double)theta));
-    cosb[idx] = (float)cos(ang);
-    sinb[idx] = (float)sin(ang);
+    table[idx] = make_float2((float)cos(ang), (float)sin(ang));
 }
 
-hipError_t launch_rope_table(float* cosb, float* sinb, int F, int Hp, int Wp, int head_dim,
+hipError_t launch_rope_table(float* table, int F, int Hp, int Wp, int head_dim,
                              float theta, hipStream_t st) {
     long total = (long)F * Hp * Wp * (head_dim / 2);
     if (total == 0) return hipSuccess;
-    rope_table_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(cosb, sinb, F, Hp, Wp, head_dim,
-                                                                      theta);
+    rope_table_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(reinterpret_cast<float2*>(table), F, Hp, Wp,
+                                                                      head_dim, theta);
     return hipGetLastError();
 }
 

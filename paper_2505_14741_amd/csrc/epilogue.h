@@ -30,7 +30,7 @@ __device__ __forceinline__ void epilogue_pair(const Epilogue& ep, T* __restrict_
             int nv = n - ep.geom.text_tokens;
             int pr = (col % ep.head_dim) >> 1;
             long ti = (long)nv * (ep.head_dim >> 1) + pr;
-            float cs = ep.rope_cos[ti], sn = ep.rope_sin[ti];
+            float cs = ep.rope_cs[2 * ti], sn = ep.rope_cs[2 * ti + 1];
             float r0 = v0 * cs - v1 * sn;
             float r1 = v0 * sn + v1 * cs;
             v0 = r0;

@@ -110,7 +110,7 @@ __device__ __forceinline__ void wave_epilogue(f32x4_t (&acc)[TM][TN][4], const E
     }
 
     // operands the strip needs from memory besides the accumulators (one 16-byte value per
-    // 4 outputs): the residual, or (cos, cos, sin, sin) of the two pairs
+    // 4 outputs): the residual, or (cos, sin, cos, sin) of the two pairs
     auto fetch = [&](int i, int k) -> f32x4_t {
         int m = wrow0 + i * 32 + 4 * k + rr;
         if (CHECK) m = m < M ? m : M - 1;
@@ -119,13 +119,9 @@ __device__ __forceinline__ void wave_epilogue(f32x4_t (&acc)[TM][TN][4], const E
         } else if constexpr (KIND == EPI_QKV_ROPE) {
             int b;
             const int n = token_of(m, b);
-            f32x4_t r = {1.f, 1.f, 0.f, 0.f};
-            if (rot && n >= text) {
-                const unsigned ti = (unsigned)((n - text) * (ep.head_dim >> 1) + pr);
-                const f32x2_t cs = *reinterpret_cast<const f32x2_t*>(ep.rope_cos + ti);
-                const f32x2_t sn = *reinterpret_cast<const f32x2_t*>(ep.rope_sin + ti);
-                r = {cs[0], cs[1], sn[0], sn[1]};
-            }
+            f32x4_t r = {1.f, 0.f, 1.f, 0.f};
+            if (rot && n >= text)                        // (cos, sin) of the lane's two pairs: one 16-byte load
+                r = *reinterpret_cast<const f32x4_t*>(ep.rope_cs + 2 * (unsigned)((n - text) * (ep.head_dim >> 1) + pr));
             return r;
         } else {
             return f32x4_t{0.f, 0.f, 0.f, 0.f};
@@ -169,9 +165,9 @@ __device__ __forceinline__ void wave_epilogue(f32x4_t (&acc)[TM][TN][4], const E
                 for (int c = 0; c < 4; ++c) x[c] = gelu_fast(x[c]);
             }
             if constexpr (KIND == EPI_QKV_ROPE) {
-                // t = (cos0, cos1, sin0, sin1); identity for text tokens and v columns
-                x = f32x4_t{x[0] * t[0] - x[1] * t[2], x[1] * t[0] + x[0] * t[2],
-                            x[2] * t[1] - x[3] * t[3], x[3] * t[1] + x[2] * t[3]} * qs;
+                // t = (cos0, sin0, cos1, sin1); identity for text tokens and v columns
+                x = f32x4_t{x[0] * t[0] - x[1] * t[1], x[1] * t[0] + x[0] * t[1],
+                            x[2] * t[2] - x[3] * t[3], x[3] * t[2] + x[2] * t[3]} * qs;
                 if (track_norms) {
                     // this lane's 4 columns of the row (the values are stored as bf16, which moves a norm by at
                     // most 2^-8 relative: covered by a factor on the final maximum).  Per-lane maxima over the
@@ -313,14 +309,15 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, const bf
         }
     }
     const unsigned lds_base = (unsigned)(size_t)PS_LDS_PTR(lds);
-    auto issue = [&](int kt) {                           // kt counts from k0; ring slot kt % NST
+    auto issue_one = [&](int kt, int i) {                // kt counts from k0; ring slot kt % NST; load group i of the wave
         const int kc = k0 + kt < k1 ? k0 + kt : k1 - 1;  // past the end: harmless re-read keeps vmcnt uniform
         const unsigned st = lds_base + (kt % NST) * STAGE;
+        const int g = wave + NW * i;
+        lds_dma16(gp[i] + (long)kc * BK, __builtin_amdgcn_readfirstlane(st + g * 1024));
+    };
+    auto issue = [&](int kt) {
 #pragma unroll
-        for (int i = 0; i < GPW; ++i) {
-            const int g = wave + NW * i;
-            lds_dma16(gp[i] + (long)kc * BK, __builtin_amdgcn_readfirstlane(st + g * 1024));
-        }
+        for (int i = 0; i < GPW; ++i) issue_one(kt, i);
     };
 
     // Accumulators: every 32 x 32 block of the wave's outputs is four 16 x 16 products (q = 2 * row half + column
@@ -370,28 +367,55 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, const bf
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
             const unsigned char* src = st;               // where the next step's fragments come from
+            // Direct loads into the slot the barrier frees: one workgroup per CU (8 waves) spreads them over the
+            // fragment rounds of the stage's last step (in one block after the barrier they held this wave's MFMAs
+            // back for ~30 instructions: QKV / fc1 shapes 6 % faster spread out); with two co-resident workgroups
+            // of 4 waves the block form measured 2-3 % faster, the other workgroup covers it.
+            constexpr bool SPREAD = NW >= 8;
             if (ks == 1) {
                 wait_vmcnt<(NST - 2) * GPW>();           // own share of stage kt+1 has landed
                 __syncthreads();                         // ... everyone's; and nobody reads stage kt any more
-                issue(kt + NST);                         // into the slot stage kt occupied
+                if constexpr (!SPREAD) issue(kt + NST);  // into the slot stage kt occupied
                 src = nx;
                 __builtin_amdgcn_sched_barrier(0);       // hand-over code stays ahead of the MFMAs
             }
             const int slot = slot_of(ks ^ 1);
+            if constexpr (!SPREAD) {
+#pragma unroll
+                for (int x = 0; x < FA; ++x) {
+                    if (x < FB) fb[ks ^ 1][x] = *reinterpret_cast<const bf16x8_t*>(src + boff[x] + slot);
+#pragma unroll
+                    for (int y = 0; y < FB; ++y)
+                        acc[x >> 1][y >> 1][(x & 1) * 2 + (y & 1)] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                            fa[x], fb[ks][y], acc[x >> 1][y >> 1][(x & 1) * 2 + (y & 1)], 0, 0, 0);
+                    fa[x] = *reinterpret_cast<const bf16x8_t*>(src + aoff[x] + slot);
+                }
+#pragma unroll
+                for (int x = 0; x < FA; ++x) {           // FB MFMAs, then the LDS reads of the round
+                    __builtin_amdgcn_sched_group_barrier(0x008, FB, 0);
+                    if (x < FB) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                    else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                continue;
+            }
+            // One fragment round = the FB MFMAs of A fragment x, the LDS reads that refill it (and, in the first
+            // rounds, one W fragment of the next step), and in the stage's last step a share of the direct loads.
+            constexpr int DPR = (GPW + FA - 1) / FA;     // direct loads per round
 #pragma unroll
             for (int x = 0; x < FA; ++x) {
-                if (x < FB) fb[ks ^ 1][x] = *reinterpret_cast<const bf16x8_t*>(src + boff[x] + slot);
 #pragma unroll
                 for (int y = 0; y < FB; ++y)
                     acc[x >> 1][y >> 1][(x & 1) * 2 + (y & 1)] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
                         fa[x], fb[ks][y], acc[x >> 1][y >> 1][(x & 1) * 2 + (y & 1)], 0, 0, 0);
+                if (x < FB) fb[ks ^ 1][x] = *reinterpret_cast<const bf16x8_t*>(src + boff[x] + slot);
                 fa[x] = *reinterpret_cast<const bf16x8_t*>(src + aoff[x] + slot);
-            }
+                if (ks == 1) {
 #pragma unroll
-            for (int x = 0; x < FA; ++x) {
-                __builtin_amdgcn_sched_group_barrier(0x008, FB, 0);
-                if (x < FB) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-                else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    for (int d = 0; d < DPR; ++d)
+                        if (x * DPR + d < GPW) issue_one(kt + NST, x * DPR + d);
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -460,7 +484,7 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
         m0 = (band * GM + in_band % rows_here) * BM;
         n0 = (in_band / rows_here) * BN;
     }
-    if constexpr (BM == 256 && WR == 2) {
+    if constexpr (BM == 256 && WR == 2 && WC == 4) {
         if (rsplit == 2 && (int)blockIdx.x >= full_tiles) {       // uniform over the workgroup
             m0 += part * (BM / 2);
             if (m0 < M) gemm_tile<BM / 2, BN, WR, WC, BK, NST, KIND>(A, W, C, M, Nn, K, m0, n0, k0, k1, -1, ep, lds);
@@ -556,7 +580,7 @@ static GemmPlan gemm_plan(int M, int Nn, int K, bool allow_split, bool allow_row
     const int tail = tiles % slots, nk = K / 64;
     // the wide tile: the tiles of the last partial round are computed by two workgroups each (upper and lower
     // half of the rows) when that fits the slots, which roughly halves the round
-    if (allow_rows && big && tail > 0 && 2 * tail <= slots && tiles > slots) {
+    if (allow_rows && p.variant == 1 && tail > 0 && 2 * tail <= slots && tiles > slots) {
         p.full = tiles - tail; p.rsplit = 2; p.pieces = 2 * tail;
         return p;
     }
@@ -614,7 +638,10 @@ hipError_t launch_gemm_mfma(const bf16_t* A, const bf16_t* W, bf16_t* C, int M, 
         // Measured and dropped: 4 waves of 128x128 outputs on the 256x256 tile (fewer LDS reads per MFMA; with the
         // 32x32x16 MFMA one wave per SIMD issued one only every ~48 cycles: 5-15 % slower; with 16x16x32 the 256
         // accumulator registers per lane make the compiler shuttle values between the two register files, 3-4
-        // copies per MFMA: 30 % slower); 32-deep stages in rings of 3 or 4
+        // copies per MFMA: 30 % slower; with the MFMAs written as inline asm on accumulator-file operands the
+        // copies go, and the variant is the fastest at 8192 x 8192 weights, 1.28 PFLOP/s, but 5-10 % slower than
+        // the 8-wave tile at this model's shapes: one wave per SIMD has nobody to cover its barrier waits);
+        // 32-deep stages in rings of 3 or 4
         // (5-25 % slower: twice the barriers).  With the loads of the loop taken out (timing probe) both tiles
         // reach 1.3-1.4 PFLOP/s, with every tile loading the same L2-resident panels only 4-10 % more than now:
         // the global->LDS path itself, not the memory behind L2, is what the loop waits for (a stand-alone stream
