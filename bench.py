@@ -152,16 +152,20 @@ def main():
     if Wm > 0:
         run(Wm, False)
     torch.cuda.synchronize()
+    # timed region: HIP events around the attention calls only (the roofline kernel); events around every launch
+    # cost about 1.5 % of a step, so the per-class breakdown comes from a second, untimed pass of the same steps
     t0 = time.perf_counter()
-    x0, sums, calls = run(K, True)
+    x0, sums, calls = run(K, 2)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    prof = B.dit_profile_read(d)
-    B.dit_profile_enable(d, False)
+    att_ms, att_n = B.dit_profile_read(d)["attention"]
     assert calls == K and bool(torch.isfinite(x0).all())
     ms_step = wall * 1e3 / K
+    run(K, 1)
+    torch.cuda.synchronize()
+    prof = B.dit_profile_read(d)
+    B.dit_profile_enable(d, False)
 
-    att_ms, att_n = prof["attention"]
     att_avg = att_ms / max(att_n, 1)
     att_tflops = 4.0 * N * N * D / (att_avg * 1e-3) / 1e12
     gemm = {}
@@ -205,6 +209,7 @@ def main():
         "gemm": {"tflops": round(gemm_tflops, 1), "frac": round(gemm_tflops / PEAK_BF16_TFLOPS, 4),
                  "per_kernel": {k: {kk: round(vv, 4) for kk, vv in v.items()} for k, v in gemm.items()}},
         "kernel_ms_per_step": {k: round(v[0] / K, 3) for k, v in prof.items()},
+        "kernel_ms_per_step_source": "second, untimed pass of the same steps with HIP events around every launch",
         "sampler_step_stress": {"n": n_big, "ms": round(ss_ms, 4), "achieved": round(ss_gbs, 1), "peak": PEAK_HBM_GBS,
                                 "unit": "GB/s", "frac": round(ss_gbs / PEAK_HBM_GBS, 4), "bound": "hbm"},
         "paper_context": "paper reports end-to-end speedups 3.88x SVD, 2.43x CogVideoX-2b, 6.56x AudioLDM2-large "

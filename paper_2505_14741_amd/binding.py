@@ -176,7 +176,8 @@ def dit_forward(d: Dit, x: torch.Tensor, ctx: Optional[torch.Tensor], t: Sequenc
     return eps_out
 
 
-def dit_profile_enable(d: Dit, on: bool):
+def dit_profile_enable(d: Dit, on):
+    """on: False/0 off, True/1 every kernel class, 2 the attention class only."""
     _check(lib().dit_profile_enable(d.handle, int(on)), "dit_profile_enable")
 
 

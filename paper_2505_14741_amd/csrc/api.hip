@@ -32,7 +32,7 @@ struct dit {
     int Hp, Wp, Nv, N, P;
     size_t esize;
     // profiling
-    bool profiling = false;
+    int profiling = 0;              // 0 off, 1 every class, 2 the attention class only
     std::vector<hipEvent_t> ev;           // pairs: start, stop
     std::vector<int> ev_class;
     size_t ev_used = 0;
@@ -81,7 +81,7 @@ struct Prof {
     hipStream_t st;
     hipError_t begin(int cls, hipEvent_t* stop) {
         *stop = nullptr;
-        if (!d->profiling) return hipSuccess;
+        if (!d->profiling || (d->profiling == 2 && cls != KC_ATTN)) return hipSuccess;
         if (d->ev_used + 2 > d->ev.size()) {
             hipEvent_t a, b;
             hipError_t e = hipEventCreate(&a);
@@ -326,7 +326,8 @@ int dit_forward(dit* d, const float* x, const void* ctx, const int32_t* t_host, 
 
 int dit_profile_enable(dit* d, int on) {
     if (!d) return PS_ERR_NULL;
-    d->profiling = on != 0;
+    if (on < 0 || on > 2) return PS_ERR_SHAPE;
+    d->profiling = on;
     if (on) {
         d->ev_used = 0;
         for (int k = 0; k < N_CLASSES; ++k) { d->prof_ms[k] = 0; d->prof_n[k] = 0; }

@@ -201,6 +201,9 @@ def test_schedule_validation():
     cfg = I.CONFIGS["tiny"]
     rc, h = _create(_cfg_struct(cfg))
     ok = _sched()
+    # event timing modes: off, every class, attention only
+    assert [L.dit_profile_enable(h, m) for m in (1, 2, 0, 3, -1)] == [0, 0, 0, -2, -2]
+    assert L.dit_profile_enable(None, 1) == -1
     assert L.sampler_workspace_bytes(h, C.byref(ok.c)) > 0
     assert L.sampler_workspace_bytes(h, C.byref(_sched(batched=1).c)) > L.sampler_workspace_bytes(h, C.byref(ok.c))
     assert L.sampler_workspace_bytes(h, C.byref(_sched(mode=2).c)) == L.sampler_workspace_bytes(h, C.byref(ok.c))
