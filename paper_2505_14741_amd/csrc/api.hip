@@ -156,9 +156,15 @@ int forward_impl(dit* d, const float* x, const void* ctx, const int32_t* t_host,
     PS_TIMED(KC_OTHER, launch_sinusoid(t_host, sinus, batch, D, st));
     PS_TIMED(KC_OTHER, launch_gemv(dt, d->W_t1, d->b_t1, sinus, hid, Dt, D, batch, D, Dt, 1, st));
     PS_TIMED(KC_OTHER, launch_gemv(dt, d->W_t2, d->b_t2, hid, cvec, Dt, Dt, batch, Dt, Dt, 1, st));
-    for (int l = 0; l < L; ++l)
-        PS_TIMED(KC_OTHER, launch_gemv(dt, d->layers[l].W_mod, d->layers[l].b_mod, cvec, mod + (long)l * 12 * D,
-                                       12 * D, Dt, batch, Dt, mod_bs, 0, st));
+    for (int l0 = 0; l0 < L; l0 += GEMV_SET) {           // the layers' modulation matrices, 32 per launch
+        GemvSet set{};
+        const int cnt = L - l0 < GEMV_SET ? L - l0 : GEMV_SET;
+        for (int i = 0; i < cnt; ++i) {
+            set.W[i] = d->layers[l0 + i].W_mod; set.bias[i] = d->layers[l0 + i].b_mod;
+            set.out[i] = mod + (long)(l0 + i) * 12 * D;
+        }
+        PS_TIMED(KC_OTHER, launch_gemv_set(dt, set, cnt, cvec, 12 * D, Dt, batch, Dt, mod_bs, 0, st));
+    }
     PS_TIMED(KC_OTHER, launch_gemv(dt, d->W_fm, d->b_fm, cvec, modf, 2 * D, Dt, batch, Dt, 2 * D, 0, st));
     PS_TIMED(KC_OTHER, launch_rope_table(rope, c.frames, d->Hp, d->Wp, c.head_dim, c.rope_theta, st));
     PS_TIMED(KC_OTHER, launch_patch_embed(dt, x, ctx, d->W_pe, d->b_pe, X, batch, c.in_channels, c.frames,

@@ -98,6 +98,11 @@ int get_kernel_path();
 
 hipError_t launch_sinusoid(const int32_t* t_host, float* out, int batch, int D, hipStream_t st);
 // out[b, r] = act(W[r,:] . in[b,:] + bias[r]);  act: 0 none, 1 SiLU.  W in dtype, in/out fp32.
+// up to GEMV_SET matrices of one shape applied to one input in a single launch
+constexpr int GEMV_SET = 32;
+struct GemvSet { const void* W[GEMV_SET]; const float* bias[GEMV_SET]; float* out[GEMV_SET]; };
+hipError_t launch_gemv_set(int dtype, const GemvSet& set, int count, const float* in, int rows, int cols, int batch,
+                           long in_bs, long out_bs, int act, hipStream_t st);
 hipError_t launch_gemv(int dtype, const void* W, const float* bias, const float* in, float* out,
                        int rows, int cols, int batch, long in_bstride, long out_bstride, int act,
                        hipStream_t st);

@@ -44,13 +44,17 @@ hipError_t launch_sinusoid(const int32_t* t_host, float* out, int batch, int D, 
 
 // One wave per output row; weights stream once from HBM (16 bytes per lane and load when the row length
 // allows), inputs stay in cache.
+// blockIdx.y picks one of up to GEMV_SET matrices of the same shape applied to the same input (the modulation
+// matrices of all layers in one launch).
 template <typename T, int MAXB>
-__global__ void gemv_kernel(const T* __restrict__ W, const float* __restrict__ bias,
-                            const float* __restrict__ in, float* __restrict__ out, int rows,
+__global__ void gemv_kernel(GemvSet set, const float* __restrict__ in, int rows,
                             int cols, int batch, long in_bs, long out_bs, int act) {
     int wave = (blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
     int lane = threadIdx.x % WAVE;
     if (wave >= rows) return;
+    const T* __restrict__ W = static_cast<const T*>(set.W[blockIdx.y]);
+    const float* __restrict__ bias = set.bias[blockIdx.y];
+    float* __restrict__ out = set.out[blockIdx.y];
     const T* w = W + (long)wave * cols;
     float acc[MAXB];
 #pragma unroll
@@ -101,18 +105,24 @@ __global__ void gemv_kernel(const T* __restrict__ W, const float* __restrict__ b
     }
 }
 
+hipError_t launch_gemv_set(int dtype, const GemvSet& set, int count, const float* in, int rows, int cols, int batch,
+                           long in_bs, long out_bs, int act, hipStream_t st) {
+    if (count < 1 || count > GEMV_SET) return hipErrorInvalidValue;
+    int threads = 256;
+    dim3 blocks((rows + (threads / WAVE) - 1) / (threads / WAVE), count);
+    if (dtype == PS_BF16)
+        gemv_kernel<bf16_t, 16><<<blocks, threads, 0, st>>>(set, in, rows, cols, batch, in_bs, out_bs, act);
+    else
+        gemv_kernel<float, 16><<<blocks, threads, 0, st>>>(set, in, rows, cols, batch, in_bs, out_bs, act);
+    return hipGetLastError();
+}
+
 hipError_t launch_gemv(int dtype, const void* W, const float* bias, const float* in, float* out,
                        int rows, int cols, int batch, long in_bs, long out_bs, int act,
                        hipStream_t st) {
-    int threads = 256;
-    int blocks = (rows + (threads / WAVE) - 1) / (threads / WAVE);
-    if (dtype == PS_BF16)
-        gemv_kernel<bf16_t, 16><<<blocks, threads, 0, st>>>((const bf16_t*)W, bias, in, out, rows,
-                                                             cols, batch, in_bs, out_bs, act);
-    else
-        gemv_kernel<float, 16><<<blocks, threads, 0, st>>>((const float*)W, bias, in, out, rows,
-                                                            cols, batch, in_bs, out_bs, act);
-    return hipGetLastError();
+    GemvSet set{};
+    set.W[0] = W; set.bias[0] = bias; set.out[0] = out;
+    return launch_gemv_set(dtype, set, 1, in, rows, cols, batch, in_bs, out_bs, act, st);
 }
 
 // ------------------------------------------------------------------------- 3D RoPE table
