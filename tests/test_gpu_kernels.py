@@ -83,6 +83,34 @@ def test_sampler_step_is_deterministic_and_exact_in_fp32():
     assert np.abs(r1[0].cpu().numpy() - ref).max() <= 2.5e-7 * np.abs(ref).max()
 
 
+def test_sampler_step_and_rel_mae_above_the_grid_cap():
+    """More 16 KB chunks than the 32768 workgroups of the grid: workgroups walk several chunks, the last one is
+    partial and 5 elements do not fill a vector.  Sampled outputs and all sums against the oracle."""
+    n = 3 * (1 << 26) + 5
+    print(f"sampler_step n={n}", flush=True)
+    g = torch.Generator(device="cuda"); g.manual_seed(7)
+    x, e, p = (torch.randn(n, generator=g, device="cuda") for _ in range(3))
+    a, b = np.float32(0.9931), np.float32(0.0517)
+    xo, sums = B.sampler_step(x, e, p, a, b)
+    torch.cuda.synchronize()
+    xh, eh, ph = host(x), host(e), host(p)
+    idx = np.unique(np.concatenate([[0, 1, 4095, 4096, n - 6, n - 5, n - 1],
+                                    np.random.default_rng(3).integers(0, n, 4096)]))
+    ref = O.sampler_step(xh[idx], eh[idx], a, b)
+    assert_close_fp32(host(xo[torch.from_numpy(idx).to(DEV)]), ref, 1e-6)
+    step = 1 << 24                                   # sums in pieces: fp64 copies of 2e8 values are large
+    want = np.zeros(4)
+    for i in range(0, n, step):
+        xs, es, ps = (v[i:i + step].astype(np.float64) for v in (xh, eh, ph))
+        r = O.sampler_step(xs, es, a, b)
+        want += [np.abs(r - xs).sum(), np.abs(r).sum(), np.abs(es - ps).sum(), np.abs(es).sum()]
+    np.testing.assert_allclose(host(sums), want, rtol=2e-5)
+    out = host(B.rel_mae(x, e))
+    num = sum(np.abs(xh[i:i + step].astype(np.float64) - eh[i:i + step]).sum() for i in range(0, n, step))
+    den = sum(np.abs(xh[i:i + step].astype(np.float64)).sum() for i in range(0, n, step))
+    np.testing.assert_allclose(out, [num, den, num / den], rtol=2e-5)
+
+
 @pytest.mark.parametrize("n", [1, 4, 6, 1023, 65537, 1123200])
 def test_rel_mae_matches_oracle(n):
     print(f"rel_mae n={n}", flush=True)
