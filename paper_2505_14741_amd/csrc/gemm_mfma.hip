@@ -66,9 +66,20 @@ constexpr int EPI_LDS_FLOATS = 32 * EPI_LDS_STRIDE;
 // area (EPI_LDS_FLOATS floats).
 // Offsets are 32-bit element indices from the uniform base pointers (the launcher
 // guarantees M*Nn < 2^31); Nn % 4 == 0, so a lane's 4 columns are inside or outside together.
-template <int TM, int TN, int J0, int KIND, bool CHECK>
+// The residual values (fp32, 4 consecutive columns) behind output (strip i, row group k) of a wave: rows and
+// columns past the edge are clamped (their results are not stored).
+__device__ __forceinline__ f32x4_t resid_fetch(const Epilogue& ep, int M, int Nn, int wrow0, int wcol0, int lane, int i, int k) {
+    const int rr = lane >> 4, col = wcol0 + (lane & 15) * 4;
+    int m = wrow0 + i * 32 + 4 * k + rr;
+    m = m < M ? m : M - 1;
+    return *reinterpret_cast<const f32x4_t*>(ep.resid + (unsigned)(m * Nn + (col < Nn ? col : 0)));
+}
+
+// PRE: `pre` holds the residual values of all TM strips, fetched ahead by the caller, if use_pre (gated residual kind).
+template <int TM, int TN, int J0, int KIND, bool CHECK, bool PRE = false, int PN = 1>
 __device__ __forceinline__ void wave_epilogue(f32x4_t (&acc)[TM][TN][4], const Epilogue& ep, bf16_t* __restrict__ C,
-                                              int M, int Nn, int wrow0, int wcol0, int lane, float* patch) {
+                                              int M, int Nn, int wrow0, int wcol0, int lane, float* patch,
+                                              const f32x4_t (*pre)[8] = nullptr, bool use_pre = false) {
     const int fcol = lane & 15, fgrp = lane >> 4;        // accumulator side: column within 16, row offset 4*fgrp
     const int rr = lane >> 4, cc = (lane & 15) * 4;      // row-contiguous side: row within 4, first column
     const int col = wcol0 + cc;
@@ -131,8 +142,10 @@ __device__ __forceinline__ void wave_epilogue(f32x4_t (&acc)[TM][TN][4], const E
 
     f32x4_t pf[8];                                       // refilled for the next strip as soon as a value is used
     if constexpr (FETCHES) {
+        if (!(PRE && use_pre)) {
 #pragma unroll
-        for (int k = 0; k < 8; ++k) pf[k] = fetch(0, k);
+            for (int k = 0; k < 8; ++k) pf[k] = fetch(0, k);
+        }
     }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
@@ -157,8 +170,12 @@ __device__ __forceinline__ void wave_epilogue(f32x4_t (&acc)[TM][TN][4], const E
             f32x4_t x = v[k] + bias;
             f32x4_t t = {0.f, 0.f, 0.f, 0.f};
             if constexpr (FETCHES) {
-                t = pf[k];
-                if (i + 1 < TM) pf[k] = fetch(i + 1, k);
+                if (PRE && use_pre) {
+                    t = pre[i][k];
+                } else {
+                    t = pf[k];
+                    if (i + 1 < TM) pf[k] = fetch(i + 1, k);
+                }
             }
             if constexpr (KIND == EPI_BIAS_GELU) {
 #pragma unroll
@@ -310,7 +327,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, const bf
     }
     const unsigned lds_base = (unsigned)(size_t)PS_LDS_PTR(lds);
     auto issue_one = [&](int kt, int i) {                // kt counts from k0; ring slot kt % NST; load group i of the wave
-        const int kc = k0 + kt < k1 ? k0 + kt : k1 - 1;  // past the end: harmless re-read keeps vmcnt uniform
+        const int kc = k0 + kt < k1 ? k0 + kt : k1 - 1;  // (the prologue of a one-stage piece may ask past the end)
         const unsigned st = lds_base + (kt % NST) * STAGE;
         const int g = wave + NW * i;
         lds_dma16(gp[i] + (long)kc * BK, __builtin_amdgcn_readfirstlane(st + g * 1024));
@@ -354,6 +371,19 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, const bf
     wait_vmcnt<(NST - 2) * GPW>();                       // own share of stage 0
     __syncthreads();
     issue(NST - 1);
+    // Gated residual update on the narrow tile: the residual values of the wave's outputs are requested ahead of
+    // the epilogue and sit in registers through the last stages (this tile has registers to spare).  Fetched in the
+    // epilogue one strip ahead, their latency was exposed strip by strip: 32 us of the out-projection's 178, 45 us
+    // of fc2's 545 at 17776 tokens (measured by leaving the loads out).  Loads return in order, so a wait for a
+    // stage's direct loads also waits for every older load: strip 0 is requested right after the last stage's
+    // direct loads (third-last iteration), strip 1 after the second-last hand-over, which waits with the 8 loads
+    // of strip 0 still allowed in flight; no wait follows until the epilogue.  (Recovers 8 and 15 us.  One request
+    // per stage over 16 stages, each allowed to stay out for one hand-over, was 20 us SLOWER: under load a request
+    // needs more than a stage to return and then every one of those hand-overs stalls.)
+    constexpr bool PRE = KIND == EPI_GATE_RESIDUAL && TN == 2 && TM == 2 && NW == 4;
+    f32x4_t pre[PRE ? TM : 1][8];
+    const int nkt = k1 - k0;
+    const bool have_pre = PRE && piece < 0 && nkt >= 3;
     {
         const int slot = slot_of(0);
 #pragma unroll
@@ -361,9 +391,12 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, const bf
 #pragma unroll
         for (int y = 0; y < FB; ++y) fb[0][y] = *reinterpret_cast<const bf16x8_t*>(lds + boff[y] + slot);
     }
-    for (int kt = 0; kt < k1 - k0; ++kt) {
+    for (int kt = 0; kt < nkt; ++kt) {
         const unsigned char* st = lds + (kt % NST) * STAGE;
         const unsigned char* nx = lds + ((kt + 1) % NST) * STAGE;
+        // no stage follows the last one: no hand-over there, and no loads for stages past the end (the fragment
+        // reads of the last step then fetch stale, unused data from the other slot)
+        const bool more = kt + 1 < nkt, fill = kt + NST < nkt;
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
             const unsigned char* src = st;               // where the next step's fragments come from
@@ -373,9 +406,22 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, const bf
             // of 4 waves the block form measured 2-3 % faster, the other workgroup covers it.
             constexpr bool SPREAD = NW >= 8;
             if (ks == 1) {
-                wait_vmcnt<(NST - 2) * GPW>();           // own share of stage kt+1 has landed
-                __syncthreads();                         // ... everyone's; and nobody reads stage kt any more
-                if constexpr (!SPREAD) issue(kt + NST);  // into the slot stage kt occupied
+                if (more) {
+                    if (PRE && have_pre && kt == nkt - 2) wait_vmcnt<(NST - 2) * GPW + 8>();   // strip 0's loads may stay out
+                    else wait_vmcnt<(NST - 2) * GPW>();  // own share of stage kt+1 has landed
+                    __syncthreads();                     // ... everyone's; and nobody reads stage kt any more
+                }
+                if constexpr (!SPREAD) { if (fill) issue(kt + NST); }   // into the slot stage kt occupied
+                if constexpr (PRE) {
+                    if (have_pre && kt >= nkt - 3 && kt <= nkt - 2) {
+                        const bool first = kt == nkt - 3;
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) {
+                            const f32x4_t v = resid_fetch(ep, M, Nn, m0 + wm * WM, n0 + wn * WN, lane, first ? 0 : 1, k);
+                            if (first) pre[0][k] = v; else pre[1][k] = v;
+                        }
+                    }
+                }
                 src = nx;
                 __builtin_amdgcn_sched_barrier(0);       // hand-over code stays ahead of the MFMAs
             }
@@ -410,7 +456,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, const bf
                         fa[x], fb[ks][y], acc[x >> 1][y >> 1][(x & 1) * 2 + (y & 1)], 0, 0, 0);
                 if (x < FB) fb[ks ^ 1][x] = *reinterpret_cast<const bf16x8_t*>(src + boff[x] + slot);
                 fa[x] = *reinterpret_cast<const bf16x8_t*>(src + aoff[x] + slot);
-                if (ks == 1) {
+                if (ks == 1 && fill) {
 #pragma unroll
                     for (int d = 0; d < DPR; ++d)
                         if (x * DPR + d < GPW) issue_one(kt + NST, x * DPR + d);
@@ -437,7 +483,10 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, const bf
     }
     float* patch = reinterpret_cast<float*>(lds) + wave * EPI_LDS_FLOATS;
     const bool interior = (m0 + BM <= M) && (n0 + BN <= Nn);
-    if (interior) {
+    if constexpr (PRE) {
+        if (interior) wave_epilogue<TM, TN, 0, KIND, false, true>(acc, ep, C, M, Nn, m0 + wm * WM, n0 + wn * WN, lane, patch, pre, have_pre);
+        else wave_epilogue<TM, TN, 0, KIND, true, true>(acc, ep, C, M, Nn, m0 + wm * WM, n0 + wn * WN, lane, patch, pre, have_pre);
+    } else if (interior) {
         wave_epilogue<TM, TN, 0, KIND, false>(acc, ep, C, M, Nn, m0 + wm * WM, n0 + wn * WN, lane, patch);
         if constexpr (TN == 4)
             wave_epilogue<TM, TN, 2, KIND, false>(acc, ep, C, M, Nn, m0 + wm * WM, n0 + wn * WN + 64, lane, patch);
