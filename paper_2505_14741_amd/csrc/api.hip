@@ -61,7 +61,7 @@ WsLayout ws_layout(const dit* d, int batch) {
     w.sinus = take((size_t)batch * D * 4);
     w.hid = take((size_t)batch * c.time_embed_dim * 4);
     w.cvec = take((size_t)batch * c.time_embed_dim * 4);
-    w.rope = take((size_t)d->Nv * (c.head_dim / 2) * 8);      // (cos, sin) per video token and pair
+    w.rope = take(rope_table_floats(c.frames, d->Hp, d->Wp, c.head_dim) * 4);   // (cos, sin) per axis position and pair
     w.attn = take(attention_workspace_bytes(c.dtype, batch, d->N, c.heads, c.head_dim));
     {   // K-split scratch of the projections: the largest need of the four shapes of a layer
         const int Mi = (int)M, Di = (int)D, Fi = (int)(c.mlp_ratio * D);
@@ -190,7 +190,7 @@ int forward_impl(dit* d, const float* x, const void* ctx, const int32_t* t_host,
         // [q|k|v] = W_qkv h + b, rotary on video q,k
         Epilogue eq{};
         eq.kind = EPI_QKV_ROPE; eq.bias = lw.b_qkv; eq.D = D; eq.geom = geom;
-        eq.rope_cs = rope; eq.head_dim = c.head_dim;
+        eq.rope_cs = rope; eq.head_dim = c.head_dim; eq.rope_F = c.frames; eq.rope_Hp = d->Hp; eq.rope_Wp = d->Wp;
         eq.q_scale = prescale ? scale * 1.4426950408889634f : 1.0f;
         eq.split_ws = gemm_ws; eq.split_ws_bytes = w.gemm_bytes;
         // the projection's epilogue leaves the per-head maxima of |q|^2 and |k|^2 the attention kernel selects on

@@ -50,7 +50,10 @@ struct Epilogue {
     int D;                    // hidden
     TokenGeom geom;
     // EPI_QKV_ROPE: rotate pairs of q and k columns of video tokens
-    const float* rope_cs;     // fp32 [N_v, d/2, 2]: (cos, sin) per video token and pair
+    // rotary table, factored by axis: (cos, sin) float pairs, first [F][d/8] for the frame axis, then [Hp][3d/16]
+    // for the patch row, then [Wp][3d/16] for the patch column (video token nv = (f * Hp + i) * Wp + j)
+    const float* rope_cs;
+    int rope_F, rope_Hp, rope_Wp;
     int head_dim;
     float q_scale;            // factor applied to the q columns (col < D) after the rotation
     // EPI_QKV_ROPE, bf16 MFMA kernel, head_dim 64, optional: [batch*heads][2] running maxima of the squared norms
@@ -103,9 +106,22 @@ constexpr int GEMV_SET = 32;
 struct GemvSet { const void* W[GEMV_SET]; const float* bias[GEMV_SET]; float* out[GEMV_SET]; };
 hipError_t launch_gemv_set(int dtype, const GemvSet& set, int count, const float* in, int rows, int cols, int batch,
                            long in_bs, long out_bs, int act, hipStream_t st);
+// Rotary (cos, sin) of pair `pair` (0 .. d/2-1) for video token nv: which axis the pair belongs to, its index on
+// that axis and the token's position on it.  Pairs 0 .. d/8-1 rotate with the frame, the next 3d/16 with the patch
+// row, the last 3d/16 with the patch column.
+struct RopeAxis { int base, stride, axis; };      // float offset of (position 0, this pair), floats per position
+__host__ __device__ inline RopeAxis rope_axis_of(int pair, int head_dim, int F, int Hp) {
+    const int p0 = head_dim / 8, p1 = 3 * head_dim / 16;
+    RopeAxis r;
+    if (pair < p0) { r.axis = 0; r.base = 2 * pair; r.stride = 2 * p0; }
+    else if (pair < p0 + p1) { r.axis = 1; r.base = 2 * (F * p0 + (pair - p0)); r.stride = 2 * p1; }
+    else { r.axis = 2; r.base = 2 * (F * p0 + Hp * p1 + (pair - p0 - p1)); r.stride = 2 * p1; }
+    return r;
+}
 hipError_t launch_gemv(int dtype, const void* W, const float* bias, const float* in, float* out,
                        int rows, int cols, int batch, long in_bstride, long out_bstride, int act,
                        hipStream_t st);
+size_t rope_table_floats(int F, int Hp, int Wp, int head_dim);
 hipError_t launch_rope_table(float* table, int F, int Hp, int Wp, int head_dim,
                              float theta, hipStream_t st);
 hipError_t launch_patch_embed(int dtype, const float* x, const void* ctx, const void* W_pe,

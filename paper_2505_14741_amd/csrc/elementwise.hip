@@ -126,36 +126,32 @@ hipError_t launch_gemv(int dtype, const void* W, const float* bias, const float*
 }
 
 // ------------------------------------------------------------------------- 3D RoPE table
-// (cos, sin) of pos_A * theta^(-2m/d_A) for every video token and pair, interleaved: table[token][pair] =
-// (cos, sin), so the two pairs behind four consecutive columns are one 16-byte load; axis widths
-// d/4, 3d/8, 3d/8 over (frame, row, col).  Double precision angles.
-__global__ void rope_table_kernel(float2* __restrict__ table, int F, int Hp,
-                                  int Wp, int head_dim, float theta) {
-    int half = head_dim / 2;
-    long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    long total = (long)F * Hp * Wp * half;
+// (cos, sin) of pos * theta^(-2m/d_A), axis widths d/4, 3d/8, 3d/8 over (frame, row, col), double precision
+// angles.  The angle of a pair depends on the token only through its position on the pair's axis, so the table is
+// stored per axis -- [F][d/8], [Hp][3d/16], [Wp][3d/16] entries of (cos, sin) -- about 1 KB instead of 256 bytes
+// per token: the projection epilogue that rotates q and k finds it in the nearest cache.
+__global__ void rope_table_kernel(float2* __restrict__ table, int F, int Hp, int Wp, int head_dim, float theta) {
+    const int p0 = head_dim / 8, p1 = 3 * head_dim / 16;
+    const int total = F * p0 + (Hp + Wp) * p1;
+    int idx = blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= total) return;
-    int pair = idx % half;
-    long tok = idx / half;
-    int j = tok % Wp;
-    int i = (tok / Wp) % Hp;
-    int f = tok / ((long)Wp * Hp);
-    int p0 = head_dim / 8;            // pairs on the frame axis
-    int p1 = 3 * head_dim / 16;       // pairs on each spatial axis
     int pos, m, dA;
-    if (pair < p0) { pos = f; m = pair; dA = 2 * p0; }
-    else if (pair < p0 + p1) { pos = i; m = pair - p0; dA = 2 * p1; }
-    else { pos = j; m = pair - p0 - p1; dA = 2 * p1; }
+    if (idx < F * p0) { pos = idx / p0; m = idx % p0; dA = 2 * p0; }
+    else if (idx < F * p0 + Hp * p1) { int r = idx - F * p0; pos = r / p1; m = r % p1; dA = 2 * p1; }
+    else { int r = idx - F * p0 - Hp * p1; pos = r / p1; m = r % p1; dA = 2 * p1; }
     double ang = (double)pos * exp(-2.0 * (double)m / (double)dA * log((double)theta));
     table[idx] = make_float2((float)cos(ang), (float)sin(ang));
 }
 
+size_t rope_table_floats(int F, int Hp, int Wp, int head_dim) {
+    return 2 * ((size_t)F * (head_dim / 8) + (size_t)(Hp + Wp) * (3 * head_dim / 16));
+}
+
 hipError_t launch_rope_table(float* table, int F, int Hp, int Wp, int head_dim,
                              float theta, hipStream_t st) {
-    long total = (long)F * Hp * Wp * (head_dim / 2);
+    const int total = (int)(rope_table_floats(F, Hp, Wp, head_dim) / 2);
     if (total == 0) return hipSuccess;
-    rope_table_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(reinterpret_cast<float2*>(table), F, Hp, Wp,
-                                                                      head_dim, theta);
+    rope_table_kernel<<<(total + 255) / 256, 256, 0, st>>>(reinterpret_cast<float2*>(table), F, Hp, Wp, head_dim, theta);
     return hipGetLastError();
 }
 

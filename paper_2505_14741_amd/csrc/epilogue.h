@@ -29,8 +29,10 @@ __device__ __forceinline__ void epilogue_pair(const Epilogue& ep, T* __restrict_
         if (n >= ep.geom.text_tokens && col < 2 * ep.D) {
             int nv = n - ep.geom.text_tokens;
             int pr = (col % ep.head_dim) >> 1;
-            long ti = (long)nv * (ep.head_dim >> 1) + pr;
-            float cs = ep.rope_cs[2 * ti], sn = ep.rope_cs[2 * ti + 1];
+            const RopeAxis ra = rope_axis_of(pr, ep.head_dim, ep.rope_F, ep.rope_Hp);
+            const int q1 = nv / ep.rope_Wp, q2 = q1 / ep.rope_Hp;
+            const int pos = ra.axis == 0 ? q2 : ra.axis == 1 ? q1 - q2 * ep.rope_Hp : nv - q1 * ep.rope_Wp;
+            float cs = ep.rope_cs[ra.base + pos * ra.stride], sn = ep.rope_cs[ra.base + pos * ra.stride + 1];
             float r0 = v0 * cs - v1 * sn;
             float r1 = v0 * sn + v1 * cs;
             v0 = r0;

@@ -99,7 +99,8 @@ __device__ __forceinline__ void wave_epilogue(f32x4_t (&acc)[TM][TN][4], const E
     // per-kind lane constants
     f32x4_t gate_v = {0.f, 0.f, 0.f, 0.f}, gate_t = gate_v;
     bool rot = false;
-    int pr = 0;
+    RopeAxis ra0{0, 0, 0}, ra1{0, 0, 0};                 // the lane's two (even, odd) pairs: usually, not always, one axis
+    float inv_wp = 0.f, inv_hp = 0.f;
     float qs = 1.0f;
     if constexpr (KIND == EPI_GATE_RESIDUAL) {
         const float* g = ep.mod_layer + b_first * ep.mod_batch_stride + colc;
@@ -112,7 +113,11 @@ __device__ __forceinline__ void wave_epilogue(f32x4_t (&acc)[TM][TN][4], const E
     unsigned nmax1 = 0u, nmax2 = 0u;
     if constexpr (KIND == EPI_QKV_ROPE) {
         rot = col < 2 * ep.D;                            // q and k columns rotate, v columns do not
-        pr = (colc % ep.head_dim) >> 1;                  // first of the lane's two (even, odd) pairs
+        const int pr = (colc % ep.head_dim) >> 1;        // first of the lane's two pairs
+        ra0 = rope_axis_of(pr, ep.head_dim, ep.rope_F, ep.rope_Hp);
+        ra1 = rope_axis_of(pr + 1, ep.head_dim, ep.rope_F, ep.rope_Hp);
+        inv_wp = 1.0f / (float)ep.rope_Wp;
+        inv_hp = 1.0f / (float)ep.rope_Hp;
         qs = col < ep.D ? ep.q_scale : 1.0f;
         track_norms = ep.norm_bounds != nullptr && wcol0 < 2 * ep.D && wcol0 < Nn;
         norm_which = wcol0 < ep.D ? 0 : 1;
@@ -131,8 +136,23 @@ __device__ __forceinline__ void wave_epilogue(f32x4_t (&acc)[TM][TN][4], const E
             int b;
             const int n = token_of(m, b);
             f32x4_t r = {1.f, 0.f, 1.f, 0.f};
-            if (rot && n >= text)                        // (cos, sin) of the lane's two pairs: one 16-byte load
-                r = *reinterpret_cast<const f32x4_t*>(ep.rope_cs + 2 * (unsigned)((n - text) * (ep.head_dim >> 1) + pr));
+            if (rot && n >= text) {
+                // video token -> (frame, patch row, patch column); the quotients come from a float multiply and one
+                // correction step (exact below 2^22 tokens per sample), then two 8-byte reads of the per-axis table
+                const int nv = n - text;
+                int q1 = (int)((float)nv * inv_wp);
+                q1 += (q1 + 1) * ep.rope_Wp <= nv ? 1 : 0;
+                q1 -= q1 * ep.rope_Wp > nv ? 1 : 0;
+                int q2 = (int)((float)q1 * inv_hp);
+                q2 += (q2 + 1) * ep.rope_Hp <= q1 ? 1 : 0;
+                q2 -= q2 * ep.rope_Hp > q1 ? 1 : 0;
+                const int pj = nv - q1 * ep.rope_Wp, pi = q1 - q2 * ep.rope_Hp;
+                const int pos0 = ra0.axis == 0 ? q2 : ra0.axis == 1 ? pi : pj;
+                const int pos1 = ra1.axis == 0 ? q2 : ra1.axis == 1 ? pi : pj;
+                const f32x2_t a = *reinterpret_cast<const f32x2_t*>(ep.rope_cs + ra0.base + pos0 * ra0.stride);
+                const f32x2_t c = *reinterpret_cast<const f32x2_t*>(ep.rope_cs + ra1.base + pos1 * ra1.stride);
+                r = f32x4_t{a[0], a[1], c[0], c[1]};
+            }
             return r;
         } else {
             return f32x4_t{0.f, 0.f, 0.f, 0.f};
