@@ -997,9 +997,13 @@ bool attention_uses_mfma(int dtype, int head_dim) {
     return dtype == PS_BF16 && head_dim == 64 && get_kernel_path() != 1;
 }
 
-float* attention_norm_bounds(int dtype, int batch, int heads, int head_dim, void* ws, hipStream_t st) {
+float* attention_norm_bounds(int dtype, int batch, int heads, int head_dim, void* ws, hipStream_t st, bool clear,
+                             int* count) {
+    if (count) *count = 0;
     if (!ws || !attention_uses_mfma(dtype, head_dim) || !attention_bounded_path(heads)) return nullptr;
     const int nb = batch * heads * 2;
+    if (count) *count = nb;
+    if (!clear) return (float*)ws;
     attn_bound_clear_kernel<<<(nb + 255) / 256, 256, 0, st>>>((float*)ws, nb);
     return hipGetLastError() == hipSuccess ? (float*)ws : nullptr;
 }

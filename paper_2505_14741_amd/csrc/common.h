@@ -95,7 +95,10 @@ hipError_t launch_attention(int dtype, const void* q, const void* k, const void*
                             bool bounds_ready = false);
 // Where a producer of q and k may leave those maxima itself: zeroes [batch*heads][2] floats at the head of `ws`
 // on the stream and returns their address; nullptr if this shape's attention does not use them.
-float* attention_norm_bounds(int dtype, int batch, int heads, int head_dim, void* ws, hipStream_t st);
+// the per-(batch, head) norm maxima buffer of the bounded attention path inside ws (nullptr if that path is off);
+// *count = its length in floats; clear: zero it with a launch of its own (else the caller zeroes it before use)
+float* attention_norm_bounds(int dtype, int batch, int heads, int head_dim, void* ws, hipStream_t st, bool clear = true,
+                             int* count = nullptr);
 void set_kernel_path(int p);
 int get_kernel_path();
 
@@ -131,7 +134,7 @@ hipError_t launch_patch_embed(int dtype, const float* x, const void* ctx, const 
 // out[m, :] = LN(X[m, :]) * (1 + scale) + shift with per-token stream selection.
 hipError_t launch_ln_modulate(int dtype, const float* X, void* out, int M, int D, float eps,
                               const float* mod_layer, long mod_batch_stride, int shift_chunk,
-                              int scale_chunk, TokenGeom geom, hipStream_t st);
+                              int scale_chunk, TokenGeom geom, hipStream_t st, float* zero_buf = nullptr, int zero_n = 0);
 hipError_t launch_final_proj(int dtype, const float* X, const float* modf, const void* W_out,
                              const float* b_out, float* eps_out, int batch, int C, int F, int H,
                              int Wd, int patch, int text_tokens, int D, float eps, hipStream_t st);

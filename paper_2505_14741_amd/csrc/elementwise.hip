@@ -227,7 +227,12 @@ hipError_t launch_patch_embed(int dtype, const float* x, const void* ctx, const 
 template <typename T, int MAXV>
 __global__ void ln_modulate_kernel(const float* __restrict__ X, T* __restrict__ out, int M, int D,
                                    float eps, const float* __restrict__ mod_layer, long mod_bs,
-                                   int shift_chunk, int scale_chunk, TokenGeom g) {
+                                   int shift_chunk, int scale_chunk, TokenGeom g, float* __restrict__ zero_buf,
+                                   int zero_n) {
+    // a few words some later kernel accumulates into (the norm maxima of the QKV projection) are cleared here
+    // instead of by a launch of their own
+    if (blockIdx.x == 0)
+        for (int i = threadIdx.x; i < zero_n; i += blockDim.x) zero_buf[i] = 0.f;
     int row = (blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
     int lane = threadIdx.x % WAVE;
     if (row >= M) return;
@@ -282,16 +287,16 @@ __global__ void ln_modulate_kernel(const float* __restrict__ X, T* __restrict__ 
 
 hipError_t launch_ln_modulate(int dtype, const float* X, void* out, int M, int D, float eps,
                               const float* mod_layer, long mod_bs, int shift_chunk, int scale_chunk,
-                              TokenGeom geom, hipStream_t st) {
+                              TokenGeom geom, hipStream_t st, float* zero_buf, int zero_n) {
     int threads = 256;
     int blocks = (M + 3) / 4;
     if (D % 4 != 0 || D > 64 * 4 * 8) return hipErrorInvalidValue;
     if (dtype == PS_BF16)
         ln_modulate_kernel<bf16_t, 8><<<blocks, threads, 0, st>>>(X, (bf16_t*)out, M, D, eps, mod_layer, mod_bs,
-                                                                 shift_chunk, scale_chunk, geom);
+                                                                 shift_chunk, scale_chunk, geom, zero_buf, zero_n);
     else
         ln_modulate_kernel<float, 8><<<blocks, threads, 0, st>>>(X, (float*)out, M, D, eps, mod_layer, mod_bs,
-                                                                shift_chunk, scale_chunk, geom);
+                                                                shift_chunk, scale_chunk, geom, zero_buf, zero_n);
     return hipGetLastError();
 }
 
