@@ -16,6 +16,11 @@ import os
 import sys
 import time
 
+# Kernel arguments in device memory: the command processor then does not fetch them from host memory at every
+# dispatch, which shortens the gaps between the ~330 dependent launches of a step (measured: 0.5 % of a step).
+# A documented HIP runtime setting; it must be in the environment before the runtime initialises.
+os.environ.setdefault("HIP_FORCE_DEV_KERNARG", "1")
+
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
