@@ -260,11 +260,12 @@ static constexpr int PART_STRIDE = 68;      // floats per row of a partial resul
 
 // Merge of the key-range pieces of the split items: one thread per (row, 4 output values).
 // O = sum_i w_i O_i / sum_i w_i l_i with w_i = 2^(c (r_i - max_i r_i)).
-__global__ void __launch_bounds__(256)
-attn_merge_kernel(const float* __restrict__ part, bf16_t* __restrict__ o, int seq, int heads, int qblocks,
-                  int full_blocks, int nsplit, int nitems, float cexp, int bq, AttnStrides s,
-                  const float* __restrict__ bounds) {
-    const int gid = blockIdx.x * 256 + threadIdx.x;
+// (a device function: it runs as a kernel of its own and as the trailing workgroups of attn_mfma_kernel)
+__device__ __forceinline__ void
+attn_merge_rows(int block, const float* __restrict__ part, bf16_t* __restrict__ o, int seq, int heads, int qblocks,
+                int full_blocks, int nsplit, int nitems, float cexp, int bq, const AttnStrides& s,
+                const float* __restrict__ bounds) {
+    const int gid = block * 256 + threadIdx.x;
     const int d4 = gid & 15, rowid = gid >> 4;          // 16 threads per row
     const int item = rowid / bq, row = rowid % bq;
     if (item >= nitems) return;
@@ -292,6 +293,21 @@ attn_merge_kernel(const float* __restrict__ part, bf16_t* __restrict__ o, int se
     wv[2] = (__bf16)(acc.z * inv); wv[3] = (__bf16)(acc.w * inv);
     *reinterpret_cast<bf16x4_t*>(o + b * s.o_batch + (long)qi * s.o_tok + h * s.o_head + d4 * 4) = wv;
 }
+
+__global__ void __launch_bounds__(256)
+attn_merge_kernel(const float* __restrict__ part, bf16_t* __restrict__ o, int seq, int heads, int qblocks,
+                  int full_blocks, int nsplit, int nitems, float cexp, int bq, AttnStrides s,
+                  const float* __restrict__ bounds) {
+    attn_merge_rows(blockIdx.x, part, o, seq, heads, qblocks, full_blocks, nsplit, nitems, cexp, bq, s, bounds);
+}
+
+// Merge work appended to a launch of attn_mfma_kernel: workgroups from `first` on merge the pieces another,
+// earlier launch left in `part` (blocks == 0: none).
+struct MergeTail {
+    const float* part;
+    int first, blocks, full_blocks, nsplit, nitems, bq;
+    float cexp;
+};
 
 // global->LDS load of 16 bytes per lane: lane j's bytes land at lds_addr + 16*j (lds_addr
 // wave-uniform, passed through M0).  _base: scalar 64-bit base + per-lane 32-bit byte offset;
@@ -327,7 +343,13 @@ template <int QT, bool PRESCALED>   // QT: 32-query column tiles per wave
 __global__ void __launch_bounds__(256, 2)
 attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
                  bf16_t* __restrict__ o, int seq, int heads, float scale_log2e, int qblocks, AttnStrides s,
-                 int full_blocks, int nsplit, float* __restrict__ part, const float* __restrict__ bounds) {
+                 int full_blocks, int nsplit, float* __restrict__ part, const float* __restrict__ bounds,
+                 MergeTail mt) {
+    if (mt.blocks != 0 && (int)blockIdx.x >= mt.first) {    // whole workgroup: before any barrier
+        attn_merge_rows(blockIdx.x - mt.first, mt.part, o, seq, heads, qblocks, mt.full_blocks, mt.nsplit, mt.nitems,
+                        mt.cexp, mt.bq, s, bounds);
+        return;
+    }
     constexpr int KV = 64;
     constexpr int BQ = 4 * QT * 32;
     constexpr int NST = 3;                       // LDS ring depth
@@ -1038,30 +1060,34 @@ hipError_t launch_attention(int dtype, const void* q, const void* k, const void*
             else
                 attn_sp_kernel<false><<<p.full + p.pieces, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c, p.qblocks,
                                                                          s, p.full, p.nsplit, part, bounds);
-            const AttnPlan& g = p;
+            // then the reference-tracking kernel (unsplit) for the other heads; the merge of attn_sp_kernel's pieces
+            // rides on that launch as workgroups after the items
+            const int nitems = p.items - p.full;
+            MergeTail mt{part, p.items, 0, p.full, p.nsplit, nitems, bq, cexp};
+            if (p.pieces != 0) mt.blocks = (int)(((long)nitems * bq * 16 + 255) / 256);
             if (q_prescaled)
-                attn_mfma_kernel<2, true><<<g.items, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c, g.qblocks, s,
-                                                                   g.items, 1, nullptr, bounds);
+                attn_mfma_kernel<2, true><<<p.items + mt.blocks, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c,
+                                                                              p.qblocks, s, p.items, 1, nullptr, bounds, mt);
             else
-                attn_mfma_kernel<2, false><<<g.items, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c, g.qblocks, s,
-                                                                    g.items, 1, nullptr, bounds);
-        } else {
-            // (one 32-query tile per wave, i.e. 128-query workgroups at three per CU, measured 9 % slower:
-            // it doubles the K/V traffic into LDS and the fragment reads per MFMA)
-            if (q_prescaled)
-                attn_mfma_kernel<2, true><<<p.full + p.pieces, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c, p.qblocks,
-                                                                             s, p.full, p.nsplit, part, nullptr);
-            else
-                attn_mfma_kernel<2, false><<<p.full + p.pieces, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c,
-                                                                              p.qblocks, s, p.full, p.nsplit, part, nullptr);
+                attn_mfma_kernel<2, false><<<p.items + mt.blocks, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c,
+                                                                               p.qblocks, s, p.items, 1, nullptr, bounds, mt);
+            return hipGetLastError();
         }
+        // (one 32-query tile per wave, i.e. 128-query workgroups at three per CU, measured 9 % slower:
+        // it doubles the K/V traffic into LDS and the fragment reads per MFMA)
+        const MergeTail none{nullptr, 0, 0, 0, 0, 0, 0, 0.f};
+        if (q_prescaled)
+            attn_mfma_kernel<2, true><<<p.full + p.pieces, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c, p.qblocks,
+                                                                         s, p.full, p.nsplit, part, nullptr, none);
+        else
+            attn_mfma_kernel<2, false><<<p.full + p.pieces, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c,
+                                                                          p.qblocks, s, p.full, p.nsplit, part, nullptr, none);
         hipError_t err = hipGetLastError();
         if (err != hipSuccess || p.pieces == 0) return err;
         const int nitems = p.items - p.full;
         const long threads = (long)nitems * bq * 16;
         attn_merge_kernel<<<(unsigned)((threads + 255) / 256), 256, 0, st>>>(part, (bf16_t*)o, seq, heads, p.qblocks,
-                                                                            p.full, p.nsplit, nitems, cexp, bq, s,
-                                                                            bounded ? bounds : nullptr);
+                                                                            p.full, p.nsplit, nitems, cexp, bq, s, nullptr);
         return hipGetLastError();
     }
     if (q_prescaled) return hipErrorInvalidValue;     // only the MFMA kernel takes pre-scaled queries
