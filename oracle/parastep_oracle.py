@@ -21,7 +21,8 @@ Pin status (see tests/test_oracle_*.py):
       constant / point-mass predictors, p = 1 == plain loop                -> pinned
   dit_forward : the paper fixes none of the network's internals; its wiring is pinned
       by invariants (zero gates, zero keys, permutation, batch independence) and by a
-      second loop-level implementation, not by any printed value.
+      second loop-level implementation, not by any printed value.  Its `query_rows`
+      option is pinned against the whole evaluation.
 """
 from __future__ import annotations
 
@@ -233,7 +234,8 @@ def _per_token(mod, D, Lt, N, name):
     return out
 
 
-def dit_forward(cfg, W: Dict[str, np.ndarray], x, ctx, t, taps: Optional[list] = None):
+def dit_forward(cfg, W: Dict[str, np.ndarray], x, ctx, t, taps: Optional[list] = None,
+                query_rows: Optional[Sequence[int]] = None):
     """Noise predictor eps_theta(x_t, t, c): a DiT with full 3D attention.
 
     x [B,C,F,H,W]; ctx [B,L_txt,D] or None; t [B] integer timesteps -> eps [B,C,F,H,W].
@@ -242,7 +244,14 @@ def dit_forward(cfg, W: Dict[str, np.ndarray], x, ctx, t, taps: Optional[list] =
     modulated LayerNorm, GELU MLP, gated residual.  Text and video tokens use
     separate modulation chunks.  If `taps` is a list, the token matrix after the
     embedding and after every block is appended to it (per batch sample).
+
+    `query_rows` (single-layer networks only) makes long sequences affordable: attention
+    is evaluated for these token rows alone (all keys and values still take part) and
+    NaN stands in for every other row of its output.  In a single layer a token's output
+    depends on the other tokens through keys and values only, so the patches of the
+    listed video tokens come out as in the whole evaluation and all others as NaN.
     """
+    assert query_rows is None or cfg.layers == 1
     x = np.asarray(x, dtype=F64)
     B = x.shape[0]
     D, H, d, Lt = cfg.hidden, cfg.heads, cfg.head_dim, cfg.text_tokens
@@ -278,7 +287,12 @@ def dit_forward(cfg, W: Dict[str, np.ndarray], x, ctx, t, taps: Optional[list] =
             v = qkv[:, 2 * D:3 * D].reshape(N, H, d)
             q[Lt:] = rope3d_apply(q[Lt:], angles)
             k[Lt:] = rope3d_apply(k[Lt:], angles)
-            o = attn3d(q[None], k[None], v[None], 1.0 / math.sqrt(d))[0].reshape(N, D)
+            if query_rows is None:
+                o = attn3d(q[None], k[None], v[None], 1.0 / math.sqrt(d))[0].reshape(N, D)
+            else:
+                rows = np.asarray(query_rows, dtype=np.int64)
+                o = np.full((N, D), np.nan, dtype=F64)
+                o[rows] = attn3d(q[None, rows], k[None], v[None], 1.0 / math.sqrt(d))[0].reshape(len(rows), D)
             X = X + ch("gate_a") * (o @ Wd[f"W_o.{l}"].T + Wd[f"b_o.{l}"])
             h2 = layer_norm(X, cfg.ln_eps) * (1.0 + ch("scale_m")) + ch("shift_m")
             u = gelu_tanh(h2 @ Wd[f"W_1.{l}"].T + Wd[f"b_1.{l}"])

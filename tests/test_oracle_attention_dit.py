@@ -253,3 +253,22 @@ def test_dit_depends_on_every_weight():
         W2 = dict(W)
         W2[name] = W[name] + 0.1
         assert np.abs(O.dit_forward(cfg, W2, x, ctx, [700]) - base).max() > 1e-9, name
+
+
+def test_dit_query_rows_option_equals_the_whole_evaluation():
+    """Single layer: the listed tokens' patches equal the whole evaluation's, all other patches are NaN."""
+    cfg = I.CONFIGS["tiny_text"].with_(layers=1)
+    W = _w(cfg, 11)
+    x, ctx = I.make_latent(cfg, 2), I.make_context(cfg, 2)
+    t = [700, 30]
+    whole = O.dit_forward(cfg, W, x, ctx, t)
+    video = np.array([0, 7, 8, 63, 64, 127])                  # video token indices (frame, row, column order)
+    part = O.dit_forward(cfg, W, x, ctx, t, query_rows=cfg.text_tokens + video)
+    listed = np.zeros(cfg.video_tokens, dtype=bool)
+    listed[video] = True
+    for b in range(2):
+        pw, pp = O.patchify(whole[b], cfg.patch), O.patchify(part[b], cfg.patch)
+        np.testing.assert_allclose(pp[listed], pw[listed], rtol=1e-12, atol=1e-14)
+        assert np.isnan(pp[~listed]).all()
+    with pytest.raises(AssertionError):
+        O.dit_forward(I.CONFIGS["tiny_text"], _w(I.CONFIGS["tiny_text"], 11), x, ctx, t, query_rows=[0])
