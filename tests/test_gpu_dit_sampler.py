@@ -123,6 +123,35 @@ def test_block_forward_bf16_whole(init):
     assert r <= 2e-2
 
 
+@pytest.mark.parametrize("name", ["full", "long"])
+def test_single_layer_forward_at_the_full_token_count_sampled_patches(name):
+    """One layer on the 13x60x90 latent (17550 video + 226 text tokens: the launch shapes the benchmark times)
+    and on the 25x60x90 latent (33750 + 226).
+
+    The oracle evaluates attention for the listed tokens only (all keys and values take part); their patches
+    are compared.  The list holds the first and last token, neighbours across a patch row, a frame and the last
+    full 256-row tile of the projections, and seeded random tokens.
+    """
+    cfg = I.CONFIGS[name].with_(layers=1)
+    print(f"dit_forward single layer, {cfg.tokens} tokens", flush=True)
+    _, W, d = setup(name, "std002", cfg)
+    x, ctx = I.make_latent(cfg, 1), I.make_context(cfg, 1)
+    eps = host(B.dit_forward(d, dev(x), dev(ctx, torch.bfloat16), [500]))
+    assert np.isfinite(eps).all()
+    Wp, per_frame = cfg.grid[2], cfg.grid[1] * cfg.grid[2]
+    edge = cfg.tokens // 256 * 256 - cfg.text_tokens          # first video token of the projections' last row tile
+    video = np.array([0, 1, Wp - 1, Wp, per_frame - 1, per_frame, edge - 1, edge, cfg.video_tokens - 1])
+    video = np.unique(np.concatenate([video, np.random.default_rng(77).integers(0, cfg.video_tokens, 40)]))
+    ref = O.dit_forward(cfg, W, x, ctx, [500], query_rows=cfg.text_tokens + video)
+    got = O.patchify(eps[0], cfg.patch)[video]
+    want = O.patchify(ref[0], cfg.patch)[video]
+    assert np.isfinite(want).all()
+    r = O.rel_mae(want, got)[2]
+    worst = max(O.rel_mae(want[i], got[i])[2] for i in range(len(video)))
+    print(f"  rel-MAE {r:.3e}, worst token {worst:.3e}", flush=True)
+    assert r <= 2e-2 and worst <= 4e-2
+
+
 # ----------------------------------------------------------------------------- sampler_run
 def oracle_run(cfg, W, x_T, ctx, S, m, cyc, mode="reuse_then_predict"):
     tau, a, b = O.ddim_coefficients(steps=S)
