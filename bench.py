@@ -81,6 +81,65 @@ def cpu_baseline(cfg, rows=6144):
             "sample_seconds": round(dt, 2)}
 
 
+def report(kind, torch, B, I):
+    """Supplementary measurements on the other named workloads (one JSON object; not the benchmark line)."""
+    cfg = I.CONFIGS["long" if kind == "long_sweep" else "full"]
+    N, D = cfg.tokens, cfg.hidden
+    d = B.dit_create(cfg, device_weights(cfg, torch, 1003))
+    g = torch.Generator(device="cuda"); g.manual_seed(42)
+    x_T = torch.randn((1,) + cfg.latent_shape, generator=g, device="cuda")
+    ctx = torch.randn((1, cfg.text_tokens, D), generator=g, device="cuda").to(torch.bfloat16)
+
+    def timed(steps, warm, window, batched=False, mode=0):
+        ts, a, b = B.ddim_coefficients(steps)
+        cycles = [window] * ((steps - warm + window - 1) // window)
+        sched = B.Schedule(ts, a, b, warm, cycles, batched=batched, mode=mode)
+        B.dit_profile_enable(d, 2)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        x0, sums, calls = B.sampler_run(d, sched, x_T, ctx)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3
+        att_ms, att_n = B.dit_profile_read(d)["attention"]
+        B.dit_profile_enable(d, 0)
+        assert bool(torch.isfinite(x0).all())
+        return {"ms": round(ms, 1), "ms_per_step": round(ms / steps, 2), "predictor_calls": int(calls),
+                "attention_avg_ms": round(att_ms / max(att_n, 1), 4), "attention_launches": int(att_n)}, x0
+
+    def deviation(x, ref):
+        return float(B.rel_mae(x, ref)[2])
+
+    timed(2, 1, 2)                                            # untimed first touch
+    shape = f"{cfg.layers}-layer DiT, {cfg.video_tokens} video + {cfg.text_tokens} text tokens, bf16, batch 1"
+    if kind == "run50":
+        plain, x_plain = timed(50, 1, 1)
+        rtp, x_rtp = timed(50, 1, 2)
+        rtp_b, x_b = timed(50, 1, 2, batched=True)
+        direct, x_dir = timed(50, 1, 2, mode=1)
+        rtp["final_rel_mae_vs_no_reuse"] = deviation(x_rtp, x_plain)
+        rtp_b["final_rel_mae_vs_no_reuse"] = deviation(x_b, x_plain)
+        rtp_b["bitwise_equal_to_unbatched"] = bool(torch.equal(x_b, x_rtp))
+        direct["final_rel_mae_vs_no_reuse"] = deviation(x_dir, x_plain)
+        return {"report": "50 DDIM steps, 1 warm-up step, reuse window 2", "workload": shape, "weights": "random (std 0.02)",
+                "no_reuse": plain, "reuse_then_predict": rtp, "reuse_then_predict_step_batched": rtp_b,
+                "direct_reuse": direct}
+    if kind == "long_sweep":
+        out = {"report": "5 denoising steps, 1 warm-up step, reuse windows 2 and 3", "workload": shape}
+        for window in (2, 3):
+            r, _ = timed(5, 1, window)
+            r["attention_tflops"] = round(4.0 * N * N * D / (r["attention_avg_ms"] * 1e-3) / 1e12, 1)
+            out[f"window_{window}"] = r
+        return out
+    # step-batched round: cycles of 4 steps, one predictor call of batch 4 per cycle, over 48 reuse steps
+    one, x_one = timed(49, 1, 4)
+    bat, x_bat = timed(49, 1, 4, batched=True)
+    bat["attention_tflops"] = round(4.0 * 4 * N * N * D / (bat["attention_avg_ms"] * 1e-3) / 1e12, 1)
+    one["attention_tflops"] = round(4.0 * N * N * D / (one["attention_avg_ms"] * 1e-3) / 1e12, 1)
+    bat["bitwise_equal_to_unbatched"] = bool(torch.equal(x_bat, x_one))
+    return {"report": "1 warm-up step + 48 steps in cycles of 4: one call per step against one call of batch 4 per cycle",
+            "workload": shape, "one_call_per_step": one, "one_call_per_cycle_batch_4": bat}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -91,6 +150,9 @@ def main():
     ap.add_argument("--kernel-path", type=lambda v: int(v, 0), default=0, help="tuning hook passed to ps_set_kernel_path")
     ap.add_argument("--kernel", default=None, choices=["attn3d", "dit_linear", "copy", "sampler_step"],
                     help="profiling target: launch only this kernel 3 times at the workload's shape and exit")
+    ap.add_argument("--report", default=None, choices=["run50", "long_sweep", "step_batched"],
+                    help="supplementary report instead of the benchmark line: the 50-step run against a no-reuse "
+                         "run, the long-video window sweep, or the step-batched round")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives are built); use --gpus 1")
@@ -140,6 +202,10 @@ def main():
             what = {"kernel": "sampler_step", "n": n, "bytes": 16 * n}
         torch.cuda.synchronize()
         print(json.dumps(what))
+        return
+
+    if args.report:
+        print(json.dumps(report(args.report, torch, B, I)))
         return
 
     d = B.dit_create(cfg, device_weights(cfg, torch, 1003))
