@@ -163,7 +163,7 @@ __global__ void patch_embed_kernel(const float* __restrict__ x, const T* __restr
                                    const T* __restrict__ W_pe, const float* __restrict__ b_pe,
                                    float* __restrict__ X, int C, int F, int H, int Wd, int patch,
                                    int text_tokens, int D, long ctx_bs) {
-    extern __shared__ float pv[];        // [TOK][P]
+    extern __shared__ float pv[];        // [P][TOK]: the TOK values one weight multiplies are contiguous
     int Hp = H / patch, Wp = Wd / patch;
     int Nv = F * Hp * Wp;
     int N = text_tokens + Nv;
@@ -180,7 +180,7 @@ __global__ void patch_embed_kernel(const float* __restrict__ x, const T* __restr
             int dx = pi % patch, dy = (pi / patch) % patch, c = pi / (patch * patch);
             val = x[((((long)b * C + c) * F + f) * H + (i * patch + dy)) * Wd + (j * patch + dx)];
         }
-        pv[e] = val;
+        pv[pi * TOK + tl] = val;
     }
     __syncthreads();
     for (int col = threadIdx.x; col < D; col += blockDim.x) {
@@ -188,10 +188,29 @@ __global__ void patch_embed_kernel(const float* __restrict__ x, const T* __restr
 #pragma unroll
         for (int tl = 0; tl < TOK; ++tl) acc[tl] = b_pe[col];
         const T* w = W_pe + (long)col * P;
-        for (int pi = 0; pi < P; ++pi) {
+        int pi = 0;
+        if ((P & 7) == 0 && (reinterpret_cast<size_t>(W_pe) & 15) == 0) {   // rows of W_pe start 16-byte aligned: 8 weights per load
+            for (; pi < P; pi += 8) {
+                float wv[8];
+                if constexpr (sizeof(T) == 2) {
+                    union { uint4 u; bf16_t h[8]; } pk;
+                    pk.u = *reinterpret_cast<const uint4*>(w + pi);
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) wv[k] = to_f32(pk.h[k]);
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) wv[k] = to_f32(w[pi + k]);
+                }
+#pragma unroll
+                for (int k = 0; k < 8; ++k)              // same order of additions as the one-by-one loop
+#pragma unroll
+                    for (int tl = 0; tl < TOK; ++tl) acc[tl] += wv[k] * pv[(pi + k) * TOK + tl];
+            }
+        }
+        for (; pi < P; ++pi) {
             float wv = to_f32(w[pi]);
 #pragma unroll
-            for (int tl = 0; tl < TOK; ++tl) acc[tl] += wv * pv[tl * P + pi];
+            for (int tl = 0; tl < TOK; ++tl) acc[tl] += wv * pv[pi * TOK + tl];
         }
 #pragma unroll
         for (int tl = 0; tl < TOK; ++tl) {
@@ -206,7 +225,7 @@ __global__ void patch_embed_kernel(const float* __restrict__ x, const T* __restr
 hipError_t launch_patch_embed(int dtype, const float* x, const void* ctx, const void* W_pe,
                               const float* b_pe, float* X, int batch, int C, int F, int H, int Wd,
                               int patch, int text_tokens, int D, long ctx_bs, hipStream_t st) {
-    constexpr int TOK = 8;
+    constexpr int TOK = 16;
     int N = text_tokens + F * (H / patch) * (Wd / patch);
     int P = C * patch * patch;
     dim3 grid((N + TOK - 1) / TOK, batch);
