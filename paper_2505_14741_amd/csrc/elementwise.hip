@@ -42,35 +42,44 @@ hipError_t launch_sinusoid(const int32_t* t_host, float* out, int batch, int D, 
     return hipGetLastError();
 }
 
-// One wave per output row; weights stream once from HBM (16 bytes per lane and load when the row length
-// allows), inputs stay in cache.
+// One wave per GEMV_ROWS consecutive output rows (8 for a single input vector, 4 for batches); weights stream once from HBM (16 bytes per lane and load when
+// the row length allows, the loads of the wave's rows in flight together), inputs stay in cache and are read once
+// for the wave's rows.  Each row's sum is formed as if the wave had that row alone (same lanes, same order).
 // blockIdx.y picks one of up to GEMV_SET matrices of the same shape applied to the same input (the modulation
 // matrices of all layers in one launch).
-template <typename T, int MAXB>
+template <typename T, int MAXB, int GEMV_ROWS>
 __global__ void gemv_kernel(GemvSet set, const float* __restrict__ in, int rows,
                             int cols, int batch, long in_bs, long out_bs, int act) {
-    int wave = (blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
-    int lane = threadIdx.x % WAVE;
-    if (wave >= rows) return;
+    const int wave = (blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
+    const int lane = threadIdx.x % WAVE;
+    const int row0 = wave * GEMV_ROWS;
+    if (row0 >= rows) return;
     const T* __restrict__ W = static_cast<const T*>(set.W[blockIdx.y]);
     const float* __restrict__ bias = set.bias[blockIdx.y];
     float* __restrict__ out = set.out[blockIdx.y];
-    const T* w = W + (long)wave * cols;
-    float acc[MAXB];
+    const T* w[GEMV_ROWS];
 #pragma unroll
-    for (int b = 0; b < MAXB; ++b) acc[b] = 0.f;
+    for (int r = 0; r < GEMV_ROWS; ++r) w[r] = W + (long)min(row0 + r, rows - 1) * cols;   // rows past the end: recomputed, not stored
+    float acc[GEMV_ROWS][MAXB];
+#pragma unroll
+    for (int r = 0; r < GEMV_ROWS; ++r)
+#pragma unroll
+        for (int b = 0; b < MAXB; ++b) acc[r][b] = 0.f;
     constexpr int VEC = 16 / sizeof(T);                      // elements per 16-byte load
     if (cols % VEC == 0 && in_bs % 4 == 0) {
         for (int c = lane * VEC; c < cols; c += WAVE * VEC) {
-            float wv[VEC];
-            if constexpr (sizeof(T) == 2) {
-                typedef __attribute__((ext_vector_type(8))) __bf16 b8;
-                const b8 v = *reinterpret_cast<const b8*>(w + c);
+            float wv[GEMV_ROWS][VEC];
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) wv[e] = (float)v[e];
-            } else {
-                const float4 v = *reinterpret_cast<const float4*>(w + c);
-                wv[0] = v.x; wv[1] = v.y; wv[2] = v.z; wv[3] = v.w;
+            for (int r = 0; r < GEMV_ROWS; ++r) {
+                if constexpr (sizeof(T) == 2) {
+                    typedef __attribute__((ext_vector_type(8))) __bf16 b8;
+                    const b8 v = *reinterpret_cast<const b8*>(w[r] + c);
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) wv[r][e] = (float)v[e];
+                } else {
+                    const float4 v = *reinterpret_cast<const float4*>(w[r] + c);
+                    wv[r][0] = v.x; wv[r][1] = v.y; wv[r][2] = v.z; wv[r][3] = v.w;
+                }
             }
 #pragma unroll
             for (int b = 0; b < MAXB; ++b) {
@@ -79,27 +88,36 @@ __global__ void gemv_kernel(GemvSet set, const float* __restrict__ in, int rows,
 #pragma unroll
                     for (int e4 = 0; e4 < VEC; e4 += 4) {
                         const float4 x = *reinterpret_cast<const float4*>(ip + e4);
-                        acc[b] += (wv[e4] * x.x + wv[e4 + 1] * x.y) + (wv[e4 + 2] * x.z + wv[e4 + 3] * x.w);
+#pragma unroll
+                        for (int r = 0; r < GEMV_ROWS; ++r)
+                            acc[r][b] += (wv[r][e4] * x.x + wv[r][e4 + 1] * x.y) + (wv[r][e4 + 2] * x.z + wv[r][e4 + 3] * x.w);
                     }
                 }
             }
         }
     } else {
         for (int c = lane; c < cols; c += WAVE) {
-            float wv = to_f32(w[c]);
 #pragma unroll
-            for (int b = 0; b < MAXB; ++b)
-                if (b < batch) acc[b] += wv * in[b * in_bs + c];
+            for (int r = 0; r < GEMV_ROWS; ++r) {
+                const float wv = to_f32(w[r][c]);
+#pragma unroll
+                for (int b = 0; b < MAXB; ++b)
+                    if (b < batch) acc[r][b] += wv * in[b * in_bs + c];
+            }
         }
     }
 #pragma unroll
-    for (int b = 0; b < MAXB; ++b) {
-        if (b < batch) {
-            float v = wave_sum(acc[b]);
-            if (lane == 0) {
-                v += bias[wave];
-                if (act == 1) v = silu_f(v);
-                out[b * out_bs + wave] = v;
+    for (int r = 0; r < GEMV_ROWS; ++r) {
+        if (row0 + r >= rows) break;
+#pragma unroll
+        for (int b = 0; b < MAXB; ++b) {
+            if (b < batch) {
+                float v = wave_sum(acc[r][b]);
+                if (lane == 0) {
+                    v += bias[row0 + r];
+                    if (act == 1) v = silu_f(v);
+                    out[b * out_bs + row0 + r] = v;
+                }
             }
         }
     }
@@ -109,11 +127,21 @@ hipError_t launch_gemv_set(int dtype, const GemvSet& set, int count, const float
                            long in_bs, long out_bs, int act, hipStream_t st) {
     if (count < 1 || count > GEMV_SET) return hipErrorInvalidValue;
     int threads = 256;
-    dim3 blocks((rows + (threads / WAVE) - 1) / (threads / WAVE), count);
-    if (dtype == PS_BF16)
-        gemv_kernel<bf16_t, 16><<<blocks, threads, 0, st>>>(set, in, rows, cols, batch, in_bs, out_bs, act);
-    else
-        gemv_kernel<float, 16><<<blocks, threads, 0, st>>>(set, in, rows, cols, batch, in_bs, out_bs, act);
+    auto go = [&](auto kernel, int rows_per_wave) {
+        const int per_block = (threads / WAVE) * rows_per_wave;
+        dim3 blocks((rows + per_block - 1) / per_block, count);
+        kernel<<<blocks, threads, 0, st>>>(set, in, rows, cols, batch, in_bs, out_bs, act);
+    };
+    if (batch < 1 || batch > 16) return hipErrorInvalidValue;
+    if (dtype == PS_BF16) {
+        if (batch == 1) go(gemv_kernel<bf16_t, 1, 8>, 8);
+        else if (batch <= 4) go(gemv_kernel<bf16_t, 4, 4>, 4);
+        else go(gemv_kernel<bf16_t, 16, 4>, 4);
+    } else {
+        if (batch == 1) go(gemv_kernel<float, 1, 8>, 8);
+        else if (batch <= 4) go(gemv_kernel<float, 4, 4>, 4);
+        else go(gemv_kernel<float, 16, 4>, 4);
+    }
     return hipGetLastError();
 }
 
