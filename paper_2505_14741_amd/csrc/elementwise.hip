@@ -271,6 +271,7 @@ hipError_t launch_patch_embed(int dtype, const float* x, const void* ctx, const 
 // One wave per token row.  fp32 statistics (mean, then centred second moment), biased
 // variance, no affine; out = y*(1+scale)+shift with the text or video chunk.
 // The row is held in registers between the passes: D <= 64*4*MAXV.
+// (Two rows per wave, both loaded before the first reduction, measured 18 % slower at 17776 x 1920: 48 against 41 us.)
 template <typename T, int MAXV>
 __global__ void ln_modulate_kernel(const float* __restrict__ X, T* __restrict__ out, int M, int D,
                                    float eps, const float* __restrict__ mod_layer, long mod_bs,
