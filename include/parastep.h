@@ -130,8 +130,7 @@ PS_API int attn3d(const void* q, const void* k, const void* v, void* o,
  * dit_linear_workspace_bytes(...) of it, shapes whose output tiles do not fill the last round
  * of workgroups split those tiles along k (fp32 partial sums pass through the workspace and
  * are added in a fixed order); with NULL or less the call computes the same product unsplit.
- * The two differ only in summation order.  (Wide outputs divide such tiles by rows instead,
- * which needs no workspace and changes no bit of the result.) */
+ * The two differ only in summation order. */
 PS_API size_t dit_linear_workspace_bytes(int m, int n_out, int k, int dtype);
 PS_API int dit_linear(const void* a, const void* w, const float* bias, void* out, int m, int n_out, int k,
                int act, int dtype, void* workspace, size_t workspace_bytes, void* hip_stream);
@@ -140,7 +139,7 @@ PS_API int dit_linear(const void* a, const void* w, const float* bias, void* out
  * use the generic fp32-FMA kernels, 2 = bf16 attention without the key-split of its last
  * partial round of workgroups, 3 = bf16 head-dim-64 attention always through the kernel that
  * tracks a softmax reference (no norm-bound shortcut), 4 = projections whose last partial
- * round of workgroups is divided neither along k nor by rows, 0x100|v = force tile variant v of the
+ * round of workgroups is not divided along k, 0x100|v = force tile variant v of the
  * bf16 MFMA GEMM (1: 256x256, 2: 128x128).  Process-wide; returns the previous value. */
 PS_API int ps_set_kernel_path(int path);
 

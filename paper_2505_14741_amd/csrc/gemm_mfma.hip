@@ -522,25 +522,22 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, const bf
 }
 
 // The first full_tiles workgroups compute one BM x BN output tile each.  The tiles beyond them -- the last, partial
-// round of the chip's workgroup slots -- are shared out so that the round is shorter:
-//   rsplit == 2: two workgroups per tile, each computing BM/2 of its rows (no reduction; the wide tile's way);
-//   nsplit  > 1: nsplit workgroups per tile along K, fp32 partial sums to ep.split_ws (in accumulator layout)
-//                for gemm_tail_kernel (the narrow tile's way, where K is long).
+// round of the chip's workgroup slots -- can be shared out so that the round is shorter: with nsplit > 1, nsplit
+// workgroups per tile along K, fp32 partial sums to ep.split_ws (in accumulator layout) for gemm_tail_kernel (the
+// narrow tile where K is long).  (Dropped: two workgroups per tail tile of the wide tile, one per half of its rows.
+// With operands resident in the cache from the previous launch it was 2 % faster; with weights and activations
+// that change from call to call, as in the network, 1-4 % slower -- each half loads the whole W panel again.)
 // Tiles walk column-fastest inside bands of 8 tile rows, so the workgroups resident on one XCD cover a compact
 // block of the output and reuse each other's panels in L2.
 template <int BM, int BN, int WR, int WC, int BK, int NST, int KIND>
 __global__ void __launch_bounds__(WR * WC * 64, (WR * WC == 4 && BM * BN <= 128 * 128) ? 2 : 1)
 gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf16_t* __restrict__ C,
-                 int M, int Nn, int K, int tiles_m, int tiles_n, int full_tiles, int nsplit, int rsplit, Epilogue ep) {
+                 int M, int Nn, int K, int tiles_m, int tiles_n, int full_tiles, int nsplit, Epilogue ep) {
     __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * (BM + BN) * BK * 2];
     const int nk = K / BK;
-    int tile, piece = -1, part = 0, k0 = 0, k1 = nk;
+    int tile, piece = -1, k0 = 0, k1 = nk;
     if ((int)blockIdx.x < full_tiles) {
         tile = xcd_remap(blockIdx.x, full_tiles);
-    } else if (rsplit == 2) {
-        const int t = blockIdx.x - full_tiles;
-        tile = full_tiles + (t >> 1);
-        part = t & 1;
     } else {
         piece = blockIdx.x - full_tiles;
         tile = full_tiles + piece / nsplit;
@@ -556,13 +553,6 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
         int rows_here = min(GM, tiles_m - band * GM);
         m0 = (band * GM + in_band % rows_here) * BM;
         n0 = (in_band / rows_here) * BN;
-    }
-    if constexpr (BM == 256 && WR == 2 && WC == 4) {
-        if (rsplit == 2 && (int)blockIdx.x >= full_tiles) {       // uniform over the workgroup
-            m0 += part * (BM / 2);
-            if (m0 < M) gemm_tile<BM / 2, BN, WR, WC, BK, NST, KIND>(A, W, C, M, Nn, K, m0, n0, k0, k1, -1, ep, lds);
-            return;
-        }
     }
     gemm_tile<BM, BN, WR, WC, BK, NST, KIND>(A, W, C, M, Nn, K, m0, n0, k0, k1, piece, ep, lds);
 }
@@ -618,7 +608,7 @@ bool gemm_mfma_supported(int M, int Nn, int K) {
 }
 
 // How a shape is spread over the chip: which tile variant, how many tiles run whole and how the rest is split.
-struct GemmPlan { int variant, tiles_m, tiles_n, full, nsplit, rsplit, pieces; size_t ws_bytes; };
+struct GemmPlan { int variant, tiles_m, tiles_n, full, nsplit, pieces; size_t ws_bytes; };
 static int gemm_compute_units() {
     static int cus = 0;
     if (cus == 0) {
@@ -632,7 +622,7 @@ static int gemm_compute_units() {
 static int g_gemm_variant = 0;   // tuning hook: 0 auto
 void set_gemm_variant(int v) { g_gemm_variant = v; }
 
-static GemmPlan gemm_plan(int M, int Nn, int K, bool allow_split, bool allow_rows = true) {
+static GemmPlan gemm_plan(int M, int Nn, int K, bool allow_split) {
     GemmPlan p{};
     p.variant = g_gemm_variant;
     if (p.variant == 0) {
@@ -645,18 +635,12 @@ static GemmPlan gemm_plan(int M, int Nn, int K, bool allow_split, bool allow_row
     p.tiles_m = (M + bm - 1) / bm;
     p.tiles_n = (Nn + bn - 1) / bn;
     const int tiles = p.tiles_m * p.tiles_n;
-    p.full = tiles; p.nsplit = 1; p.rsplit = 1; p.pieces = 0; p.ws_bytes = 0;
+    p.full = tiles; p.nsplit = 1; p.pieces = 0; p.ws_bytes = 0;
     // the last partial round: split along K if the partial sums (two passes over tile-size fp32 per piece) and
     // the second launch cost less than the round they save -- measured at 17776 tokens: true for the 128x128
     // tile with a long K (fc2: 0.62 -> 0.57 ms), not for K = 1920 (0.188 -> 0.196 ms) nor for the 256x256 tile
     const int slots = gemm_compute_units() * (big ? 1 : 2);
     const int tail = tiles % slots, nk = K / 64;
-    // the wide tile: the tiles of the last partial round are computed by two workgroups each (upper and lower
-    // half of the rows) when that fits the slots, which roughly halves the round
-    if (allow_rows && p.variant == 1 && tail > 0 && 2 * tail <= slots && tiles > slots) {
-        p.full = tiles - tail; p.rsplit = 2; p.pieces = 2 * tail;
-        return p;
-    }
     if (allow_split && !big && K >= 4096 && tail > 0 && tiles > slots) {
         int ns = slots / tail;
         if (ns > 8) ns = 8;
@@ -679,9 +663,9 @@ static hipError_t launch_kind(const bf16_t* A, const bf16_t* W, bf16_t* C, int M
                               const Epilogue& ep, hipStream_t st) {
     dim3 block(WR * WC * 64);
     gemm_mfma_kernel<BM, BN, WR, WC, BK, NST, KIND><<<p.full + p.pieces, block, 0, st>>>(A, W, C, M, Nn, K, p.tiles_m, p.tiles_n,
-                                                                                p.full, p.nsplit, p.rsplit, ep);
+                                                                                p.full, p.nsplit, ep);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || p.pieces == 0 || p.rsplit != 1) return e;
+    if (e != hipSuccess || p.pieces == 0) return e;
     gemm_tail_kernel<BM, BN, WR, WC, KIND><<<p.pieces / p.nsplit, block, 0, st>>>(C, M, Nn, p.tiles_m, p.tiles_n, p.full,
                                                                                   p.nsplit, ep);
     return hipGetLastError();
@@ -703,8 +687,8 @@ static hipError_t launch_tile(const bf16_t* A, const bf16_t* W, bf16_t* C, int M
 hipError_t launch_gemm_mfma(const bf16_t* A, const bf16_t* W, bf16_t* C, int M, int Nn, int K,
                             const Epilogue& ep, hipStream_t st) {
     const bool tails = (get_kernel_path() & 0xff) != 4;
-    GemmPlan p = gemm_plan(M, Nn, K, ep.split_ws != nullptr && tails, tails);
-    if (p.ws_bytes > ep.split_ws_bytes) p = gemm_plan(M, Nn, K, false, tails);
+    GemmPlan p = gemm_plan(M, Nn, K, ep.split_ws != nullptr && tails);
+    if (p.ws_bytes > ep.split_ws_bytes) p = gemm_plan(M, Nn, K, false);
     switch (p.variant) {
         case 1: return launch_tile<256, 256, 2, 4, 64, 2>(A, W, C, M, Nn, K, p, ep, st);   // 8 waves, 128x64 each
         case 2: return launch_tile<128, 128, 2, 2, 64, 2>(A, W, C, M, Nn, K, p, ep, st);   // 4 waves, 64x64 each, 2 per CU
