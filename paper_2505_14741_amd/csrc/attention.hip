@@ -301,11 +301,12 @@ attn_merge_kernel(const float* __restrict__ part, bf16_t* __restrict__ o, int se
     attn_merge_rows(blockIdx.x, part, o, seq, heads, qblocks, full_blocks, nsplit, nitems, cexp, bq, s, bounds);
 }
 
-// Merge work appended to a launch of attn_mfma_kernel: workgroups from `first` on merge the pieces another,
-// earlier launch left in `part` (blocks == 0: none).
+// Merge work that rides on a launch of attn_mfma_kernel: its first `blocks` workgroups merge the pieces another,
+// earlier launch left in `part` (blocks == 0: none); the items follow.  (In front, because where every head is
+// bounded the item workgroups exit at once and the merge is all the launch does.)
 struct MergeTail {
     const float* part;
-    int first, blocks, full_blocks, nsplit, nitems, bq;
+    int blocks, full_blocks, nsplit, nitems, bq;
     float cexp;
 };
 
@@ -345,8 +346,8 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
                  bf16_t* __restrict__ o, int seq, int heads, float scale_log2e, int qblocks, AttnStrides s,
                  int full_blocks, int nsplit, float* __restrict__ part, const float* __restrict__ bounds,
                  MergeTail mt) {
-    if (mt.blocks != 0 && (int)blockIdx.x >= mt.first) {    // whole workgroup: before any barrier
-        attn_merge_rows(blockIdx.x - mt.first, mt.part, o, seq, heads, qblocks, mt.full_blocks, mt.nsplit, mt.nitems,
+    if ((int)blockIdx.x < mt.blocks) {                      // whole workgroup: before any barrier
+        attn_merge_rows(blockIdx.x, mt.part, o, seq, heads, qblocks, mt.full_blocks, mt.nsplit, mt.nitems,
                         mt.cexp, mt.bq, s, bounds);
         return;
     }
@@ -365,7 +366,7 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
     // The remaining items -- fewer than half a round of the chip's workgroup slots -- are each
     // split nsplit ways along the keys, so the last round costs 1/nsplit of a full one; such
     // a workgroup leaves unnormalised sums, row sum and reference in `part` for the merge kernel.
-    int id = blockIdx.x;
+    int id = blockIdx.x - mt.blocks;
     int piece = -1, jt0 = 0, jt1 = (seq + KV - 1) / KV;
     if (id < full_blocks) {
         int per = full_blocks / 8, rem = full_blocks % 8, x = id % 8, j = id / 8;
@@ -1061,10 +1062,11 @@ hipError_t launch_attention(int dtype, const void* q, const void* k, const void*
                 attn_sp_kernel<false><<<p.full + p.pieces, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c, p.qblocks,
                                                                          s, p.full, p.nsplit, part, bounds);
             // then the reference-tracking kernel (unsplit) for the other heads; the merge of attn_sp_kernel's pieces
-            // rides on that launch as workgroups after the items
+            // rides on that launch as workgroups in front of the items
             const int nitems = p.items - p.full;
-            MergeTail mt{part, p.items, 0, p.full, p.nsplit, nitems, bq, cexp};
-            if (p.pieces != 0) mt.blocks = (int)(((long)nitems * bq * 16 + 255) / 256);
+            MergeTail mt{part, 0, p.full, p.nsplit, nitems, bq, cexp};
+            // (a multiple of 8 workgroups, so that the items keep their place in the round-robin over the 8 XCDs)
+            if (p.pieces != 0) mt.blocks = ((int)(((long)nitems * bq * 16 + 255) / 256) + 7) & ~7;
             if (q_prescaled)
                 attn_mfma_kernel<2, true><<<p.items + mt.blocks, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c,
                                                                               p.qblocks, s, p.items, 1, nullptr, bounds, mt);
@@ -1075,7 +1077,7 @@ hipError_t launch_attention(int dtype, const void* q, const void* k, const void*
         }
         // (one 32-query tile per wave, i.e. 128-query workgroups at three per CU, measured 9 % slower:
         // it doubles the K/V traffic into LDS and the fragment reads per MFMA)
-        const MergeTail none{nullptr, 0, 0, 0, 0, 0, 0, 0.f};
+        const MergeTail none{nullptr, 0, 0, 0, 0, 0, 0.f};
         if (q_prescaled)
             attn_mfma_kernel<2, true><<<p.full + p.pieces, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c, p.qblocks,
                                                                          s, p.full, p.nsplit, part, nullptr, none);
