@@ -558,19 +558,20 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
 }
 
 // Sums the K-split pieces of the tail tiles (fixed order: deterministic) and applies the epilogue; one
-// workgroup per tail tile, same wave layout as gemm_mfma_kernel.
+// single-wave workgroup per wave of gemm_mfma_kernel's layout (the few tail tiles then spread over four times
+// as many compute units: the kernel is a chain of dependent loads).
 template <int BM, int BN, int WR, int WC, int KIND>
-__global__ void __launch_bounds__(WR * WC * 64)
+__global__ void __launch_bounds__(64)
 gemm_tail_kernel(bf16_t* __restrict__ C, int M, int Nn, int tiles_m, int tiles_n, int full_tiles, int nsplit,
                  Epilogue ep) {
     constexpr int NW = WR * WC;
     constexpr int WM = BM / WR, WN = BN / WC;
     constexpr int TM = WM / 32, TN = WN / 32;
-    __shared__ __attribute__((aligned(16))) float patches[NW * EPI_LDS_FLOATS];
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    __shared__ __attribute__((aligned(16))) float patch[EPI_LDS_FLOATS];
+    const int lane = threadIdx.x;
+    const int wave = blockIdx.x % NW, tail = blockIdx.x / NW;
     const int wm = wave / WC, wn = wave % WC;
-    const int tile = full_tiles + blockIdx.x;
+    const int tile = full_tiles + tail;
     int m0, n0;
     {
         constexpr int GM = 8;
@@ -588,7 +589,7 @@ gemm_tail_kernel(bf16_t* __restrict__ C, int M, int Nn, int tiles_m, int tiles_n
 #pragma unroll
             for (int q = 0; q < 4; ++q) acc[i][j][q] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     for (int pi = 0; pi < nsplit; ++pi) {
-        const float* pp = ep.split_ws + ((((long)blockIdx.x * nsplit + pi) * NW + wave) * (TM * TN) * 64 + lane) * 16;
+        const float* pp = ep.split_ws + ((((long)tail * nsplit + pi) * NW + wave) * (TM * TN) * 64 + lane) * 16;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -597,10 +598,9 @@ gemm_tail_kernel(bf16_t* __restrict__ C, int M, int Nn, int tiles_m, int tiles_n
                 for (int q = 0; q < 4; ++q)
                     acc[i][j][q] += *reinterpret_cast<const f32x4_t*>(pp + (i * TN + j) * 64 * 16 + q * 4);
     }
-    wave_epilogue<TM, TN, 0, KIND, true>(acc, ep, C, M, Nn, m0 + wm * WM, n0 + wn * WN, lane, patches + wave * EPI_LDS_FLOATS);
+    wave_epilogue<TM, TN, 0, KIND, true>(acc, ep, C, M, Nn, m0 + wm * WM, n0 + wn * WN, lane, patch);
     if constexpr (TN == 4)
-        wave_epilogue<TM, TN, 2, KIND, true>(acc, ep, C, M, Nn, m0 + wm * WM, n0 + wn * WN + 64, lane,
-                                             patches + wave * EPI_LDS_FLOATS);
+        wave_epilogue<TM, TN, 2, KIND, true>(acc, ep, C, M, Nn, m0 + wm * WM, n0 + wn * WN + 64, lane, patch);
 }
 
 bool gemm_mfma_supported(int M, int Nn, int K) {
@@ -666,7 +666,7 @@ static hipError_t launch_kind(const bf16_t* A, const bf16_t* W, bf16_t* C, int M
                                                                                 p.full, p.nsplit, ep);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.pieces == 0) return e;
-    gemm_tail_kernel<BM, BN, WR, WC, KIND><<<p.pieces / p.nsplit, block, 0, st>>>(C, M, Nn, p.tiles_m, p.tiles_n, p.full,
+    gemm_tail_kernel<BM, BN, WR, WC, KIND><<<p.pieces / p.nsplit * (WR * WC), 64, 0, st>>>(C, M, Nn, p.tiles_m, p.tiles_n, p.full,
                                                                                   p.nsplit, ep);
     return hipGetLastError();
 }
