@@ -102,7 +102,7 @@ PS_API int dit_forward(dit* d, const float* x, const void* ctx, const int32_t* t
  * recorded events and returns accumulated milliseconds and launch counts since the
  * last dit_profile_enable(d, on > 0); both arrays are HOST [7].
  * on: 0 off, 1 every class (two events per launch: about 1.5 % of a 30-layer forward at
- * 17776 tokens), 2 the attention class only (0.15 %); other values: PS_ERR_SHAPE. */
+ * 17776 tokens), 2 the attention class only (0.3 %); other values: PS_ERR_SHAPE. */
 PS_API int dit_profile_enable(dit* d, int on);
 PS_API int dit_profile_read(dit* d, double* ms_out, int64_t* launches_out);
 
