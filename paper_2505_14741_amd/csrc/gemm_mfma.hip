@@ -139,6 +139,8 @@ __device__ __forceinline__ void wave_epilogue(f32x4_t (&acc)[TM][TN][4], const E
             if (rot && n >= text) {
                 // video token -> (frame, patch row, patch column); the quotients come from a float multiply and one
                 // correction step (exact below 2^22 tokens per sample), then two 8-byte reads of the per-axis table
+                // (measured no faster: a copy of the table in LDS and the rows' packed positions computed once per
+                // tile, so that this lambda needs neither global loads nor the quotients)
                 const int nv = n - text;
                 int q1 = (int)((float)nv * inv_wp);
                 q1 += (q1 + 1) * ep.rope_Wp <= nv ? 1 : 0;
