@@ -45,6 +45,20 @@ __device__ __forceinline__ int xcd_remap(int id, int total) {
     return x * per + (x < rem ? x : rem) + j;
 }
 
+// Tile id -> first row and column of the tile.  Tiles walk down the 8 tile rows of a band, column after column, so
+// the workgroups resident on one XCD (a contiguous range of ids, about one band) cover a compact block of the
+// output and reuse each other's panels in L2.  Each band starts its walk a few columns further on than the one
+// before: the XCDs then do not all ask for the same W panel at the same moment (fc1 at 17776 tokens: 8-15 us
+// faster inside the network, the other shapes unchanged; larger steps slowed the K-split tail of fc2 down).
+__device__ __forceinline__ void tile_origin(int tile, int tiles_m, int tiles_n, int bm, int bn, int& m0, int& n0) {
+    constexpr int GM = 8;
+    const int per_band = GM * tiles_n;
+    const int band = tile / per_band, in_band = tile % per_band;
+    const int rows_here = min(GM, tiles_m - band * GM);
+    m0 = (band * GM + in_band % rows_here) * bm;
+    n0 = ((in_band / rows_here + band * max(1, tiles_n / 8)) % tiles_n) * bn;
+}
+
 // tanh-form GELU written as x * sigmoid(2u), u = sqrt(2/pi)(x + 0.044715 x^3): two
 // transcendentals and four FMAs; used where the result is rounded to bf16.
 __device__ __forceinline__ float gelu_fast(float x) {
@@ -529,8 +543,6 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, const bf
 // narrow tile where K is long).  (Dropped: two workgroups per tail tile of the wide tile, one per half of its rows.
 // With operands resident in the cache from the previous launch it was 2 % faster; with weights and activations
 // that change from call to call, as in the network, 1-4 % slower -- each half loads the whole W panel again.)
-// Tiles walk column-fastest inside bands of 8 tile rows, so the workgroups resident on one XCD cover a compact
-// block of the output and reuse each other's panels in L2.
 template <int BM, int BN, int WR, int WC, int BK, int NST, int KIND>
 __global__ void __launch_bounds__(WR * WC * 64, (WR * WC == 4 && BM * BN <= 128 * 128) ? 2 : 1)
 gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf16_t* __restrict__ C,
@@ -548,14 +560,7 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
         k1 = nk * (pi + 1) / nsplit;
     }
     int m0, n0;
-    {
-        constexpr int GM = 8;
-        int per_band = GM * tiles_n;
-        int band = tile / per_band, in_band = tile % per_band;
-        int rows_here = min(GM, tiles_m - band * GM);
-        m0 = (band * GM + in_band % rows_here) * BM;
-        n0 = (in_band / rows_here) * BN;
-    }
+    tile_origin(tile, tiles_m, tiles_n, BM, BN, m0, n0);
     gemm_tile<BM, BN, WR, WC, BK, NST, KIND>(A, W, C, M, Nn, K, m0, n0, k0, k1, piece, ep, lds);
 }
 
@@ -575,14 +580,7 @@ gemm_tail_kernel(bf16_t* __restrict__ C, int M, int Nn, int tiles_m, int tiles_n
     const int wm = wave / WC, wn = wave % WC;
     const int tile = full_tiles + tail;
     int m0, n0;
-    {
-        constexpr int GM = 8;
-        int per_band = GM * tiles_n;
-        int band = tile / per_band, in_band = tile % per_band;
-        int rows_here = min(GM, tiles_m - band * GM);
-        m0 = (band * GM + in_band % rows_here) * BM;
-        n0 = (in_band / rows_here) * BN;
-    }
+    tile_origin(tile, tiles_m, tiles_n, BM, BN, m0, n0);
     f32x4_t acc[TM][TN][4];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
