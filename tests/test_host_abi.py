@@ -249,3 +249,32 @@ def test_inputs_are_reproducible_and_bf16_exact():
                                                          "W_mod.0", "b_mod.0"]
     assert cfg.tokens == 16 + 2 * 6 * 8 and I.CONFIGS["full"].tokens == 17776 and I.CONFIGS["long"].tokens == 33976
     assert I.CONFIGS["block"].tokens == 4516 and I.CONFIGS["full"].latent_elems == 1123200
+
+
+def test_binding_fails_loudly_without_the_built_library(monkeypatch):
+    """No fallback: with the shared library missing the binding raises instead of computing anything."""
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "_LIB_PATH", os.path.join(ROOT, "paper_2505_14741_amd", "no_such_library.so"))
+    with pytest.raises(RuntimeError, match="missing"):
+        B.lib()
+    with pytest.raises(RuntimeError, match="missing"):
+        B.ddim_coefficients(4)
+
+
+def test_the_product_never_imports_the_oracle():
+    """The oracle is test infrastructure: nothing under the package imports or includes it."""
+    pkg = os.path.join(ROOT, "paper_2505_14741_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(from|import)\s+oracle|import_module\(.oracle|#include.*oracle", text, flags=re.M), \
+                    os.path.join(dirpath, f)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr
