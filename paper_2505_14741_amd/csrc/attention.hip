@@ -909,6 +909,7 @@ attn_sp_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const
         const int slot = (j - jt0) & (NST - 1);
         const bool mask = LAST && (j + 1) * KV > seq;
         // tile j+1 has landed (own share), for every wave after the barrier; the slot of tile j-2 is free
+        // (the barrier costs 0.5 % of the kernel: timed once without it)
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         issue(j + 2);
