@@ -286,6 +286,27 @@ def test_reduced_30_layer_reuse_run_bf16():
     assert torch.equal(x0again, x0)
 
 
+def test_step_batched_round_at_full_shape_agrees_with_one_call_per_step():
+    """30 layers at 17776 tokens: one warm-up step and one cycle of four, as four calls and as one call of batch 4.
+
+    At this shape the batch moves the projections' and the attention's last partial round (whose tiles are summed in
+    pieces), so the two runs agree to rounding rather than bit for bit; the per-step sums agree likewise.
+    """
+    print("sampler_run full shape, cycle of four, batched against unbatched", flush=True)
+    cfg = I.CONFIGS["full"]
+    _, W, d = setup("full", "std002")
+    x_T = dev(I.make_latent(cfg, 1))
+    ctx = dev(I.make_context(cfg, 1), torch.bfloat16)
+    x0a, sa, ca = gpu_run(d, x_T, ctx, 5, 1, [4], batched=False)
+    x0b, sb, cb = gpu_run(d, x_T, ctx, 5, 1, [4], batched=True)
+    assert ca == 5 and cb == 2
+    assert bool(torch.isfinite(x0a).all()) and bool(torch.isfinite(x0b).all())
+    r = float(host(B.rel_mae(x0b, x0a))[2])
+    print(f"  rel-MAE between the two runs {r:.3e}", flush=True)
+    assert r <= 2e-3
+    np.testing.assert_allclose(host(sb), host(sa), rtol=2e-3, atol=1e-6)
+
+
 # ------------------------------------------------- trajectories, deviation curves, other schedulers
 @pytest.mark.parametrize("batched", [False, True])
 def test_trajectory_output_matches_oracle_step_by_step(batched):
