@@ -368,3 +368,30 @@ def test_other_schedulers_run_matches_oracle(kind):
     close_fp32(host(x0)[0], ref["x0"])
     s = host(sums)
     np.testing.assert_allclose(s[:, 0] / s[:, 1], ref["rx"], rtol=1e-4)
+
+
+def test_bench_prints_one_json_line_with_the_agreed_fields():
+    """bench.py (one step, no CPU leg) as a child process: one JSON line, the contract's keys, sane values."""
+    import json
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    print("bench.py --steps 1 --warmup 1 --no-cpu-baseline", flush=True)
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--steps", "1", "--warmup", "1",
+                        "--no-cpu-baseline"], capture_output=True, text=True, timeout=170)
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [l for l in r.stdout.splitlines() if l.startswith("{")]
+    assert len(lines) == 1
+    out = json.loads(lines[0])
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                "vs_baseline", "dtype", "data", "config", "roofline"):
+        assert key in out, key
+    assert out["n_gpus"] == 1 and out["steps"] == 1 and out["unit"] == "ms" and out["higher_is_better"] is False
+    assert out["vs_baseline"] is None and out["dtype"] == "bf16" and out["data"] == "synthetic"
+    assert "workload" in out["config"] and "model" not in out["config"]
+    roof = out["roofline"]
+    assert roof["bound"] == "mfma" and roof["unit"] == "TFLOP/s" and roof["peak"] == 2500.0
+    assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-3
+    assert roof["launches"] == 30 and 0.2 < roof["frac"] < 1.0
+    assert 30.0 < out["value"] < 1000.0
