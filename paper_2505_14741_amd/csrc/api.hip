@@ -83,10 +83,12 @@ struct Prof {
         *stop = nullptr;
         if (!d->profiling || (d->profiling == 2 && cls != KC_ATTN)) return hipSuccess;
         if (d->ev_used + 2 > d->ev.size()) {
+            // timing-only events: without the system-scope fence (cache write-back and invalidation) an event
+            // otherwise performs when it is recorded, which delays the launch that follows
             hipEvent_t a, b;
-            hipError_t e = hipEventCreate(&a);
+            hipError_t e = hipEventCreateWithFlags(&a, hipEventDisableSystemFence);
             if (e != hipSuccess) return e;
-            e = hipEventCreate(&b);
+            e = hipEventCreateWithFlags(&b, hipEventDisableSystemFence);
             if (e != hipSuccess) { hipEventDestroy(a); return e; }
             d->ev.push_back(a);
             d->ev.push_back(b);
