@@ -152,14 +152,16 @@ PS_API int ps_set_kernel_path(int path);
  * in fp32 on the increment  d = (a-1)*x + b*eps,  x_out = x + d,  sum|x_out-x| = sum|d|,
  * with (a-1) rounded to fp32 only after the subtraction.
  * x_out may alias x.  workspace: DEVICE, >= sampler_step_workspace_bytes(n), only
- * needed when sums4 != NULL. */
+ * needed when sums4 != NULL.  n may be 0: x, eps and x_out are then not looked at (NULL
+ * is accepted) and the sums are zero. */
 PS_API size_t sampler_step_workspace_bytes(size_t n);
 PS_API int sampler_step(const float* x, const float* eps, const float* eps_prev, float* x_out,
                  double a, double b, size_t n, float* sums4,
                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Relative MAE of Eq. (1): out3 = { sum|a-b|, sum|a|, sum|a-b| / sum|a| } (DEVICE fp32).
- * The denominator is the FIRST argument; a zero denominator yields inf or nan. */
+ * The denominator is the FIRST argument; a zero denominator yields inf or nan.
+ * n may be 0 (a and b are then not looked at, NULL is accepted): { 0, 0, nan }. */
 PS_API size_t rel_mae_workspace_bytes(size_t n);
 PS_API int rel_mae(const float* a, const float* b, size_t n, float* out3,
             void* workspace, size_t workspace_bytes, void* hip_stream);

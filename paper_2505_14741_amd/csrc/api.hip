@@ -415,10 +415,10 @@ size_t rel_mae_workspace_bytes(size_t n) { return align256(reduce_workspace_byte
 
 int sampler_step(const float* x, const float* eps, const float* eps_prev, float* x_out, double a, double b,
                  size_t n, float* sums4, void* workspace, size_t workspace_bytes, void* hip_stream) {
-    if (!x || !eps || !x_out) return PS_ERR_NULL;
+    if (n > 0 && (!x || !eps || !x_out)) return PS_ERR_NULL;      // an empty input has nothing to point at
     if (!aligned(x, 16) || !aligned(eps, 16) || !aligned(x_out, 16) || (eps_prev && !aligned(eps_prev, 16)))
         return PS_ERR_SHAPE;
-    if (eps == x_out || (eps_prev && eps_prev == x_out)) return PS_ERR_SHAPE;
+    if (n > 0 && (eps == x_out || (eps_prev && eps_prev == x_out))) return PS_ERR_SHAPE;
     if (sums4 && (!workspace || !aligned(workspace, 256) || workspace_bytes < sampler_step_workspace_bytes(n)))
         return PS_ERR_WORKSPACE;
     hipError_t e = launch_sampler_step(x, eps, eps_prev, x_out, a, b, n, sums4, workspace, (hipStream_t)hip_stream);
@@ -427,7 +427,7 @@ int sampler_step(const float* x, const float* eps, const float* eps_prev, float*
 
 int rel_mae(const float* a, const float* b, size_t n, float* out3, void* workspace, size_t workspace_bytes,
             void* hip_stream) {
-    if (!a || !b || !out3) return PS_ERR_NULL;
+    if (!out3 || (n > 0 && (!a || !b))) return PS_ERR_NULL;
     if (!aligned(a, 16) || !aligned(b, 16)) return PS_ERR_SHAPE;
     if (!workspace || !aligned(workspace, 256) || workspace_bytes < rel_mae_workspace_bytes(n)) return PS_ERR_WORKSPACE;
     hipError_t e = launch_rel_mae(a, b, n, out3, workspace, (hipStream_t)hip_stream);

@@ -132,6 +132,21 @@ def test_rel_mae_closed_forms_and_zero_denominator():
     assert math.isinf(host(B.rel_mae(z, torch.ones_like(z)))[2])
 
 
+def test_sampler_step_and_rel_mae_on_empty_inputs():
+    """n = 0: nothing is read or written, the sums are zero, the ratio is the oracle's 0/0."""
+    print("sampler_step / rel_mae n=0", flush=True)
+    buf = torch.full((8,), 3.0, device=DEV)
+    x, e, p = buf[:0], buf[4:4], buf[4:4]
+    out = torch.full((8,), 7.0, device=DEV)
+    _, sums = B.sampler_step(x, e, p, 0.9, 0.1, x_out=out[:0])
+    torch.cuda.synchronize()
+    assert host(sums).tolist() == [0.0, 0.0, 0.0, 0.0]
+    assert bool((out == 7.0).all()) and bool((buf == 3.0).all())
+    got = host(B.rel_mae(x, e))
+    num, den, ratio = O.rel_mae(np.zeros(0), np.zeros(0))
+    assert got[0] == num == 0.0 and got[1] == den == 0.0 and math.isnan(got[2]) and math.isnan(ratio)
+
+
 # ---------------------------------------------------------------------------------- attn3d
 @pytest.mark.parametrize("d", [16, 32, 64])
 @pytest.mark.parametrize("N", [1, 63, 64, 65, 127, 129, 300])
