@@ -323,7 +323,8 @@ def expand_cycles(steps: int, warmup: int, cycle_len: Sequence[int]) -> List[int
 
 def run_sampler(predict: Callable, x_T, tau, a, b, warmup: int, cycle_len: Sequence[int],
                 mode: str = "reuse_then_predict", trace: Optional[list] = None,
-                reuse_trace: Optional[list] = None):
+                reuse_trace: Optional[list] = None, state: Optional[dict] = None,
+                stop: Optional[int] = None):
     """Denoising loop of Algorithm 1 with every rank simulated on one host.
 
     predict(x, tau) -> eps is the noise predictor for one sample.  Every rank r keeps
@@ -349,6 +350,12 @@ def run_sampler(predict: Callable, x_T, tau, a, b, warmup: int, cycle_len: Seque
     `trace`, if a list, receives (step, evaluating rank or -1, rank whose eps rank 0
     applies) tuples; `reuse_trace`, if a list, receives (step, rank, step at which the
     eps that rank reuses was predicted) for every reuse update of a non-root rank.
+
+    A run in pieces: `stop` ends the loop after step stop-1, and the returned dict's
+    "state" holds what Algorithm 1 carries from one step to the next -- the step count,
+    cycle and round, every rank's sample and eps_cache, and the last applied eps (for the
+    adjacent-step relative MAE); passing it back as `state` continues from there.  The
+    lists then cover the steps of that piece only.
     """
     S = len(tau)
     if mode not in ("reuse_then_predict", "direct_reuse", "latest_eps"):
@@ -363,7 +370,15 @@ def run_sampler(predict: Callable, x_T, tau, a, b, warmup: int, cycle_len: Seque
     xs, eps_used, rx, re = [], [], [], []
     calls = 0
     cyc, rnd = 0, 0
-    for i in range(S):
+    first, eps_last = 0, None
+    if state is not None:
+        first, cyc, rnd, calls = state["step"], state["cycle"], state["round"], state["calls"]
+        x = [v.copy() for v in state["x"]]
+        cache = [None if v is None else v.copy() for v in state["cache"]]
+        born = list(state["born"])
+        eps_last = state["eps_last"]
+    last = S if stop is None else stop
+    for i in range(first, last):
         x_before = x[0]
         if i < warmup:
             e = predict(x[0], int(tau[i]))
@@ -411,9 +426,13 @@ def run_sampler(predict: Callable, x_T, tau, a, b, warmup: int, cycle_len: Seque
                 rnd += 1
         xs.append(x[0].copy())
         rx.append(rel_mae(x[0], x_before)[2])
-        re.append(rel_mae(applied, eps_used[-1])[2] if eps_used else float("nan"))
-        eps_used.append(np.asarray(applied, dtype=F64).copy())
-    return dict(x0=x[0], xs=xs, eps=eps_used, rx=rx, re=re, calls=calls)
+        re.append(rel_mae(applied, eps_last)[2] if eps_last is not None else float("nan"))
+        eps_last = np.asarray(applied, dtype=F64).copy()
+        eps_used.append(eps_last)
+    out_state = dict(step=last, cycle=cyc, round=rnd, calls=calls, x=[v.copy() for v in x],
+                     cache=[None if v is None else np.asarray(v, dtype=F64).copy() for v in cache],
+                     born=list(born), eps_last=eps_last)
+    return dict(x0=x[0], xs=xs, eps=eps_used, rx=rx, re=re, calls=calls, state=out_state)
 
 
 def run_sampler_batched(predict_batch: Callable, x_T, tau, a, b, warmup: int,

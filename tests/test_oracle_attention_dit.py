@@ -272,3 +272,48 @@ def test_dit_query_rows_option_equals_the_whole_evaluation():
         assert np.isnan(pp[~listed]).all()
     with pytest.raises(AssertionError):
         O.dit_forward(I.CONFIGS["tiny_text"], _w(I.CONFIGS["tiny_text"], 11), x, ctx, t, query_rows=[0])
+
+
+def _shifted_angles(grid, d, offset):
+    """Angles of the tokens of `grid` placed at positions (f, i, j) + offset: a sub-block of a larger grid."""
+    F, Hp, Wp = grid
+    of, oi, oj = offset
+    big = (F + of, Hp + oi, Wp + oj)
+    ang = O.rope3d_angles(big, d).reshape(big + (d // 2,))
+    return ang[of:, oi:, oj:].reshape(F * Hp * Wp, d // 2)
+
+
+def test_constant_position_offset_leaves_attention_unchanged():
+    """With video tokens only, rotary logits depend on position differences: moving every token by the
+    same (frames, rows, columns) offset changes q and k but not softmax(q k^T) v."""
+    grid, H, d = (2, 3, 4), 2, 16
+    N = grid[0] * grid[1] * grid[2]
+    rng = np.random.default_rng(3)
+    q, k, v = (rng.standard_normal((N, H, d)) for _ in range(3))
+    a0 = O.rope3d_angles(grid, d)
+    np.testing.assert_allclose(_shifted_angles(grid, d, (0, 0, 0)), a0, rtol=0, atol=0)
+    base = O.attn3d(O.rope3d_apply(q, a0)[None], O.rope3d_apply(k, a0)[None], v[None], 0.25)
+    for offset in [(1, 0, 0), (0, 2, 0), (0, 0, 5), (3, 1, 2)]:
+        a1 = _shifted_angles(grid, d, offset)
+        assert np.abs(O.rope3d_apply(q, a1) - O.rope3d_apply(q, a0)).max() > 0.1      # q itself does change
+        moved = O.attn3d(O.rope3d_apply(q, a1)[None], O.rope3d_apply(k, a1)[None], v[None], 0.25)
+        np.testing.assert_allclose(moved, base, rtol=0, atol=1e-12)
+    # rotating only the queries by an offset is not neutral (the property is about differences)
+    a1 = _shifted_angles(grid, d, (1, 0, 0))
+    other = O.attn3d(O.rope3d_apply(q, a1)[None], O.rope3d_apply(k, a0)[None], v[None], 0.25)
+    assert np.abs(other - base).max() > 1e-3
+
+
+def test_permuting_video_tokens_with_their_positions_permutes_the_output():
+    """Attention has no order of its own: tokens permuted together with their rotary angles give the
+    permuted output; permuting the tokens but not the angles does not."""
+    grid, H, d = (2, 3, 4), 2, 16
+    N = grid[0] * grid[1] * grid[2]
+    rng = np.random.default_rng(4)
+    q, k, v = (rng.standard_normal((N, H, d)) for _ in range(3))
+    ang = O.rope3d_angles(grid, d)
+    perm = rng.permutation(N)
+    att = lambda q_, k_, v_, a_: O.attn3d(O.rope3d_apply(q_, a_)[None], O.rope3d_apply(k_, a_)[None], v_[None], 0.25)[0]
+    base = att(q, k, v, ang)
+    np.testing.assert_allclose(att(q[perm], k[perm], v[perm], ang[perm]), base[perm], rtol=0, atol=1e-12)
+    assert np.abs(att(q[perm], k[perm], v[perm], ang) - base[perm]).max() > 1e-3

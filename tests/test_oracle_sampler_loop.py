@@ -258,3 +258,52 @@ def test_critical_path_against_the_papers_bound_and_measurements():
             assert measured < S / O.critical_path_calls(S, m, p) + 1e-12, model
             rows += 1
     assert rows == 9
+
+
+@pytest.mark.parametrize("mode", ["reuse_then_predict", "latest_eps", "direct_reuse"])
+@pytest.mark.parametrize("S,m,cyc", [(7, 1, [3, 3]), (10, 1, [1, 2, 4, 2]), (8, 2, [2, 2, 2]), (6, 2, [3, 3])])
+def test_a_run_in_two_pieces_is_the_whole_run(mode, S, m, cyc):
+    """Stopping after any step and continuing from the returned state (step, cycle, round, every rank's
+    sample and eps_cache, last eps) reproduces the uninterrupted run bit for bit."""
+    tau, a, b = O.ddim_coefficients(steps=S)
+    xT = np.array([0.3, -1.1, 2.0, 0.7])
+    whole = O.run_sampler(scalar_predictor, xT, tau, a, b, m, cyc, mode=mode)
+    for k in range(1, S):
+        one = O.run_sampler(scalar_predictor, xT, tau, a, b, m, cyc, mode=mode, stop=k)
+        assert one["state"]["step"] == k and len(one["xs"]) == k
+        two = O.run_sampler(scalar_predictor, xT, tau, a, b, m, cyc, mode=mode, state=one["state"])
+        assert np.array_equal(two["x0"], whole["x0"])
+        assert one["calls"] <= two["calls"] == whole["calls"]          # (direct reuse: a piece may hold no prediction)
+        for got, ref in zip(one["xs"] + two["xs"], whole["xs"]):
+            assert np.array_equal(got, ref)
+        np.testing.assert_array_equal((one["rx"] + two["rx"]), whole["rx"])
+        np.testing.assert_array_equal((one["re"] + two["re"])[1:], whole["re"][1:])
+
+
+def test_the_state_between_steps_is_what_the_straight_line_script_holds():
+    """S=7, m=1, p=3 stopped after step 2 (middle of the first cycle) and after step 4 (second cycle):
+    the state's per-rank samples and caches against the loop-free script of
+    test_straight_line_script_S7_m1_p3."""
+    f = scalar_predictor
+    tau, a, b = O.ddim_coefficients(steps=7)
+    st = lambda i, x, e: a[i] * x + b[i] * e
+    xT = np.array([0.3, -1.1, 2.0])
+    e0 = f(xT, tau[0]);  X1 = st(0, xT, e0)
+    E1 = f(X1, tau[1]);  X2 = st(1, X1, E1);  Y2 = st(1, X1, e0);  Z2 = st(1, X1, e0)
+    E2 = f(Y2, tau[2]);  X3 = st(2, X2, E2);  Z3 = st(2, Z2, e0)
+    E3 = f(Z3, tau[3]);  X4 = st(3, X3, E3)
+    E4 = f(X4, tau[4]);  X5 = st(4, X4, E4);  Y5 = st(4, X4, E2);  Z5 = st(4, X4, E3)
+    s3 = O.run_sampler(f, xT, tau, a, b, 1, [3, 3], stop=3)["state"]
+    assert (s3["step"], s3["cycle"], s3["round"], s3["calls"]) == (3, 0, 2, 3)
+    np.testing.assert_allclose(s3["x"][0], X3, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(s3["x"][2], Z3, rtol=0, atol=1e-12)      # rank 2 has still to predict
+    np.testing.assert_allclose(s3["cache"][1], E2, rtol=0, atol=1e-12)  # rank 1 predicted at step 2
+    np.testing.assert_allclose(s3["cache"][2], e0, rtol=0, atol=1e-12)  # rank 2 still holds the warm-up eps
+    np.testing.assert_allclose(s3["eps_last"], E2, rtol=0, atol=1e-12)
+    s5 = O.run_sampler(f, xT, tau, a, b, 1, [3, 3], stop=5)["state"]
+    assert (s5["step"], s5["cycle"], s5["round"], s5["calls"]) == (5, 1, 1, 5)
+    for got, ref in zip(s5["x"], [X5, Y5, Z5]):
+        np.testing.assert_allclose(got, ref, rtol=0, atol=1e-12)
+    for got, ref in zip(s5["cache"], [E4, E2, E3]):
+        np.testing.assert_allclose(got, ref, rtol=0, atol=1e-12)
+    assert s5["born"] == [4, 2, 3]
