@@ -147,7 +147,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="full", choices=["full", "long", "block"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--kernel-path", type=lambda v: int(v, 0), default=0, help="tuning hook passed to ps_set_kernel_path")
+    ap.add_argument("--kernel-path", type=lambda v: int(v, 0), default=0, help="kernel path of the handle and of the stand-alone calls (see dit_set_kernel_path)")
     ap.add_argument("--kernel", default=None, choices=["attn3d", "dit_linear", "copy", "sampler_step"],
                     help="profiling target: launch only this kernel 3 times at the workload's shape and exit")
     ap.add_argument("--report", default=None, choices=["run50", "long_sweep", "step_batched"],
@@ -164,7 +164,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     B.lib()
     torch.cuda.set_device(0)
-    B.ps_set_kernel_path(args.kernel_path)
+    kpath = args.kernel_path
     cfg = I.CONFIGS[args.workload]
     N, D = cfg.tokens, cfg.hidden
     K, Wm = args.steps, args.warmup
@@ -176,7 +176,7 @@ def main():
                        for _ in range(3))
             o = torch.empty_like(q)
             for _ in range(3):
-                B.attn3d(q, k, v, cfg.head_dim ** -0.5, out=o)
+                B.attn3d(q, k, v, cfg.head_dim ** -0.5, out=o, kernel_path=kpath)
             what = {"kernel": "attn3d", "tokens": N, "heads": cfg.heads, "flop": 4.0 * N * N * D}
         elif args.kernel == "dit_linear":         # the four projection shapes of a layer (plain bias / GELU epilogues)
             shapes = [(3 * D, D, 0), (D, D, 0), (4 * D, D, 1), (D, 4 * D, 0)]
@@ -186,7 +186,7 @@ def main():
                 bias = torch.randn((nn,), generator=g, device="cuda")
                 out = torch.empty((N, nn), device="cuda", dtype=torch.bfloat16)
                 for _ in range(3):
-                    B.dit_linear(a, w, bias, act, out=out)
+                    B.dit_linear(a, w, bias, act, out=out, kernel_path=kpath)
             what = {"kernel": "dit_linear", "tokens": N, "shapes": shapes}
         elif args.kernel == "copy":               # plain copy of known size: scale for FETCH_SIZE / WRITE_SIZE
             n = 1 << 28
@@ -209,6 +209,7 @@ def main():
         return
 
     d = B.dit_create(cfg, device_weights(cfg, torch, 1003))
+    B.dit_set_kernel_path(d, kpath)
     g = torch.Generator(device="cuda"); g.manual_seed(42)
     x_T = torch.randn((1,) + cfg.latent_shape, generator=g, device="cuda")
     ctx = torch.randn((1, cfg.text_tokens, D), generator=g, device="cuda").to(torch.bfloat16)

@@ -19,7 +19,24 @@
  *    default stream) and the call returns without synchronising; outputs, including
  *    device-side sums, are valid once the caller has synchronised that stream;
  *  - results are deterministic: no floating-point atomics, fixed reduction order;
+ *  - a sample's result does not depend on the batch it is computed in: every sample of a
+ *    batch is tiled and summed exactly as if it were alone (Section 3.3: the batched step
+ *    must reproduce the per-step process), so dit_forward on B samples equals B calls bit
+ *    for bit (one caveat: which of two softmax kernels a head takes is decided from an
+ *    upper bound of its largest query and key norm that is formed per tile of rows; a head
+ *    within a factor 2 of that limit may be sent to the other kernel, whose result differs
+ *    in rounding);
+ *  - the library keeps no process-wide mutable state: kernels are selected per call from
+ *    the shapes and from the kernel path of the handle (dit_set_kernel_path) or of the
+ *    call (attn3d, dit_linear);
  *  - calls on one `dit` handle must not overlap; distinct handles/streams may.
+ *
+ * Shape limits (anything beyond them is PS_ERR_SHAPE at dit_create, never a slow or wrong
+ * path): layers <= 64, hidden <= 2048 and a multiple of 8, head_dim in {16, 32, 64},
+ * mlp_ratio <= 8, batch <= 16, in_channels*patch^2 <= 1024, at most 2^24 tokens per sample
+ * and, for bf16, tokens * hidden * max(mlp_ratio, 3) < 2^31.  The MFMA kernels serve bf16
+ * with K % 64 == 0 and at least 64 outputs (projections) and head_dim 64 (attention);
+ * every other accepted shape runs on generic fp32-FMA kernels.
  */
 #ifndef PARASTEP_H
 #define PARASTEP_H
@@ -84,6 +101,19 @@ PS_API int dit_num_weights(int layers);
 PS_API int dit_create(const dit_config* cfg, const void* const* weights, int n_weights, dit** out);
 PS_API int dit_destroy(dit* d);
 
+/* Kernel path of a handle (0 after dit_create), used by every later call on it.  Low byte = mode:
+ * 0 the fastest kernel for each shape, 1 the generic fp32-FMA kernels, 2 bf16 attention without
+ * the key split of its last partial round of workgroups, 3 bf16 head-dim-64 attention always
+ * through the kernel that tracks a softmax reference (no norm-bound shortcut), 4 projections whose
+ * last partial round of workgroups is not divided along k.  Bits 8-11: tile variant of the bf16
+ * MFMA projections (0 automatic, 1: 256x256, 2: 128x128, 3: 192x256, 4: 192x128); the variant
+ * decides which workgroup computes an output and, for k >= 4096, which outputs of the last partial
+ * round are summed in k pieces (a different rounding of those); nothing else.  Other values:
+ * PS_ERR_SHAPE.
+ * dit_workspace_bytes does not depend on the path. */
+PS_API int dit_set_kernel_path(dit* d, int path);
+PS_API int dit_get_kernel_path(const dit* d);    /* the handle's path, PS_ERR_NULL for NULL */
+
 /* Bytes of DEVICE workspace dit_forward needs for `batch` samples (0 on bad input). */
 PS_API size_t dit_workspace_bytes(const dit* d, int batch);
 
@@ -116,10 +146,11 @@ PS_API int dit_profile_read(dit* d, double* ms_out, int64_t* launches_out);
  * that is 0); scratch only.  It is non-zero for bf16 with head_dim 64: those kernels keep the
  * largest query and key norm of every (batch, head) there (heads whose scores are provably
  * bounded take a softmax without running maximum) and the partial sums of the workgroups
- * that split their keys in the last, partial round (merged by a second kernel). */
+ * that split their keys in the last, partial round (merged by a second kernel).
+ * kernel_path: as for dit_set_kernel_path (0 = default); the workspace size does not depend on it. */
 PS_API size_t attn3d_workspace_bytes(int batch, int seq, int heads, int head_dim, int dtype);
 PS_API int attn3d(const void* q, const void* k, const void* v, void* o,
-           int batch, int seq, int heads, int head_dim, float scale, int dtype,
+           int batch, int seq, int heads, int head_dim, float scale, int dtype, int kernel_path,
            void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* The projection every DiT sub-layer uses, exposed for per-kernel parity and timing:
@@ -130,18 +161,11 @@ PS_API int attn3d(const void* q, const void* k, const void* v, void* o,
  * dit_linear_workspace_bytes(...) of it, shapes whose output tiles do not fill the last round
  * of workgroups split those tiles along k (fp32 partial sums pass through the workspace and
  * are added in a fixed order); with NULL or less the call computes the same product unsplit.
- * The two differ only in summation order. */
-PS_API size_t dit_linear_workspace_bytes(int m, int n_out, int k, int dtype);
+ * The two differ only in summation order.
+ * kernel_path: as for dit_set_kernel_path (0 = default); it enters the workspace size. */
+PS_API size_t dit_linear_workspace_bytes(int m, int n_out, int k, int dtype, int kernel_path);
 PS_API int dit_linear(const void* a, const void* w, const float* bias, void* out, int m, int n_out, int k,
-               int act, int dtype, void* workspace, size_t workspace_bytes, void* hip_stream);
-
-/* Test and tuning hook: 0 = pick the fastest kernel for each shape (default), 1 = always
- * use the generic fp32-FMA kernels, 2 = bf16 attention without the key-split of its last
- * partial round of workgroups, 3 = bf16 head-dim-64 attention always through the kernel that
- * tracks a softmax reference (no norm-bound shortcut), 4 = projections whose last partial
- * round of workgroups is not divided along k, 0x100|v = force tile variant v of the
- * bf16 MFMA GEMM (1: 256x256, 2: 128x128).  Process-wide; returns the previous value. */
-PS_API int ps_set_kernel_path(int path);
+               int act, int dtype, int kernel_path, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* ------------------------------------------------------------- scheduler and metric
  * Fused DDIM update  x_out = a*x + b*eps  (the element-wise Scheduler of the paper's
@@ -228,6 +252,37 @@ PS_API size_t sampler_workspace_bytes(const dit* d, const sampler_schedule* s);
 PS_API int sampler_run(dit* d, const sampler_schedule* s, const float* x_T, const void* ctx,
                 float* x0_out, float* step_sums, float* trajectory_out, int* calls_out,
                 void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* ------------------------------------------------------------- a run in pieces (split / resume)
+ * What Algorithm 1 carries from one step to the next is the step count, the round within the
+ * cycle, and per rank its sample and its eps_cache (plus, for the adjacent-step sums, the eps of
+ * the last step).  sampler_run_steps advances a run from state->step to stop_step and leaves that
+ * state behind: the position in `state` (HOST, plain data) and the tensors in the first
+ * sampler_state_bytes(d, s) bytes of the workspace.  A run taken in pieces -- in one process with
+ * the workspace left alone in between, or in another process from a stored copy of the struct and
+ * of those bytes put at the head of a workspace of the same size, with the same schedule and
+ * weights -- is bit-identical to sampler_run's.
+ *   state      in/out.  step == 0 starts a run (the other fields are ignored and x_T is read);
+ *              otherwise it must be what an earlier call with this schedule left: a state whose
+ *              cycle, round or slots do not fit the schedule is PS_ERR_SCHEDULE
+ *   stop_step  state->step < stop_step <= steps.  With batched == 1 a cycle is one predictor call,
+ *              so a run can only pause inside warm-up or between cycles (else PS_ERR_SCHEDULE)
+ *   x_T        needed iff state->step == 0;  x_out (optional) receives rank 0's sample after
+ *              stop_step steps;  step_sums / trajectory_out as in sampler_run, rows
+ *              state->step .. stop_step-1 are written. */
+typedef struct {
+    int32_t step;       /* steps taken so far */
+    int32_t cycle;      /* cycle (after warm-up) and round within it at which the next step runs */
+    int32_t round;
+    int32_t toggle;     /* which of the two eps buffers rank 0's next prediction goes to */
+    int32_t eps_prev;   /* where the last step's eps lives: -1 nowhere yet, 0 / 1 eps buffer, 2 + r rank r's cache */
+    int32_t calls;      /* predictor launches so far */
+    int32_t src[16];    /* rank r's current sample is in sample slot src[r] (0 after a broadcast, else r) */
+} sampler_state;
+PS_API size_t sampler_state_bytes(const dit* d, const sampler_schedule* s);
+PS_API int sampler_run_steps(dit* d, const sampler_schedule* s, sampler_state* state, int stop_step,
+                      const float* x_T, const void* ctx, float* x_out, float* step_sums,
+                      float* trajectory_out, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 #ifdef __cplusplus
 }

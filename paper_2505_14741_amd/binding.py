@@ -42,6 +42,12 @@ class _Schedule(C.Structure):
                 ("cycle_len", C.POINTER(C.c_int32)), ("batched", C.c_int), ("mode", C.c_int)]
 
 
+class SamplerState(C.Structure):
+    """Host part of a run's state between two steps (`sampler_state`); plain data, may be stored."""
+    _fields_ = [("step", C.c_int32), ("cycle", C.c_int32), ("round", C.c_int32), ("toggle", C.c_int32),
+                ("eps_prev", C.c_int32), ("calls", C.c_int32), ("src", C.c_int32 * 16)]
+
+
 def lib():
     """Load the shared library once; fail loudly if it has not been built."""
     global _lib
@@ -53,7 +59,8 @@ def lib():
     vp, sz, i32, f32 = C.c_void_p, C.c_size_t, C.c_int, C.c_float
     sig = {
         "ps_strerror": (C.c_char_p, [i32]),
-        "ps_set_kernel_path": (i32, [i32]),
+        "dit_set_kernel_path": (i32, [vp, i32]),
+        "dit_get_kernel_path": (i32, [vp]),
         "dit_num_weights": (i32, [i32]),
         "dit_create": (i32, [C.POINTER(_DitConfig), C.POINTER(vp), i32, C.POINTER(vp)]),
         "dit_destroy": (i32, [vp]),
@@ -62,9 +69,9 @@ def lib():
         "dit_profile_enable": (i32, [vp, i32]),
         "dit_profile_read": (i32, [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
         "attn3d_workspace_bytes": (sz, [i32, i32, i32, i32, i32]),
-        "attn3d": (i32, [vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, vp, sz, vp]),
-        "dit_linear_workspace_bytes": (C.c_size_t, [i32, i32, i32, i32]),
-        "dit_linear": (i32, [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, C.c_size_t, vp]),
+        "attn3d": (i32, [vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, i32, vp, sz, vp]),
+        "dit_linear_workspace_bytes": (C.c_size_t, [i32, i32, i32, i32, i32]),
+        "dit_linear": (i32, [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, C.c_size_t, vp]),
         "sampler_step_workspace_bytes": (sz, [sz]),
         "sampler_step": (i32, [vp, vp, vp, vp, C.c_double, C.c_double, sz, vp, vp, sz, vp]),
         "rel_mae_workspace_bytes": (sz, [sz]),
@@ -76,6 +83,9 @@ def lib():
         "flow_euler_coefficients": (i32, [i32, i32, C.POINTER(C.c_int32), C.POINTER(C.c_double),
                                           C.POINTER(C.c_double)]),
         "sampler_workspace_bytes": (sz, [vp, C.POINTER(_Schedule)]),
+        "sampler_state_bytes": (sz, [vp, C.POINTER(_Schedule)]),
+        "sampler_run_steps": (i32, [vp, C.POINTER(_Schedule), C.POINTER(SamplerState), i32, vp, vp, vp, vp, vp, vp, sz,
+                                    vp]),
         "sampler_run": (i32, [vp, C.POINTER(_Schedule), vp, vp, vp, vp, vp, C.POINTER(i32), vp, sz, vp]),
     }
     for name, (res, args) in sig.items():
@@ -85,11 +95,12 @@ def lib():
     return L
 
 
-EXPORTED = ("ps_strerror", "ps_set_kernel_path", "dit_num_weights", "dit_create", "dit_destroy",
+EXPORTED = ("ps_strerror", "dit_set_kernel_path", "dit_get_kernel_path", "dit_num_weights", "dit_create", "dit_destroy",
             "dit_workspace_bytes", "dit_forward", "dit_profile_enable", "dit_profile_read",
             "attn3d_workspace_bytes", "attn3d", "dit_linear_workspace_bytes", "dit_linear", "sampler_step_workspace_bytes", "sampler_step",
             "rel_mae_workspace_bytes", "rel_mae", "ddim_coefficients", "euler_discrete_coefficients",
-            "flow_euler_coefficients", "sampler_workspace_bytes", "sampler_run")
+            "flow_euler_coefficients", "sampler_workspace_bytes", "sampler_run", "sampler_state_bytes",
+            "sampler_run_steps")
 
 
 def _check(status: int, where: str):
@@ -117,10 +128,6 @@ def _workspace(nbytes: int, device) -> Optional[torch.Tensor]:
     if nbytes == 0:
         return None
     return torch.empty(nbytes, dtype=torch.uint8, device=device)
-
-
-def ps_set_kernel_path(path: int) -> int:
-    return lib().ps_set_kernel_path(int(path))
 
 
 # ---------------------------------------------------------------------------- predictor
@@ -164,6 +171,10 @@ def dit_create(cfg: DiTConfig, weights: Sequence[torch.Tensor]) -> Dit:
     return Dit(cfg, weights)
 
 
+def dit_set_kernel_path(d: Dit, path: int):
+    _check(lib().dit_set_kernel_path(d.handle, int(path)), "dit_set_kernel_path")
+
+
 def dit_forward(d: Dit, x: torch.Tensor, ctx: Optional[torch.Tensor], t: Sequence[int],
                 eps_out: Optional[torch.Tensor] = None) -> torch.Tensor:
     B = x.shape[0]
@@ -190,29 +201,29 @@ def dit_profile_read(d: Dit):
 
 # ---------------------------------------------------------------------------- attention
 def attn3d(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, scale: float,
-           out: Optional[torch.Tensor] = None) -> torch.Tensor:
+           out: Optional[torch.Tensor] = None, kernel_path: int = 0) -> torch.Tensor:
     B, N, H, d = q.shape
     dt = PS_BF16 if q.dtype == torch.bfloat16 else PS_F32
     if out is None:
         out = torch.empty_like(q)
     n = lib().attn3d_workspace_bytes(B, N, H, d, dt)
     ws = _workspace(n, q.device)
-    _check(lib().attn3d(_ptr(q), _ptr(k), _ptr(v), _ptr(out), B, N, H, d, float(scale), dt, _ptr(ws), n, _stream()),
-           "attn3d")
+    _check(lib().attn3d(_ptr(q), _ptr(k), _ptr(v), _ptr(out), B, N, H, d, float(scale), dt, int(kernel_path),
+                        _ptr(ws), n, _stream()), "attn3d")
     return out
 
 
 def dit_linear(a: torch.Tensor, w: torch.Tensor, bias: torch.Tensor, act: int = 0,
-               out: Optional[torch.Tensor] = None, use_workspace: bool = True) -> torch.Tensor:
+               out: Optional[torch.Tensor] = None, use_workspace: bool = True, kernel_path: int = 0) -> torch.Tensor:
     M, K = a.shape
     Nn = w.shape[0]
     dt = PS_BF16 if a.dtype == torch.bfloat16 else PS_F32
     if out is None:
         out = torch.empty(M, Nn, dtype=a.dtype, device=a.device)
-    nb = lib().dit_linear_workspace_bytes(M, Nn, K, dt) if use_workspace else 0
+    nb = lib().dit_linear_workspace_bytes(M, Nn, K, dt, int(kernel_path)) if use_workspace else 0
     ws = _workspace(nb, a.device)
-    _check(lib().dit_linear(_ptr(a), _ptr(w), _ptr(bias), _ptr(out), M, Nn, K, int(act), dt, _ptr(ws), nb, _stream()),
-           "dit_linear")
+    _check(lib().dit_linear(_ptr(a), _ptr(w), _ptr(bias), _ptr(out), M, Nn, K, int(act), dt, int(kernel_path),
+                            _ptr(ws), nb, _stream()), "dit_linear")
     return out
 
 
@@ -298,6 +309,27 @@ def sampler_run(d: Dit, sched: Schedule, x_T: torch.Tensor, ctx: Optional[torch.
     if want_trajectory:
         return x0, sums, calls.value, traj
     return x0, sums, calls.value
+
+
+def sampler_workspace(d: Dit, sched: Schedule, device) -> torch.Tensor:
+    nb = lib().sampler_workspace_bytes(d.handle, C.byref(sched.c))
+    if nb == 0:
+        raise PsError(-5, "sampler_workspace_bytes")
+    return _workspace(nb, device)
+
+
+def sampler_state_bytes(d: Dit, sched: Schedule) -> int:
+    return lib().sampler_state_bytes(d.handle, C.byref(sched.c))
+
+
+def sampler_run_steps(d: Dit, sched: Schedule, state: SamplerState, stop_step: int, x_T: Optional[torch.Tensor],
+                      ctx: Optional[torch.Tensor], ws: torch.Tensor, x_out: Optional[torch.Tensor] = None,
+                      step_sums: Optional[torch.Tensor] = None, trajectory: Optional[torch.Tensor] = None):
+    """Advance a run from state.step to stop_step; `ws` (from sampler_workspace) carries the tensors of the state."""
+    _check(lib().sampler_run_steps(d.handle, C.byref(sched.c), C.byref(state), int(stop_step), _ptr(x_T), _ptr(ctx),
+                                   _ptr(x_out), _ptr(step_sums), _ptr(trajectory), _ptr(ws), ws.numel(), _stream()),
+           "sampler_run_steps")
+    return x_out
 
 
 def weights_to_device(cfg: DiTConfig, weights, device="cuda") -> List[torch.Tensor]:

@@ -31,6 +31,7 @@ struct dit {
     std::vector<LayerW> layers;
     int Hp, Wp, Nv, N, P;
     size_t esize;
+    int kernel_path = 0;            // see kernel_path_valid(); dit_set_kernel_path
     // profiling
     int profiling = 0;              // 0 off, 1 every class, 2 the attention class only
     std::vector<hipEvent_t> ev;           // pairs: start, stop
@@ -63,12 +64,17 @@ WsLayout ws_layout(const dit* d, int batch) {
     w.cvec = take((size_t)batch * c.time_embed_dim * 4);
     w.rope = take(rope_table_floats(c.frames, d->Hp, d->Wp, c.head_dim) * 4);   // (cos, sin) per axis position and pair
     w.attn = take(attention_workspace_bytes(c.dtype, batch, d->N, c.heads, c.head_dim));
-    {   // K-split scratch of the projections: the largest need of the four shapes of a layer
-        const int Mi = (int)M, Di = (int)D, Fi = (int)(c.mlp_ratio * D);
-        size_t g = gemm_split_workspace_bytes(c.dtype, Mi, 3 * Di, Di);
-        g = std::max(g, gemm_split_workspace_bytes(c.dtype, Mi, Di, Di));
-        g = std::max(g, gemm_split_workspace_bytes(c.dtype, Mi, Fi, Di));
-        g = std::max(g, gemm_split_workspace_bytes(c.dtype, Mi, Di, Fi));
+    {   // K-split scratch of the projections: the largest need of the four shapes of a layer, under any tile
+        // variant a kernel path can force (so the size does not change when the handle's path does)
+        const int Di = (int)D, Fi = (int)(c.mlp_ratio * D);
+        size_t g = 0;
+        for (int v = 0; v <= PS_PATH_MAX_VARIANT; ++v) {
+            const int path = v << 8;
+            g = std::max(g, gemm_split_workspace_bytes(c.dtype, batch, d->N, 3 * Di, Di, path));
+            g = std::max(g, gemm_split_workspace_bytes(c.dtype, batch, d->N, Di, Di, path));
+            g = std::max(g, gemm_split_workspace_bytes(c.dtype, batch, d->N, Fi, Di, path));
+            g = std::max(g, gemm_split_workspace_bytes(c.dtype, batch, d->N, Di, Fi, path));
+        }
         w.gemm_bytes = g;
         w.gemm = take(g);
     }
@@ -136,7 +142,7 @@ int forward_impl(dit* d, const float* x, const void* ctx, const int32_t* t_host,
                  int batch, void* workspace, hipStream_t st, bool ctx_shared = false) {
     const dit_config& c = d->cfg;
     const int D = c.hidden, Dt = c.time_embed_dim, L = c.layers, N = d->N, M = batch * N;
-    const int dt = c.dtype;
+    const int dt = c.dtype, path = d->kernel_path;
     WsLayout w = ws_layout(d, batch);
     char* base = (char*)workspace;
     float* X = (float*)(base + w.X);
@@ -182,16 +188,16 @@ int forward_impl(dit* d, const float* x, const void* ctx, const int32_t* t_host,
     const float scale = 1.0f / sqrtf((float)c.head_dim);
     // the MFMA attention kernel takes queries that already carry scale*log2(e); the QKV
     // projection applies the factor in fp32, before its single rounding to bf16
-    const bool prescale = attention_uses_mfma(dt, c.head_dim);
+    const bool prescale = attention_uses_mfma(dt, c.head_dim, path);
 
     for (int l = 0; l < L; ++l) {
         const LayerW& lw = d->layers[l];
         const float* mod_l = mod + (long)l * 12 * D;
         // the projection's epilogue leaves the per-head maxima of |q|^2 and |k|^2 the attention kernel selects on;
         // the LayerNorm kernel in front of it clears them
-        const bool fused_bounds = c.head_dim == 64 && gemm_uses_mfma(dt, M, 3 * D, D);
+        const bool fused_bounds = c.head_dim == 64 && gemm_uses_mfma(dt, N, 3 * D, D, path);
         int nbounds = 0;
-        float* bounds = fused_bounds ? attention_norm_bounds(dt, batch, c.heads, c.head_dim, attn_ws, st, false, &nbounds)
+        float* bounds = fused_bounds ? attention_norm_bounds(dt, batch, c.heads, c.head_dim, attn_ws, path, st, false, &nbounds)
                                      : nullptr;
         // h = LN(X)(1+scale_a)+shift_a
         PS_TIMED(KC_LN, launch_ln_modulate(dt, X, Hb, M, D, c.ln_eps, mod_l, mod_bs, 0, 1, geom, st, bounds, nbounds));
@@ -203,37 +209,37 @@ int forward_impl(dit* d, const float* x, const void* ctx, const int32_t* t_host,
         eq.split_ws = gemm_ws; eq.split_ws_bytes = w.gemm_bytes;
         eq.norm_bounds = bounds;
         eq.heads = c.heads;
-        PS_TIMED(KC_QKV, launch_gemm(dt, Hb, lw.W_qkv, QKV, M, 3 * D, D, eq, st));
+        PS_TIMED(KC_QKV, launch_gemm(dt, Hb, lw.W_qkv, QKV, batch, N, 3 * D, D, eq, path, st));
         // o = attention(q, k, v) -> Hb (token-major, heads concatenated)
         const char* qp = (const char*)QKV;
         PS_TIMED(KC_ATTN, launch_attention(dt, qp, qp + (size_t)D * es, qp + (size_t)2 * D * es, Hb, batch, N,
-                                           c.heads, c.head_dim, scale, as, attn_ws, st, prescale,
+                                           c.heads, c.head_dim, scale, as, attn_ws, path, st, prescale,
                                            eq.norm_bounds != nullptr));
         // X += gate_a * (W_o o + b_o)
         Epilogue eo{};
         eo.kind = EPI_GATE_RESIDUAL; eo.bias = lw.b_o; eo.resid = X; eo.mod_layer = mod_l;
         eo.mod_batch_stride = mod_bs; eo.gate_chunk = 2; eo.D = D; eo.geom = geom;
         eo.split_ws = gemm_ws; eo.split_ws_bytes = w.gemm_bytes;
-        PS_TIMED(KC_OPROJ, launch_gemm(dt, Hb, lw.W_o, nullptr, M, D, D, eo, st));
+        PS_TIMED(KC_OPROJ, launch_gemm(dt, Hb, lw.W_o, nullptr, batch, N, D, D, eo, path, st));
         // h2 = LN(X)(1+scale_m)+shift_m ; u = GELU(W_1 h2 + b_1) ; X += gate_m * (W_2 u + b_2)
         PS_TIMED(KC_LN, launch_ln_modulate(dt, X, Hb, M, D, c.ln_eps, mod_l, mod_bs, 3, 4, geom, st));
         Epilogue e1{};
         e1.kind = EPI_BIAS_GELU; e1.bias = lw.b_1;
         e1.split_ws = gemm_ws; e1.split_ws_bytes = w.gemm_bytes;
-        PS_TIMED(KC_FC1, launch_gemm(dt, Hb, lw.W_1, QKV, M, c.mlp_ratio * D, D, e1, st));
+        PS_TIMED(KC_FC1, launch_gemm(dt, Hb, lw.W_1, QKV, batch, N, c.mlp_ratio * D, D, e1, path, st));
         Epilogue e2 = eo;
         e2.bias = lw.b_2; e2.gate_chunk = 5;
-        PS_TIMED(KC_FC2, launch_gemm(dt, QKV, lw.W_2, nullptr, M, D, c.mlp_ratio * D, e2, st));
+        PS_TIMED(KC_FC2, launch_gemm(dt, QKV, lw.W_2, nullptr, batch, N, D, c.mlp_ratio * D, e2, path, st));
     }
     // eps = unpatchify(W_out (LN(X)(1+scale_f)+shift_f) + b_out) over the video tokens
     const int P = c.in_channels * c.patch * c.patch;
-    if (gemm_uses_mfma(dt, M, P, D)) {
+    if (gemm_uses_mfma(dt, N, P, D, path)) {
         // as every other projection: normalised rows in bf16 (text rows included, dropped by the epilogue)
         PS_TIMED(KC_LN, launch_ln_modulate(dt, X, Hb, M, D, c.ln_eps, modf, 2L * D, 0, 1, TokenGeom{N, 0}, st));
         Epilogue ef{};
         ef.kind = EPI_UNPATCHIFY; ef.bias = d->b_out; ef.resid = eps_out; ef.geom = geom;
         ef.pg = PatchGeom{c.in_channels, c.frames, c.height, c.width, c.patch};
-        PS_TIMED(KC_OTHER, launch_gemm(dt, Hb, d->W_out, nullptr, M, P, D, ef, st));
+        PS_TIMED(KC_OTHER, launch_gemm(dt, Hb, d->W_out, nullptr, batch, N, P, D, ef, path, st));
     } else {
         PS_TIMED(KC_OTHER, launch_final_proj(dt, X, modf, d->W_out, d->b_out, eps_out, batch, c.in_channels,
                                              c.frames, c.height, c.width, c.patch, c.text_tokens, D, c.ln_eps, st));
@@ -258,10 +264,13 @@ const char* ps_strerror(int status) {
     }
 }
 
-int ps_set_kernel_path(int path) {
-    int old = get_kernel_path();
-    set_kernel_path(path);
-    return old;
+int dit_get_kernel_path(const dit* d) { return d ? d->kernel_path : PS_ERR_NULL; }
+
+int dit_set_kernel_path(dit* d, int path) {
+    if (!d) return PS_ERR_NULL;
+    if (!kernel_path_valid(path)) return PS_ERR_SHAPE;
+    d->kernel_path = path;
+    return PS_OK;
 }
 
 int dit_num_weights(int layers) { return layers < 0 ? 0 : 6 + 10 * layers + 4; }
@@ -279,7 +288,8 @@ int dit_create(const dit_config* cfg, const void* const* weights, int n_weights,
     if (c.in_channels < 1 || c.patch < 1 || c.frames < 1 || c.height < 1 || c.width < 1) return PS_ERR_SHAPE;
     if (c.height % c.patch || c.width % c.patch) return PS_ERR_SHAPE;
     if (c.text_tokens < 0 || c.time_embed_dim < 1) return PS_ERR_SHAPE;
-    if ((long)c.in_channels * c.patch * c.patch > 4096) return PS_ERR_SHAPE;
+    // the patch-embedding kernel stages 16 patch vectors in LDS (64 bytes per patch value, 64 KB at most)
+    if ((long)c.in_channels * c.patch * c.patch > 1024) return PS_ERR_SHAPE;
     if (!(c.ln_eps > 0.f) || !(c.rope_theta > 1.f)) return PS_ERR_SHAPE;
     if ((long)c.in_channels * c.frames * c.height * c.width % 4 != 0) return PS_ERR_SHAPE;
     if (n_weights != dit_num_weights(c.layers)) return PS_ERR_SHAPE;
@@ -289,6 +299,9 @@ int dit_create(const dit_config* cfg, const void* const* weights, int n_weights,
     }
     long nv = (long)c.frames * (c.height / c.patch) * (c.width / c.patch);
     if (nv + c.text_tokens > (1L << 24)) return PS_ERR_SHAPE;
+    // the bf16 projections address a sample's activations with 32-bit element offsets
+    if (c.dtype == PS_BF16 && (nv + c.text_tokens) * (long)c.hidden * std::max(c.mlp_ratio, 3) >= (1L << 31))
+        return PS_ERR_SHAPE;
     dit* d = new (std::nothrow) dit();
     if (!d) return PS_ERR_HIP;
     d->cfg = c;
@@ -368,9 +381,11 @@ size_t attn3d_workspace_bytes(int batch, int seq, int heads, int head_dim, int d
 }
 
 int attn3d(const void* q, const void* k, const void* v, void* o, int batch, int seq, int heads,
-           int head_dim, float scale, int dtype, void* workspace, size_t workspace_bytes, void* hip_stream) {
+           int head_dim, float scale, int dtype, int kernel_path, void* workspace, size_t workspace_bytes,
+           void* hip_stream) {
     if (!q || !k || !v || !o) return PS_ERR_NULL;
     if (dtype != PS_F32 && dtype != PS_BF16) return PS_ERR_DTYPE;
+    if (!kernel_path_valid(kernel_path)) return PS_ERR_SHAPE;
     if (batch < 1 || seq < 1 || heads < 1) return PS_ERR_SHAPE;
     if (head_dim != 16 && head_dim != 32 && head_dim != 64) return PS_ERR_SHAPE;
     if (batch > 65535 || heads > 65535 || seq > (1 << 24)) return PS_ERR_SHAPE;
@@ -384,19 +399,20 @@ int attn3d(const void* q, const void* k, const void* v, void* o, int batch, int 
     s.q_head = s.k_head = s.v_head = s.o_head = head_dim;
     s.q_batch = s.k_batch = s.v_batch = s.o_batch = (long)seq * heads * head_dim;
     hipError_t e = launch_attention(dtype, q, k, v, o, batch, seq, heads, head_dim, scale, s,
-                                    need ? workspace : nullptr, (hipStream_t)hip_stream);
+                                    need ? workspace : nullptr, kernel_path, (hipStream_t)hip_stream);
     return e == hipSuccess ? PS_OK : PS_ERR_HIP;
 }
 
-size_t dit_linear_workspace_bytes(int m, int n_out, int k, int dtype) {
-    if (m < 1 || n_out < 2 || k < 8 || (dtype != PS_F32 && dtype != PS_BF16)) return 0;
-    return align256(gemm_split_workspace_bytes(dtype, m, n_out, k));
+size_t dit_linear_workspace_bytes(int m, int n_out, int k, int dtype, int kernel_path) {
+    if (m < 1 || n_out < 2 || k < 8 || (dtype != PS_F32 && dtype != PS_BF16) || !kernel_path_valid(kernel_path)) return 0;
+    return align256(gemm_split_workspace_bytes(dtype, 1, m, n_out, k, kernel_path));
 }
 
 int dit_linear(const void* a, const void* w, const float* bias, void* out, int m, int n_out, int k, int act,
-               int dtype, void* workspace, size_t workspace_bytes, void* hip_stream) {
+               int dtype, int kernel_path, void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (!a || !w || !bias || !out) return PS_ERR_NULL;
     if (dtype != PS_F32 && dtype != PS_BF16) return PS_ERR_DTYPE;
+    if (!kernel_path_valid(kernel_path)) return PS_ERR_SHAPE;
     if (m < 1 || n_out < 2 || k < 8 || (n_out & 1) || (k % 8) || (act != 0 && act != 1)) return PS_ERR_SHAPE;
     if (!aligned(a, 16) || !aligned(w, 16) || !aligned(out, 16) || !aligned(bias, 16) || out == a || out == w)
         return PS_ERR_SHAPE;
@@ -404,9 +420,10 @@ int dit_linear(const void* a, const void* w, const float* bias, void* out, int m
     Epilogue ep{};
     ep.kind = act ? EPI_BIAS_GELU : EPI_BIAS;
     ep.bias = bias;
+    ep.geom = TokenGeom{m, 0};
     ep.split_ws = (float*)workspace;                 // used only if large enough for the shape's split
     ep.split_ws_bytes = workspace ? workspace_bytes : 0;
-    hipError_t e = launch_gemm(dtype, a, w, out, m, n_out, k, ep, (hipStream_t)hip_stream);
+    hipError_t e = launch_gemm(dtype, a, w, out, 1, m, n_out, k, ep, kernel_path, (hipStream_t)hip_stream);
     return e == hipSuccess ? PS_OK : PS_ERR_HIP;
 }
 
@@ -534,7 +551,10 @@ int plan_schedule(const sampler_schedule* s, RunPlan* plan) {
     return PS_OK;
 }
 
-struct RunWs { size_t xbuf, cache, pp, xb, eb, red, dit, total; };
+// [per-rank samples | per-rank eps_cache | two eps buffers] is the state a run carries from step to step
+// (Algorithm 1: x and eps_cache of every rank, plus the eps of the last step for the adjacent-step sums);
+// everything after `state_end` is scratch.
+struct RunWs { size_t xbuf, cache, pp, state_end, xb, eb, red, dit, total; };
 
 RunWs run_layout(const dit* d, const sampler_schedule* s, const RunPlan& plan) {
     size_t n = (size_t)d->cfg.in_channels * d->cfg.frames * d->cfg.height * d->cfg.width;
@@ -546,12 +566,24 @@ RunWs run_layout(const dit* d, const sampler_schedule* s, const RunPlan& plan) {
     w.xbuf = take(nb * p);        // per-rank samples (rank 0 = true trajectory)
     w.cache = take(nb * p);       // per-rank eps_cache
     w.pp = take(nb * 2);          // ping-pong eps buffers / eps_prev copy
+    w.state_end = off;
     w.xb = take(s->batched ? nb * p : 0);
     w.eb = take(s->batched ? nb * p : 0);
     w.red = take(reduce_workspace_bytes(n));
     w.dit = take(dit_workspace_bytes(d, s->batched ? p : 1));
     w.total = off;
     return w;
+}
+
+// (cycle, round) at which step `step` runs; false if `step` lies inside warm-up (then both are 0)
+bool position_of(const RunPlan& plan, int step, int* cyc, int* rnd) {
+    *cyc = 0; *rnd = 0;
+    if (step < plan.warm) return false;
+    int left = step - plan.warm;
+    size_t c = 0;
+    while (c < plan.cycles.size() && left >= plan.cycles[c]) { left -= plan.cycles[c]; ++c; }
+    *cyc = (int)c; *rnd = left;
+    return true;
 }
 
 }  // namespace
@@ -564,17 +596,43 @@ size_t sampler_workspace_bytes(const dit* d, const sampler_schedule* s) {
     return run_layout(d, s, plan).total;
 }
 
-int sampler_run(dit* d, const sampler_schedule* s, const float* x_T, const void* ctx, float* x0_out,
-                float* step_sums, float* trajectory_out, int* calls_out, void* workspace, size_t workspace_bytes,
-                void* hip_stream) {
-    if (!d || !s || !x_T || !x0_out) return PS_ERR_NULL;
+size_t sampler_state_bytes(const dit* d, const sampler_schedule* s) {
+    RunPlan plan;
+    if (!d || plan_schedule(s, &plan) != PS_OK) return 0;
+    return run_layout(d, s, plan).state_end;
+}
+
+int sampler_run_steps(dit* d, const sampler_schedule* s, sampler_state* state, int stop_step, const float* x_T,
+                      const void* ctx, float* x_out, float* step_sums, float* trajectory_out, void* workspace,
+                      size_t workspace_bytes, void* hip_stream) {
+    if (!d || !s || !state) return PS_ERR_NULL;
     if (d->cfg.text_tokens > 0 && !ctx) return PS_ERR_NULL;
     RunPlan plan;
     int rc = plan_schedule(s, &plan);
     if (rc != PS_OK) return rc;
-    if (!aligned(x_T, 16) || !aligned(x0_out, 16) || (step_sums && !aligned(step_sums, 16))) return PS_ERR_SHAPE;
-    if (trajectory_out && (!aligned(trajectory_out, 16) || trajectory_out == x_T || trajectory_out == x0_out))
+    const int P = plan.pmax;
+    const bool fresh = state->step == 0;
+    if (fresh && !x_T) return PS_ERR_NULL;
+    if (state->step < 0 || state->step >= s->steps || stop_step <= state->step || stop_step > s->steps)
+        return PS_ERR_SCHEDULE;
+    if ((x_T && !aligned(x_T, 16)) || (x_out && !aligned(x_out, 16)) || (step_sums && !aligned(step_sums, 16)))
         return PS_ERR_SHAPE;
+    if (trajectory_out && (!aligned(trajectory_out, 16) || trajectory_out == x_T || trajectory_out == x_out))
+        return PS_ERR_SHAPE;
+    int cyc = 0, rnd = 0;
+    position_of(plan, state->step, &cyc, &rnd);
+    if (!fresh) {
+        // a state that does not belong to this schedule is an error, not a different run
+        if (state->cycle != cyc || state->round != rnd || (state->toggle != 0 && state->toggle != 1)) return PS_ERR_SCHEDULE;
+        if (state->eps_prev < 0 || state->eps_prev >= 2 + P || state->calls < 0) return PS_ERR_SCHEDULE;
+        for (int r = 0; r < P; ++r)
+            if (state->src[r] != 0 && state->src[r] != r) return PS_ERR_SCHEDULE;
+    }
+    if (s->batched) {               // a cycle is one predictor call: a run can only pause between cycles
+        int c2, r2;
+        if (position_of(plan, state->step, &c2, &r2) && r2 != 0) return PS_ERR_SCHEDULE;
+        if (stop_step < s->steps && position_of(plan, stop_step, &c2, &r2) && r2 != 0) return PS_ERR_SCHEDULE;
+    }
     RunWs w = run_layout(d, s, plan);
     if (!workspace || !aligned(workspace, 256) || workspace_bytes < w.total) return PS_ERR_WORKSPACE;
 
@@ -582,7 +640,6 @@ int sampler_run(dit* d, const sampler_schedule* s, const float* x_T, const void*
     const size_t n = (size_t)d->cfg.in_channels * d->cfg.frames * d->cfg.height * d->cfg.width;
     const size_t nb = align256(n * 4);
     char* base = (char*)workspace;
-    const int P = plan.pmax;
     auto xbuf = [&](int r) { return (float*)(base + w.xbuf + nb * r); };
     // mode 2 (latest eps): every rank reuses the eps applied in the step before the cycle;
     // it is kept in slot 0, which Algorithm 1 never reads (rank 0 has no reuse update)
@@ -593,8 +650,6 @@ int sampler_run(dit* d, const sampler_schedule* s, const float* x_T, const void*
     auto eb = [&](int r) { return (float*)(base + w.eb + n * 4 * r); };
     void* red = base + w.red;
     void* dws = base + w.dit;
-    const size_t dws_bytes = w.total - w.dit;
-    int calls = 0;
 
     auto step = [&](const float* x, const float* e, const float* eprev, float* xo, int i, bool record) -> int {
         float* sums = (record && step_sums) ? step_sums + 4 * (size_t)i : nullptr;
@@ -609,21 +664,28 @@ int sampler_run(dit* d, const sampler_schedule* s, const float* x_T, const void*
     };
 #define PS_RC(expr) do { int rc__ = (expr); if (rc__ != PS_OK) return rc__; } while (0)
 
+    // the eps of the last step: nowhere yet (-1), eps buffer 0 / 1, or rank r's cache (2 + r)
+    auto eps_at = [&](int code) -> float* { return code < 0 ? nullptr : code < 2 ? pp(code) : cache(code - 2); };
+    int calls = fresh ? 0 : state->calls;
+    int eprev_code = fresh ? -1 : state->eps_prev;
+    int toggle = fresh ? 0 : state->toggle;
+    std::vector<int> src(P, 0);
+    if (!fresh) for (int r = 0; r < P; ++r) src[r] = state->src[r];
+    if (fresh) PS_RC(copy(xbuf(0), x_T));
+    int i = state->step;
+
     if (!s->batched) {
         // rank r's current sample lives in xbuf[src[r]] (after a broadcast every rank reads
         // rank 0's buffer until its next own update)
-        std::vector<int> src(P, 0);
-        PS_RC(copy(xbuf(0), x_T));
-        const float* eprev = nullptr;
-        int toggle = 0;
-        int cyc = 0, rnd = 0;
-        for (int i = 0; i < s->steps; ++i) {
+        for (; i < stop_step; ++i) {
             int32_t t = s->timesteps[i];
+            const float* eprev = eps_at(eprev_code);
             if (i < plan.warm) {
+                const int ecode = toggle;
                 float* e = pp(toggle); toggle ^= 1;
                 PS_RC(forward_impl(d, xbuf(0), ctx, &t, e, 1, dws, st)); ++calls;
                 PS_RC(step(xbuf(0), e, eprev, xbuf(0), i, true));
-                eprev = e;
+                eprev_code = ecode;
                 if (i == plan.warm - 1) {                                   // eps_cache of every rank
                     if (latest) PS_RC(copy(cache(0), e));
                     else for (int r = 1; r < P; ++r) PS_RC(copy(cache(r), e));
@@ -634,16 +696,19 @@ int sampler_run(dit* d, const sampler_schedule* s, const float* x_T, const void*
             if (s->mode == 1) {                      // direct reuse: predict only in round 0
                 const float* e = eprev;
                 if (rnd == 0) {
+                    const int ecode = toggle;
                     float* en = pp(toggle); toggle ^= 1;
                     PS_RC(forward_impl(d, xbuf(0), ctx, &t, en, 1, dws, st)); ++calls;
                     e = en;
+                    eprev_code = ecode;
                 }
                 PS_RC(step(xbuf(0), e, eprev, xbuf(0), i, true));
-                eprev = e;
             } else {
                 const int master = rnd;
                 float* e;
-                if (master == 0 || latest) { e = pp(toggle); toggle ^= 1; } else { e = cache(master); }
+                int ecode;
+                if (master == 0 || latest) { ecode = toggle; e = pp(toggle); toggle ^= 1; }
+                else { ecode = 2 + master; e = cache(master); }
                 PS_RC(forward_impl(d, xbuf(src[master]), ctx, &t, e, 1, dws, st)); ++calls;
                 // ranks that still have to predict in this cycle advance with their own cache;
                 // they may read rank 0's buffer, so they go before rank 0's in-place update
@@ -652,35 +717,31 @@ int sampler_run(dit* d, const sampler_schedule* s, const float* x_T, const void*
                     src[r] = r;
                 }
                 PS_RC(step(xbuf(0), e, eprev, xbuf(0), i, true));   // rank 0 applies the master's eps
-                eprev = e;
+                eprev_code = ecode;
             }
             if (rnd == p - 1) {                      // broadcast rank 0's sample
                 for (int r = 1; r < P; ++r) src[r] = 0;
-                if (latest && P > 1) PS_RC(copy(cache(0), eprev));
+                if (latest && P > 1) PS_RC(copy(cache(0), eps_at(eprev_code)));
                 ++cyc; rnd = 0;
             } else {
                 ++rnd;
             }
         }
-        PS_RC(copy(x0_out, xbuf(0)));
     } else {
-        // batched: rank 0's sample lives in xb(0)'s neighbour xbuf(0); inputs of a cycle in xb(r)
-        PS_RC(copy(xbuf(0), x_T));
+        // batched: rank 0's sample lives in xbuf(0); inputs of a cycle in xb(r); the eps of the last step in pp(0)
         float* eprev_buf = pp(0);
-        bool have_prev = false;
-        int i = 0;
         int32_t tb[MAX_BATCH];
-        for (; i < plan.warm; ++i) {
+        for (; i < plan.warm && i < stop_step; ++i) {
             tb[0] = s->timesteps[i];
             PS_RC(forward_impl(d, xbuf(0), ctx, tb, eb(0), 1, dws, st)); ++calls;
-            PS_RC(step(xbuf(0), eb(0), have_prev ? eprev_buf : nullptr, xbuf(0), i, true));
+            PS_RC(step(xbuf(0), eb(0), eprev_code >= 0 ? eprev_buf : nullptr, xbuf(0), i, true));
             PS_RC(copy(eprev_buf, eb(0)));
-            have_prev = true;
+            eprev_code = 0;
             if (i == plan.warm - 1)
                 for (int r = 0; r < (latest ? 1 : P); ++r) PS_RC(copy(cache(r), eb(0)));
         }
-        for (size_t c = 0; c < plan.cycles.size() && i < s->steps; ++c) {
-            int p = plan.cycles[c];
+        for (; (size_t)cyc < plan.cycles.size() && i < stop_step; ++cyc) {
+            int p = plan.cycles[cyc];
             int nn = p < s->steps - i ? p : s->steps - i;
             // rank r's input: the current sample advanced r times with that rank's cached eps
             PS_RC(copy(xb(0), xbuf(0)));
@@ -692,21 +753,39 @@ int sampler_run(dit* d, const sampler_schedule* s, const float* x_T, const void*
             // the text context is shared by all ranks of the cycle
             PS_RC(forward_impl(d, xb(0), ctx, tb, eb(0), nn, dws, st, true)); ++calls;
             for (int r = 0; r < nn; ++r) {
-                const float* prev = r == 0 ? (have_prev ? eprev_buf : nullptr) : eb(r - 1);
+                const float* prev = r == 0 ? (eprev_code >= 0 ? eprev_buf : nullptr) : eb(r - 1);
                 PS_RC(step(xbuf(0), eb(r), prev, xbuf(0), i + r, true));
             }
             if (latest) PS_RC(copy(cache(0), eb(nn - 1)));
             else for (int r = 0; r < nn; ++r) PS_RC(copy(cache(r), eb(r)));
             PS_RC(copy(eprev_buf, eb(nn - 1)));
-            have_prev = true;
+            eprev_code = 0;
             i += nn;
         }
-        PS_RC(copy(x0_out, xbuf(0)));
+        rnd = 0;
     }
+    if (x_out) PS_RC(copy(x_out, xbuf(0)));
 #undef PS_RC
-    (void)dws_bytes;
-    if (calls_out) *calls_out = calls;
+    state->step = i;
+    state->cycle = cyc;
+    state->round = rnd;
+    state->toggle = toggle;
+    state->eps_prev = eprev_code;
+    state->calls = calls;
+    for (int r = 0; r < MAX_BATCH; ++r) state->src[r] = r < P ? src[r] : 0;
     return PS_OK;
+}
+
+int sampler_run(dit* d, const sampler_schedule* s, const float* x_T, const void* ctx, float* x0_out,
+                float* step_sums, float* trajectory_out, int* calls_out, void* workspace, size_t workspace_bytes,
+                void* hip_stream) {
+    if (!d || !s || !x_T || !x0_out) return PS_ERR_NULL;
+    sampler_state state;
+    memset(&state, 0, sizeof(state));
+    int rc = sampler_run_steps(d, s, &state, s->steps, x_T, ctx, x0_out, step_sums, trajectory_out, workspace,
+                               workspace_bytes, hip_stream);
+    if (rc == PS_OK && calls_out) *calls_out = state.calls;
+    return rc;
 }
 
 }  // extern "C"

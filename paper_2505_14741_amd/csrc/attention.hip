@@ -16,8 +16,6 @@
 
 namespace ps {
 
-int get_kernel_path();
-
 // ------------------------------------------------------------------------------ generic
 template <typename T, int HD>
 __global__ void __launch_bounds__(128)
@@ -258,23 +256,60 @@ __device__ __forceinline__ bool head_is_bounded(const float* __restrict__ bounds
 
 static constexpr int PART_STRIDE = 68;      // floats per row of a partial result (64 + l + r, padded to 16 B)
 
+// Work items of a launch.  Every sample of the batch has the same items -- (head, block of 256 queries), qblocks *
+// heads of them -- and the same plan: the first full_ps run whole, the last tail_ps (fewer than half a round of the
+// chip's workgroup slots) are each split nsplit ways along the keys.  The plan depends on the sample's shape only,
+// never on the batch, so a sample's result is bit-identical whatever batch it is computed in (Section 3.3: the
+// batched step must reproduce the per-step process).  Workgroup ids: the batch * full_ps whole items of all samples
+// first, then the pieces.
+struct AttnGrid { int qblocks, heads, full_ps, tail_ps, nsplit, all_full; };
+
+// id -> sample, head, query block; piece index (-1: whole item) and its share [jt0, jt1) of the nt key tiles
+__device__ __forceinline__ void attn_item(const AttnGrid& g, int id, int nt, int& bh, int& qb, int& piece, int& jt0,
+                                          int& jt1) {
+    int sample, local;
+    piece = -1; jt0 = 0; jt1 = nt;
+    if (id < g.all_full) {
+        // consecutive ids of one XCD walk the query blocks of one head, so that head's K and V stay in that XCD's L2
+        const int per = g.all_full / 8, rem = g.all_full % 8, x = id % 8, j = id / 8;
+        id = x * per + (x < rem ? x : rem) + j;
+        sample = id / g.full_ps;
+        local = id - sample * g.full_ps;
+    } else {
+        piece = id - g.all_full;
+        const int per_sample = g.tail_ps * g.nsplit;
+        sample = piece / per_sample;
+        const int lp = piece - sample * per_sample;
+        local = g.full_ps + lp / g.nsplit;
+        const int pi = lp % g.nsplit;
+        jt0 = (int)((long)nt * pi / g.nsplit);
+        jt1 = (int)((long)nt * (pi + 1) / g.nsplit);
+    }
+    const int h = local / g.qblocks;
+    qb = local - h * g.qblocks;
+    bh = sample * g.heads + h;
+}
+
 // Merge of the key-range pieces of the split items: one thread per (row, 4 output values).
 // O = sum_i w_i O_i / sum_i w_i l_i with w_i = 2^(c (r_i - max_i r_i)).
 // (a device function: it runs as a kernel of its own and as the trailing workgroups of attn_mfma_kernel)
+// g: the plan the pieces were produced under; nitems = batch * g.tail_ps
 __device__ __forceinline__ void
-attn_merge_rows(int block, const float* __restrict__ part, bf16_t* __restrict__ o, int seq, int heads, int qblocks,
-                int full_blocks, int nsplit, int nitems, float cexp, int bq, const AttnStrides& s,
-                const float* __restrict__ bounds) {
+attn_merge_rows(int block, const float* __restrict__ part, bf16_t* __restrict__ o, int seq, const AttnGrid& g,
+                int nitems, float cexp, int bq, const AttnStrides& s, const float* __restrict__ bounds) {
     const int gid = block * 256 + threadIdx.x;
     const int d4 = gid & 15, rowid = gid >> 4;          // 16 threads per row
-    const int item = rowid / bq, row = rowid % bq;
+    const int item = rowid / bq, row = rowid % bq;      // item: over all samples
     if (item >= nitems) return;
-    const int id = full_blocks + item;
-    const int bh = id / qblocks, qb = id % qblocks;
+    const int sample = item / g.tail_ps;
+    const int local = g.full_ps + item % g.tail_ps;
+    const int h = local / g.qblocks, qb = local % g.qblocks;
+    const int bh = sample * g.heads + h;
     if (bounds != nullptr && !head_is_bounded(bounds, bh, cexp)) return;   // pieces exist for attn_sp_kernel's heads only
-    const int b = bh / heads, h = bh % heads;
+    const int b = sample;
     const int qi = qb * bq + row;
     if (qi >= seq) return;
+    const int nsplit = g.nsplit;
     const float* p0 = part + ((long)item * nsplit * bq + row) * PART_STRIDE;
     float rmax = p0[65];
     for (int i = 1; i < nsplit; ++i) rmax = fmaxf(rmax, p0[(long)i * bq * PART_STRIDE + 65]);
@@ -295,19 +330,19 @@ attn_merge_rows(int block, const float* __restrict__ part, bf16_t* __restrict__ 
 }
 
 __global__ void __launch_bounds__(256)
-attn_merge_kernel(const float* __restrict__ part, bf16_t* __restrict__ o, int seq, int heads, int qblocks,
-                  int full_blocks, int nsplit, int nitems, float cexp, int bq, AttnStrides s,
-                  const float* __restrict__ bounds) {
-    attn_merge_rows(blockIdx.x, part, o, seq, heads, qblocks, full_blocks, nsplit, nitems, cexp, bq, s, bounds);
+attn_merge_kernel(const float* __restrict__ part, bf16_t* __restrict__ o, int seq, AttnGrid g, int nitems, float cexp,
+                  int bq, AttnStrides s, const float* __restrict__ bounds) {
+    attn_merge_rows(blockIdx.x, part, o, seq, g, nitems, cexp, bq, s, bounds);
 }
 
 // Merge work that rides on a launch of attn_mfma_kernel: its first `blocks` workgroups merge the pieces another,
-// earlier launch left in `part` (blocks == 0: none); the items follow.  (In front, because where every head is
-// bounded the item workgroups exit at once and the merge is all the launch does.)
+// earlier launch left in `part` under plan `g` (blocks == 0: none); the items follow.  (In front, because where
+// every head is bounded the item workgroups exit at once and the merge is all the launch does.)
 struct MergeTail {
     const float* part;
-    int blocks, full_blocks, nsplit, nitems, bq;
+    int blocks, nitems, bq;
     float cexp;
+    AttnGrid g;
 };
 
 // global->LDS load of 16 bytes per lane: lane j's bytes land at lds_addr + 16*j (lds_addr
@@ -343,14 +378,13 @@ __device__ __forceinline__ float rowsum_bf16x8(bf16x8_t p, float acc) {
 template <int QT, bool PRESCALED>   // QT: 32-query column tiles per wave
 __global__ void __launch_bounds__(256, 2)
 attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
-                 bf16_t* __restrict__ o, int seq, int heads, float scale_log2e, int qblocks, AttnStrides s,
-                 int full_blocks, int nsplit, float* __restrict__ part, const float* __restrict__ bounds,
-                 MergeTail mt) {
+                 bf16_t* __restrict__ o, int seq, float scale_log2e, AttnStrides s, AttnGrid grid,
+                 float* __restrict__ part, const float* __restrict__ bounds, MergeTail mt) {
     if ((int)blockIdx.x < mt.blocks) {                      // whole workgroup: before any barrier
-        attn_merge_rows(blockIdx.x, mt.part, o, seq, heads, qblocks, mt.full_blocks, mt.nsplit, mt.nitems,
-                        mt.cexp, mt.bq, s, bounds);
+        attn_merge_rows(blockIdx.x, mt.part, o, seq, mt.g, mt.nitems, mt.cexp, mt.bq, s, bounds);
         return;
     }
+    const int heads = grid.heads;
     constexpr int KV = 64;
     constexpr int BQ = 4 * QT * 32;
     constexpr int NST = 3;                       // LDS ring depth
@@ -360,26 +394,10 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform values stay in scalar registers
     const int col = lane & 31, half = lane >> 5;
-    // workgroup -> (batch*head, query block); consecutive ids of one XCD walk the query
-    // blocks of one head so that head's K and V stay in that XCD's L2
-    // The first full_blocks (query block, head) items each take one workgroup over all keys.
-    // The remaining items -- fewer than half a round of the chip's workgroup slots -- are each
-    // split nsplit ways along the keys, so the last round costs 1/nsplit of a full one; such
-    // a workgroup leaves unnormalised sums, row sum and reference in `part` for the merge kernel.
-    int id = blockIdx.x - mt.blocks;
-    int piece = -1, jt0 = 0, jt1 = (seq + KV - 1) / KV;
-    if (id < full_blocks) {
-        int per = full_blocks / 8, rem = full_blocks % 8, x = id % 8, j = id / 8;
-        id = x * per + (x < rem ? x : rem) + j;
-    } else {
-        piece = id - full_blocks;
-        id = full_blocks + piece / nsplit;
-        const int pi = piece % nsplit;
-        const int nt = jt1;
-        jt0 = (int)((long)nt * pi / nsplit);
-        jt1 = (int)((long)nt * (pi + 1) / nsplit);
-    }
-    const int bh = id / qblocks, qb = id % qblocks;
+    // workgroup -> (batch*head, query block), see AttnGrid.  A whole item takes one workgroup over all keys; a
+    // piece of a split item leaves unnormalised sums, row sum and reference in `part` for the merge.
+    int bh, qb, piece, jt0, jt1;
+    attn_item(grid, blockIdx.x - mt.blocks, (seq + KV - 1) / KV, bh, qb, piece, jt0, jt1);
     // with `bounds` given, heads whose exponents are provably small belong to attn_sp_kernel
     if (bounds != nullptr && head_is_bounded(bounds, bh, PRESCALED ? 1.0f : scale_log2e)) return;
     const int b = bh / heads, h = bh % heads;
@@ -706,8 +724,8 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
 template <bool PRESCALED>
 __global__ void __launch_bounds__(256, 2)
 attn_sp_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
-               bf16_t* __restrict__ o, int seq, int heads, float scale_log2e, int qblocks, AttnStrides s,
-               int full_blocks, int nsplit, float* __restrict__ part, const float* __restrict__ bounds) {
+               bf16_t* __restrict__ o, int seq, float scale_log2e, AttnStrides s, AttnGrid grid,
+               float* __restrict__ part, const float* __restrict__ bounds) {
     constexpr int QT = 2;                        // 32-query column tiles per wave
     constexpr int KV = 64;                       // keys per tile
     constexpr int BQ = 4 * QT * 32;              // queries per workgroup
@@ -719,20 +737,9 @@ attn_sp_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, half = lane >> 5;
     // work items and the key split of the last partial round: as in attn_mfma_kernel
-    int id = blockIdx.x;
-    int piece = -1, jt0 = 0, jt1 = (seq + KV - 1) / KV;
-    if (id < full_blocks) {
-        int per = full_blocks / 8, rem = full_blocks % 8, x = id % 8, j = id / 8;
-        id = x * per + (x < rem ? x : rem) + j;
-    } else {
-        piece = id - full_blocks;
-        id = full_blocks + piece / nsplit;
-        const int pi = piece % nsplit;
-        const int nt = jt1;
-        jt0 = (int)((long)nt * pi / nsplit);
-        jt1 = (int)((long)nt * (pi + 1) / nsplit);
-    }
-    const int bh = id / qblocks, qb = id % qblocks;
+    const int heads = grid.heads;
+    int bh, qb, piece, jt0, jt1;
+    attn_item(grid, blockIdx.x, (seq + KV - 1) / KV, bh, qb, piece, jt0, jt1);
     const float cexp = PRESCALED ? 1.0f : scale_log2e;
     if (!head_is_bounded(bounds, bh, cexp)) return;          // whole workgroup: before any barrier
     const int b = bh / heads, h = bh % heads;
@@ -974,36 +981,33 @@ attn_sp_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const
     }
 }
 
-// Split plan for the bf16 head-dim-64 kernel (see attn_mfma_kernel): how many work items run
-// whole, and how many ways the rest is split along the keys.
-struct AttnPlan { int qblocks, items, full, nsplit, pieces, bq; };
+// Split plan for the bf16 head-dim-64 kernels (see AttnGrid): per sample, how many work items run whole and how
+// many ways the rest is split along the keys.
+struct AttnPlan { int qblocks, items_ps, full_ps, tail_ps, nsplit, bq; };
 static int compute_units() {
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-            cus = 256;
-    }
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        cus = 256;
     return cus;
 }
 // kernel path 3 sends every head to the reference-tracking kernel; otherwise heads with provably bounded
 // exponents take the check-free software-pipelined kernel
-static bool attention_bounded_path(int heads) { return get_kernel_path() != 3 && heads <= BOUND_MAX_HEADS; }
-static AttnPlan attention_plan(int batch, int seq, int heads) {
+static bool attention_bounded_path(int heads, int path) { return (path & 0xff) != 3 && heads <= BOUND_MAX_HEADS; }
+static AttnPlan attention_plan(int seq, int heads) {
     constexpr int KV = 64;
     AttnPlan p;
     p.bq = 256;
     p.qblocks = (seq + p.bq - 1) / p.bq;
-    p.items = p.qblocks * heads * batch;
+    p.items_ps = p.qblocks * heads;
     const int slots = compute_units() * 2;               // two resident workgroups per CU
-    const int tail = p.items % slots;
+    const int tail = p.items_ps % slots;
     const int ntiles = (seq + KV - 1) / KV;
     int ns = tail > 0 ? slots / tail : 1;
     if (ns > 8) ns = 8;
     if (ns > ntiles / 2) ns = ntiles / 2;
-    if (tail == 0 || p.items < slots || ns < 2) { p.full = p.items; p.nsplit = 1; p.pieces = 0; }
-    else { p.full = p.items - tail; p.nsplit = ns; p.pieces = tail * ns; }
+    if (tail == 0 || p.items_ps < slots || ns < 2) { p.full_ps = p.items_ps; p.tail_ps = 0; p.nsplit = 1; }
+    else { p.full_ps = p.items_ps - tail; p.tail_ps = tail; p.nsplit = ns; }
     return p;
 }
 
@@ -1012,19 +1016,19 @@ static size_t bounds_bytes(int batch, int heads) { return (((size_t)batch * head
 // workspace of the bf16 head-dim-64 kernels: [2 floats per (batch, head): norm bounds | key-split pieces]
 size_t attention_workspace_bytes(int dtype, int batch, int seq, int heads, int head_dim) {
     if (dtype != PS_BF16 || head_dim != 64 || batch < 1 || seq < 1 || heads < 1) return 0;
-    const AttnPlan p = attention_plan(batch, seq, heads);
-    const size_t need = (size_t)p.pieces * p.bq * PART_STRIDE * sizeof(float);
+    const AttnPlan p = attention_plan(seq, heads);
+    const size_t need = (size_t)batch * p.tail_ps * p.nsplit * p.bq * PART_STRIDE * sizeof(float);
     return bounds_bytes(batch, heads) + need;
 }
 
-bool attention_uses_mfma(int dtype, int head_dim) {
-    return dtype == PS_BF16 && head_dim == 64 && get_kernel_path() != 1;
+bool attention_uses_mfma(int dtype, int head_dim, int path) {
+    return dtype == PS_BF16 && head_dim == 64 && (path & 0xff) != 1;
 }
 
-float* attention_norm_bounds(int dtype, int batch, int heads, int head_dim, void* ws, hipStream_t st, bool clear,
-                             int* count) {
+float* attention_norm_bounds(int dtype, int batch, int heads, int head_dim, void* ws, int path, hipStream_t st,
+                             bool clear, int* count) {
     if (count) *count = 0;
-    if (!ws || !attention_uses_mfma(dtype, head_dim) || !attention_bounded_path(heads)) return nullptr;
+    if (!ws || !attention_uses_mfma(dtype, head_dim, path) || !attention_bounded_path(heads, path)) return nullptr;
     const int nb = batch * heads * 2;
     if (count) *count = nb;
     if (!clear) return (float*)ws;
@@ -1034,19 +1038,24 @@ float* attention_norm_bounds(int dtype, int batch, int heads, int head_dim, void
 
 hipError_t launch_attention(int dtype, const void* q, const void* k, const void* v, void* o,
                             int batch, int seq, int heads, int head_dim, float scale,
-                            const AttnStrides& s, void* ws, hipStream_t st, bool q_prescaled, bool bounds_ready) {
-    if (attention_uses_mfma(dtype, head_dim)) {
+                            const AttnStrides& s, void* ws, int path, hipStream_t st, bool q_prescaled,
+                            bool bounds_ready) {
+    if (attention_uses_mfma(dtype, head_dim, path)) {
         if (ws == nullptr) return hipErrorInvalidValue;
         if (s.k_tok >= (1 << 24) || s.v_tok >= (1 << 24)) return hipErrorInvalidValue;   // 32-bit in-tile offsets
-        const bool bounded = attention_bounded_path(heads);
-        AttnPlan p = attention_plan(batch, seq, heads);
-        if (get_kernel_path() == 2) { p.full = p.items; p.nsplit = 1; p.pieces = 0; }
+        const bool bounded = attention_bounded_path(heads, path);
+        AttnPlan p = attention_plan(seq, heads);
+        if ((path & 0xff) == 2) { p.full_ps = p.items_ps; p.tail_ps = 0; p.nsplit = 1; }
         const float c = scale * 1.4426950408889634f;
         const float cexp = q_prescaled ? 1.0f : c;
         const bf16_t *qq = (const bf16_t*)q, *kk = (const bf16_t*)k, *vv = (const bf16_t*)v;
         float* bounds = (float*)ws;
         float* part = (float*)((char*)ws + bounds_bytes(batch, heads));
         const int bq = p.bq;
+        const AttnGrid split{p.qblocks, heads, p.full_ps, p.tail_ps, p.nsplit, batch * p.full_ps};
+        const AttnGrid whole{p.qblocks, heads, p.items_ps, 0, 1, batch * p.items_ps};
+        const int split_blocks = batch * (p.full_ps + p.tail_ps * p.nsplit);
+        const int nitems = batch * p.tail_ps;
         if (bounded) {
             // norm bounds per (batch, head), then the check-free kernel for the heads they qualify and the
             // reference-tracking kernel (unsplit) for the others; each workgroup looks its head up
@@ -1057,40 +1066,36 @@ hipError_t launch_attention(int dtype, const void* q, const void* k, const void*
                                                                                                  bounds);
             }
             if (q_prescaled)
-                attn_sp_kernel<true><<<p.full + p.pieces, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c, p.qblocks, s,
-                                                                        p.full, p.nsplit, part, bounds);
+                attn_sp_kernel<true><<<split_blocks, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, c, s, split, part, bounds);
             else
-                attn_sp_kernel<false><<<p.full + p.pieces, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c, p.qblocks,
-                                                                         s, p.full, p.nsplit, part, bounds);
+                attn_sp_kernel<false><<<split_blocks, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, c, s, split, part, bounds);
             // then the reference-tracking kernel (unsplit) for the other heads; the merge of attn_sp_kernel's pieces
             // rides on that launch as workgroups in front of the items
-            const int nitems = p.items - p.full;
-            MergeTail mt{part, 0, p.full, p.nsplit, nitems, bq, cexp};
+            MergeTail mt{part, 0, nitems, bq, cexp, split};
             // (a multiple of 8 workgroups, so that the items keep their place in the round-robin over the 8 XCDs)
-            if (p.pieces != 0) mt.blocks = ((int)(((long)nitems * bq * 16 + 255) / 256) + 7) & ~7;
+            if (nitems != 0) mt.blocks = ((int)(((long)nitems * bq * 16 + 255) / 256) + 7) & ~7;
             if (q_prescaled)
-                attn_mfma_kernel<2, true><<<p.items + mt.blocks, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c,
-                                                                              p.qblocks, s, p.items, 1, nullptr, bounds, mt);
+                attn_mfma_kernel<2, true><<<whole.all_full + mt.blocks, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, c, s,
+                                                                                    whole, nullptr, bounds, mt);
             else
-                attn_mfma_kernel<2, false><<<p.items + mt.blocks, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c,
-                                                                               p.qblocks, s, p.items, 1, nullptr, bounds, mt);
+                attn_mfma_kernel<2, false><<<whole.all_full + mt.blocks, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, c, s,
+                                                                                     whole, nullptr, bounds, mt);
             return hipGetLastError();
         }
         // (one 32-query tile per wave, i.e. 128-query workgroups at three per CU, measured 9 % slower:
         // it doubles the K/V traffic into LDS and the fragment reads per MFMA)
-        const MergeTail none{nullptr, 0, 0, 0, 0, 0, 0.f};
+        const MergeTail none{nullptr, 0, 0, 0, 0.f, whole};
         if (q_prescaled)
-            attn_mfma_kernel<2, true><<<p.full + p.pieces, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c, p.qblocks,
-                                                                         s, p.full, p.nsplit, part, nullptr, none);
+            attn_mfma_kernel<2, true><<<split_blocks, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, c, s, split, part, nullptr,
+                                                                   none);
         else
-            attn_mfma_kernel<2, false><<<p.full + p.pieces, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, heads, c,
-                                                                          p.qblocks, s, p.full, p.nsplit, part, nullptr, none);
+            attn_mfma_kernel<2, false><<<split_blocks, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, c, s, split, part, nullptr,
+                                                                    none);
         hipError_t err = hipGetLastError();
-        if (err != hipSuccess || p.pieces == 0) return err;
-        const int nitems = p.items - p.full;
+        if (err != hipSuccess || nitems == 0) return err;
         const long threads = (long)nitems * bq * 16;
-        attn_merge_kernel<<<(unsigned)((threads + 255) / 256), 256, 0, st>>>(part, (bf16_t*)o, seq, heads, p.qblocks,
-                                                                            p.full, p.nsplit, nitems, cexp, bq, s, nullptr);
+        attn_merge_kernel<<<(unsigned)((threads + 255) / 256), 256, 0, st>>>(part, (bf16_t*)o, seq, split, nitems, cexp, bq,
+                                                                            s, nullptr);
         return hipGetLastError();
     }
     if (q_prescaled) return hipErrorInvalidValue;     // only the MFMA kernel takes pre-scaled queries

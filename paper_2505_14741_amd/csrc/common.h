@@ -69,16 +69,29 @@ struct Epilogue {
     size_t split_ws_bytes;
 };
 
+// Kernel path: a per-call selector handed down from the entry points (a field of the `dit` handle, an argument of
+// the stand-alone calls); nothing process-wide selects kernels.  Low byte = mode: 0 the fastest kernel for each
+// shape, 1 the generic fp32-FMA kernels, 2 bf16 attention without the key split of its last partial round,
+// 3 bf16 head-dim-64 attention always through the kernel that tracks a softmax reference, 4 projections whose
+// last partial round is not divided along K.  Bits 8-11: tile variant of the bf16 MFMA GEMM (0 automatic,
+// 1: 256x256, 2: 128x128, 3: 192x256, 4: 192x128).
+constexpr int PS_PATH_MAX_VARIANT = 4;
+inline bool kernel_path_valid(int path) {
+    return path >= 0 && (path & ~0xfff) == 0 && (path & 0xff) <= 4 && ((path >> 8) & 0xf) <= PS_PATH_MAX_VARIANT;
+}
+
+// The M rows of a projection are `batch` samples of `tokens` rows each; every sample is tiled on its own, so a
+// sample's result is bit-identical whatever batch it is computed in.
 // scratch that lets launch_gemm split its last partial round along K (0: the shape does not profit)
-size_t gemm_split_workspace_bytes(int dtype, int M, int Nn, int K);
+size_t gemm_split_workspace_bytes(int dtype, int batch, int tokens, int Nn, int K, int path);
 // whether launch_gemm sends a bf16 shape to the MFMA kernel (EPI_UNPATCHIFY exists only there)
-bool gemm_uses_mfma(int dtype, int M, int Nn, int K);
+bool gemm_uses_mfma(int dtype, int tokens, int Nn, int K, int path);
 
 // ---- launchers (each validates nothing; callers have checked shapes) -----------------
-// C[M, Nn] = A[M, K] * W[Nn, K]^T with epilogue.  A, W, C in `dtype` (C ignored for
-// EPI_GATE_RESIDUAL).  lda/ldc in elements.
-hipError_t launch_gemm(int dtype, const void* A, const void* W, void* C, int M, int Nn, int K,
-                       const Epilogue& epi, hipStream_t st);
+// C[batch * tokens, Nn] = A[batch * tokens, K] * W[Nn, K]^T with epilogue.  A, W, C in `dtype` (C ignored for
+// EPI_GATE_RESIDUAL).
+hipError_t launch_gemm(int dtype, const void* A, const void* W, void* C, int batch, int tokens, int Nn, int K,
+                       const Epilogue& epi, int path, hipStream_t st);
 
 // Full attention with explicit strides (in elements) for token, head and batch.
 struct AttnStrides { long q_tok, q_head, q_batch, k_tok, k_head, k_batch, v_tok, v_head, v_batch,
@@ -86,21 +99,19 @@ struct AttnStrides { long q_tok, q_head, q_batch, k_tok, k_head, k_batch, v_tok,
 // `ws` is scratch of attention_workspace_bytes() bytes (may be NULL when that is 0).
 size_t attention_workspace_bytes(int dtype, int batch, int seq, int heads, int head_dim);
 // q_prescaled: q already carries scale*log2(e) (only valid when attention_uses_mfma()).
-bool attention_uses_mfma(int dtype, int head_dim);
+bool attention_uses_mfma(int dtype, int head_dim, int path);
 // bounds_ready: the per-(batch, head) norm maxima at the head of `ws` are already in place (see
 // attention_norm_bounds()), so the pass over q and k that finds them is skipped.
 hipError_t launch_attention(int dtype, const void* q, const void* k, const void* v, void* o,
                             int batch, int seq, int heads, int head_dim, float scale,
-                            const AttnStrides& s, void* ws, hipStream_t st, bool q_prescaled = false,
+                            const AttnStrides& s, void* ws, int path, hipStream_t st, bool q_prescaled = false,
                             bool bounds_ready = false);
 // Where a producer of q and k may leave those maxima itself: zeroes [batch*heads][2] floats at the head of `ws`
 // on the stream and returns their address; nullptr if this shape's attention does not use them.
 // the per-(batch, head) norm maxima buffer of the bounded attention path inside ws (nullptr if that path is off);
 // *count = its length in floats; clear: zero it with a launch of its own (else the caller zeroes it before use)
-float* attention_norm_bounds(int dtype, int batch, int heads, int head_dim, void* ws, hipStream_t st, bool clear = true,
-                             int* count = nullptr);
-void set_kernel_path(int p);
-int get_kernel_path();
+float* attention_norm_bounds(int dtype, int batch, int heads, int head_dim, void* ws, int path, hipStream_t st,
+                             bool clear = true, int* count = nullptr);
 
 hipError_t launch_sinusoid(const int32_t* t_host, float* out, int batch, int D, hipStream_t st);
 // out[b, r] = act(W[r,:] . in[b,:] + bias[r]);  act: 0 none, 1 SiLU.  W in dtype, in/out fp32.

@@ -6,14 +6,6 @@
 
 namespace ps {
 
-void set_gemm_variant(int v);
-static int g_kernel_path = 0;   // 0 auto, 1 force the generic kernels, 0x100|v force MFMA GEMM tile variant v
-void set_kernel_path(int p) {
-    g_kernel_path = p;
-    set_gemm_variant((p & 0x100) ? (p & 0xff) : 0);
-}
-int get_kernel_path() { return g_kernel_path; }
-
 // 64x64 output tile, 16-deep K slices, 256 threads, 4x4 outputs per thread.
 template <typename T, int KIND>
 __global__ void __launch_bounds__(256)
@@ -82,23 +74,24 @@ static hipError_t launch_generic(const T* A, const T* W, T* C, int M, int Nn, in
     return hipGetLastError();
 }
 
-bool gemm_mfma_supported(int M, int Nn, int K);
-hipError_t launch_gemm_mfma(const bf16_t* A, const bf16_t* W, bf16_t* C, int M, int Nn, int K,
-                            const Epilogue& ep, hipStream_t st);
+bool gemm_mfma_supported(int tokens, int Nn, int K);
+hipError_t launch_gemm_mfma(const bf16_t* A, const bf16_t* W, bf16_t* C, int batch, int tokens, int Nn, int K,
+                            const Epilogue& ep, int path, hipStream_t st);
 
-bool gemm_uses_mfma(int dtype, int M, int Nn, int K) {
-    return dtype == PS_BF16 && g_kernel_path != 1 && gemm_mfma_supported(M, Nn, K);
+bool gemm_uses_mfma(int dtype, int tokens, int Nn, int K, int path) {
+    return dtype == PS_BF16 && (path & 0xff) != 1 && gemm_mfma_supported(tokens, Nn, K);
 }
 
-hipError_t launch_gemm(int dtype, const void* A, const void* W, void* C, int M, int Nn, int K,
-                       const Epilogue& epi, hipStream_t st) {
-    if (M <= 0 || Nn <= 0 || K <= 0 || (Nn & 1)) return hipErrorInvalidValue;
-    if (epi.kind == EPI_UNPATCHIFY && !gemm_uses_mfma(dtype, M, Nn, K)) return hipErrorInvalidValue;
-    if (dtype == PS_BF16) {
-        if (g_kernel_path != 1 && gemm_mfma_supported(M, Nn, K))
-            return launch_gemm_mfma((const bf16_t*)A, (const bf16_t*)W, (bf16_t*)C, M, Nn, K, epi, st);
+hipError_t launch_gemm(int dtype, const void* A, const void* W, void* C, int batch, int tokens, int Nn, int K,
+                       const Epilogue& epi, int path, hipStream_t st) {
+    if (batch <= 0 || tokens <= 0 || Nn <= 0 || K <= 0 || (Nn & 1)) return hipErrorInvalidValue;
+    const bool mfma = gemm_uses_mfma(dtype, tokens, Nn, K, path);
+    if (epi.kind == EPI_UNPATCHIFY && !mfma) return hipErrorInvalidValue;
+    if (mfma)
+        return launch_gemm_mfma((const bf16_t*)A, (const bf16_t*)W, (bf16_t*)C, batch, tokens, Nn, K, epi, path, st);
+    const int M = batch * tokens;                    // (the generic kernel forms 64-bit offsets)
+    if (dtype == PS_BF16)
         return launch_generic<bf16_t>((const bf16_t*)A, (const bf16_t*)W, (bf16_t*)C, M, Nn, K, epi, st);
-    }
     return launch_generic<float>((const float*)A, (const float*)W, (float*)C, M, Nn, K, epi, st);
 }
 

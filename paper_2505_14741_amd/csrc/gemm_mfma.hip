@@ -537,31 +537,62 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, const bf
     }
 }
 
-// The first full_tiles workgroups compute one BM x BN output tile each.  The tiles beyond them -- the last, partial
-// round of the chip's workgroup slots -- can be shared out so that the round is shorter: with nsplit > 1, nsplit
-// workgroups per tile along K, fp32 partial sums to ep.split_ws (in accumulator layout) for gemm_tail_kernel (the
-// narrow tile where K is long).  (Dropped: two workgroups per tail tile of the wide tile, one per half of its rows.
-// With operands resident in the cache from the previous launch it was 2 % faster; with weights and activations
-// that change from call to call, as in the network, 1-4 % slower -- each half loads the whole W panel again.)
+// Every sample of a batch (rows [b * tokens, (b+1) * tokens) of the operands) is tiled on its own: a tile never
+// holds rows of two samples, and which of its tiles are summed in K pieces depends on the sample's shape alone,
+// so a sample's result does not depend on the batch it is computed in (Section 3.3: the batched step must
+// reproduce the per-step process).  A workgroup shifts the operand, output, residual, modulation and norm-maximum
+// pointers to its sample and from then on works on a [tokens, Nn] problem.
+//
+// The first batch * full_tiles workgroups compute one BM x BN output tile each.  The tiles beyond them -- the last,
+// partial round of the chip's workgroup slots, per sample -- can be shared out so that the round is shorter: with
+// nsplit > 1, nsplit workgroups per tile along K, fp32 partial sums to ep.split_ws (in accumulator layout) for
+// gemm_tail_kernel (the narrow tile where K is long).  (Dropped: two workgroups per tail tile of the wide tile,
+// one per half of its rows.  With operands resident in the cache from the previous launch it was 2 % faster;
+// with weights and activations that change from call to call, as in the network, 1-4 % slower -- each half
+// loads the whole W panel again.)
+struct GemmGrid { int tokens, batch, tiles_m, tiles_n, full_tiles, tail_tiles, nsplit; };
+
+__device__ __forceinline__ void shift_to_sample(Epilogue& ep, int sample, int tokens, int Nn) {
+    if (sample == 0) return;
+    if (ep.kind == EPI_GATE_RESIDUAL) {
+        ep.resid += (long)sample * tokens * Nn;
+        ep.mod_layer += (long)sample * ep.mod_batch_stride;
+    } else if (ep.kind == EPI_QKV_ROPE) {
+        if (ep.norm_bounds) ep.norm_bounds += 2L * sample * ep.heads;
+    } else if (ep.kind == EPI_UNPATCHIFY) {
+        ep.resid += (long)sample * ep.pg.C * ep.pg.F * ep.pg.H * ep.pg.W;
+    }
+}
+
 template <int BM, int BN, int WR, int WC, int BK, int NST, int KIND>
-__global__ void __launch_bounds__(WR * WC * 64, (WR * WC == 4 && BM * BN <= 128 * 128) ? 2 : 1)
+__global__ void __launch_bounds__(WR * WC * 64, (WR * WC == 4 && BM * BN <= 192 * 128) ? 2 : 1)
 gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf16_t* __restrict__ C,
-                 int M, int Nn, int K, int tiles_m, int tiles_n, int full_tiles, int nsplit, Epilogue ep) {
+                 int Nn, int K, GemmGrid g, Epilogue ep) {
     __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * (BM + BN) * BK * 2];
     const int nk = K / BK;
-    int tile, piece = -1, k0 = 0, k1 = nk;
-    if ((int)blockIdx.x < full_tiles) {
-        tile = xcd_remap(blockIdx.x, full_tiles);
+    const int all_full = g.batch * g.full_tiles;
+    int sample, tile, piece = -1, k0 = 0, k1 = nk;
+    if ((int)blockIdx.x < all_full) {
+        const int id = xcd_remap(blockIdx.x, all_full);
+        sample = id / g.full_tiles;
+        tile = id - sample * g.full_tiles;
     } else {
-        piece = blockIdx.x - full_tiles;
-        tile = full_tiles + piece / nsplit;
-        const int pi = piece % nsplit;
-        k0 = nk * pi / nsplit;
-        k1 = nk * (pi + 1) / nsplit;
+        piece = blockIdx.x - all_full;                   // index of the partial sums in ep.split_ws
+        const int per_sample = g.tail_tiles * g.nsplit;
+        sample = piece / per_sample;
+        const int lp = piece - sample * per_sample;
+        tile = g.full_tiles + lp / g.nsplit;
+        const int pi = lp % g.nsplit;
+        k0 = nk * pi / g.nsplit;
+        k1 = nk * (pi + 1) / g.nsplit;
     }
+    sample = __builtin_amdgcn_readfirstlane(sample);
+    A += (long)sample * g.tokens * K;
+    if (C) C += (long)sample * g.tokens * Nn;
+    shift_to_sample(ep, sample, g.tokens, Nn);
     int m0, n0;
-    tile_origin(tile, tiles_m, tiles_n, BM, BN, m0, n0);
-    gemm_tile<BM, BN, WR, WC, BK, NST, KIND>(A, W, C, M, Nn, K, m0, n0, k0, k1, piece, ep, lds);
+    tile_origin(tile, g.tiles_m, g.tiles_n, BM, BN, m0, n0);
+    gemm_tile<BM, BN, WR, WC, BK, NST, KIND>(A, W, C, g.tokens, Nn, K, m0, n0, k0, k1, piece, ep, lds);
 }
 
 // Sums the K-split pieces of the tail tiles (fixed order: deterministic) and applies the epilogue; one
@@ -569,18 +600,21 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
 // as many compute units: the kernel is a chain of dependent loads).
 template <int BM, int BN, int WR, int WC, int KIND>
 __global__ void __launch_bounds__(64)
-gemm_tail_kernel(bf16_t* __restrict__ C, int M, int Nn, int tiles_m, int tiles_n, int full_tiles, int nsplit,
-                 Epilogue ep) {
+gemm_tail_kernel(bf16_t* __restrict__ C, int Nn, GemmGrid g, Epilogue ep) {
     constexpr int NW = WR * WC;
     constexpr int WM = BM / WR, WN = BN / WC;
     constexpr int TM = WM / 32, TN = WN / 32;
     __shared__ __attribute__((aligned(16))) float patch[EPI_LDS_FLOATS];
     const int lane = threadIdx.x;
-    const int wave = blockIdx.x % NW, tail = blockIdx.x / NW;
+    const int wave = blockIdx.x % NW, tail = blockIdx.x / NW;      // tail: over all samples
     const int wm = wave / WC, wn = wave % WC;
-    const int tile = full_tiles + tail;
+    const int sample = tail / g.tail_tiles;
+    const int tile = g.full_tiles + tail % g.tail_tiles;
+    if (C) C += (long)sample * g.tokens * Nn;
+    shift_to_sample(ep, sample, g.tokens, Nn);
+    const int M = g.tokens, nsplit = g.nsplit;
     int m0, n0;
-    tile_origin(tile, tiles_m, tiles_n, BM, BN, m0, n0);
+    tile_origin(tile, g.tiles_m, g.tiles_n, BM, BN, m0, n0);
     f32x4_t acc[TM][TN][4];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -603,95 +637,136 @@ gemm_tail_kernel(bf16_t* __restrict__ C, int M, int Nn, int tiles_m, int tiles_n
         wave_epilogue<TM, TN, 2, KIND, true>(acc, ep, C, M, Nn, m0 + wm * WM, n0 + wn * WN + 64, lane, patch);
 }
 
-bool gemm_mfma_supported(int M, int Nn, int K) {
-    return K % 64 == 0 && Nn % 4 == 0 && M >= 1 && Nn >= 64 && K >= 64 && (long)M * Nn < (1L << 31);
+// `tokens` rows per sample; offsets inside a sample are 32-bit element indices
+bool gemm_mfma_supported(int tokens, int Nn, int K) {
+    return K % 64 == 0 && Nn % 4 == 0 && tokens >= 1 && Nn >= 64 && K >= 64 && (long)tokens * Nn < (1L << 31);
 }
 
-// How a shape is spread over the chip: which tile variant, how many tiles run whole and how the rest is split.
-struct GemmPlan { int variant, tiles_m, tiles_n, full, nsplit, pieces; size_t ws_bytes; };
+// How a sample's [tokens, Nn] output is spread over the chip: which tile variant, how many tiles run whole and
+// how the rest is split.  A function of the sample's shape only (never of the batch): see gemm_mfma_kernel.
+struct GemmPlan { int variant, bm, bn, per_cu, tiles_m, tiles_n, full, tail, nsplit; size_t ws_bytes_per_sample; };
 static int gemm_compute_units() {
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-            cus = 256;
-    }
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        cus = 256;
     return cus;
 }
-static int g_gemm_variant = 0;   // tuning hook: 0 auto
-void set_gemm_variant(int v) { g_gemm_variant = v; }
 
-static GemmPlan gemm_plan(int M, int Nn, int K, bool allow_split) {
-    GemmPlan p{};
-    p.variant = g_gemm_variant;
-    if (p.variant == 0) {
-        // measured at 17776 tokens: wide outputs are better off with the 256x256 tile's lower L2
-        // traffic; narrow ones with two co-resident 128x128 workgroups that hide each other's epilogue
-        p.variant = (M >= 1024 && Nn >= 5760) ? 1 : 2;
-    }
-    const bool big = p.variant == 1;
-    const int bm = big ? 256 : 128, bn = bm;
-    p.tiles_m = (M + bm - 1) / bm;
-    p.tiles_n = (Nn + bn - 1) / bn;
-    const int tiles = p.tiles_m * p.tiles_n;
-    p.full = tiles; p.nsplit = 1; p.pieces = 0; p.ws_bytes = 0;
-    // the last partial round: split along K if the partial sums (two passes over tile-size fp32 per piece) and
-    // the second launch cost less than the round they save -- measured at 17776 tokens: true for the 128x128
-    // tile with a long K (fc2: 0.62 -> 0.57 ms), not for K = 1920 (0.188 -> 0.196 ms) nor for the 256x256 tile
-    const int slots = gemm_compute_units() * (big ? 1 : 2);
+struct TileVariant { int bm, bn, per_cu; float cost; };
+// cost: measured time per output of a full round of workgroup slots, relative to the 256x256 tile, inside the
+// 30-layer network at 17776 and 33976 tokens.  The loop is bound by LDS traffic (fragment reads plus the direct
+// loads' writes, 128 bytes per clock and CU): a wave tile of 128x64 reads 12 fragments per 32 MFMAs, 96x64 10 per
+// 24, 64x64 8 per 16; two co-resident workgroups win some of it back by hiding each other's epilogue.
+static const TileVariant kVariants[5] = {
+    {0, 0, 0, 0.f},
+    {256, 256, 1, 1.00f},     // 1: 8 waves of 128x64
+    {128, 128, 2, 1.17f},     // 2: 4 waves of 64x64, two workgroups per CU
+    {192, 256, 1, 1.10f},     // 3: 8 waves of 96x64
+    {192, 128, 2, 1.10f},     // 4: 4 waves of 96x64, two workgroups per CU
+};
+
+// the K split of the last partial round: pieces per tail tile (1: none)
+static int tail_split(int tiles, int slots, int K, bool allow_split) {
     const int tail = tiles % slots, nk = K / 64;
-    if (allow_split && !big && K >= 4096 && tail > 0 && tiles > slots) {
-        int ns = slots / tail;
-        if (ns > 8) ns = 8;
-        if (ns > nk / 2) ns = nk / 2;
-        if (ns >= 2) {
-            p.full = tiles - tail; p.nsplit = ns; p.pieces = tail * ns;
-            p.ws_bytes = (size_t)p.pieces * bm * bn * sizeof(float);
+    if (!allow_split || K < 4096 || tail == 0 || tiles <= slots) return 1;
+    int ns = slots / tail;
+    if (ns > 8) ns = 8;
+    if (ns > nk / 2) ns = nk / 2;
+    return ns >= 2 ? ns : 1;
+}
+
+static GemmPlan gemm_plan(int batch, int tokens, int Nn, int K, bool allow_split, int forced_variant) {
+    GemmPlan p{};
+    const int cus = gemm_compute_units();
+    int v = forced_variant;
+    if (v < 1 || v > 4) {
+        // the variant with the least estimated time: rounds of workgroup slots (a K-split tail counts as 1/pieces of
+        // a round plus a fifth of a round for its partial sums and second launch) x tile area x the tile's cost
+        // per output.  Outputs with fewer tiles than slots take the smallest tile.
+        // Which tiles are summed in K pieces depends on the variant, and must not depend on the batch: where a split
+        // is possible (long K) the choice looks at one sample; elsewhere the variant never changes a value and the
+        // choice may count the tiles of the whole batch.
+        const bool may_split = allow_split && K >= 4096;
+        const int nb = may_split ? 1 : batch;
+        float best = 0.f;
+        v = 2;
+        for (int c = 1; c <= 4; ++c) {
+            const TileVariant& t = kVariants[c];
+            const int tiles = nb * ((tokens + t.bm - 1) / t.bm) * ((Nn + t.bn - 1) / t.bn);
+            const int slots = cus * t.per_cu;
+            if (tiles < slots) continue;
+            const int ns = tail_split(tiles, slots, K, may_split);
+            float rounds = (float)(tiles / slots);
+            if (tiles % slots) rounds += ns > 1 ? 1.0f / ns + 0.2f : 1.0f;
+            const float est = rounds * slots * t.bm * t.bn * t.cost;
+            if (best == 0.f || est < best) { best = est; v = c; }
         }
+    }
+    const TileVariant& t = kVariants[v];
+    p.variant = v; p.bm = t.bm; p.bn = t.bn; p.per_cu = t.per_cu;
+    p.tiles_m = (tokens + p.bm - 1) / p.bm;
+    p.tiles_n = (Nn + p.bn - 1) / p.bn;
+    const int tiles = p.tiles_m * p.tiles_n;
+    p.full = tiles; p.tail = 0; p.nsplit = 1; p.ws_bytes_per_sample = 0;
+    // the last partial round: split along K if the partial sums (two passes over tile-size fp32 per piece) and
+    // the second launch cost less than the round they save -- measured at 17776 tokens: true with a long K
+    // (fc2 on 128x128 tiles: 0.62 -> 0.57 ms), not for K = 1920 (0.188 -> 0.196 ms)
+    const int slots = cus * p.per_cu;
+    const int ns = tail_split(tiles, slots, K, allow_split);
+    if (ns > 1) {
+        const int tail = tiles % slots;
+        p.full = tiles - tail; p.tail = tail; p.nsplit = ns;
+        p.ws_bytes_per_sample = (size_t)tail * ns * p.bm * p.bn * sizeof(float);
     }
     return p;
 }
 
-size_t gemm_split_workspace_bytes(int dtype, int M, int Nn, int K) {
-    if (dtype != PS_BF16 || !gemm_mfma_supported(M, Nn, K)) return 0;
-    return gemm_plan(M, Nn, K, true).ws_bytes;
+// kernel path: low byte = mode (4: never split a tail along K), bits 8-11 = forced tile variant (0: automatic)
+static int forced_variant_of(int path) { return (path >> 8) & 0xf; }
+
+size_t gemm_split_workspace_bytes(int dtype, int batch, int tokens, int Nn, int K, int path) {
+    if (dtype != PS_BF16 || !gemm_mfma_supported(tokens, Nn, K) || (path & 0xff) == 4) return 0;
+    return gemm_plan(batch, tokens, Nn, K, true, forced_variant_of(path)).ws_bytes_per_sample * (size_t)batch;
 }
 
 template <int BM, int BN, int WR, int WC, int BK, int NST, int KIND>
-static hipError_t launch_kind(const bf16_t* A, const bf16_t* W, bf16_t* C, int M, int Nn, int K, const GemmPlan& p,
-                              const Epilogue& ep, hipStream_t st) {
+static hipError_t launch_kind(const bf16_t* A, const bf16_t* W, bf16_t* C, int batch, int tokens, int Nn, int K,
+                              const GemmPlan& p, const Epilogue& ep, hipStream_t st) {
     dim3 block(WR * WC * 64);
-    gemm_mfma_kernel<BM, BN, WR, WC, BK, NST, KIND><<<p.full + p.pieces, block, 0, st>>>(A, W, C, M, Nn, K, p.tiles_m, p.tiles_n,
-                                                                                p.full, p.nsplit, ep);
+    const GemmGrid g{tokens, batch, p.tiles_m, p.tiles_n, p.full, p.tail, p.nsplit};
+    const int grid = batch * (p.full + p.tail * p.nsplit);
+    gemm_mfma_kernel<BM, BN, WR, WC, BK, NST, KIND><<<grid, block, 0, st>>>(A, W, C, Nn, K, g, ep);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || p.pieces == 0) return e;
-    gemm_tail_kernel<BM, BN, WR, WC, KIND><<<p.pieces / p.nsplit * (WR * WC), 64, 0, st>>>(C, M, Nn, p.tiles_m, p.tiles_n, p.full,
-                                                                                  p.nsplit, ep);
+    if (e != hipSuccess || p.tail == 0) return e;
+    gemm_tail_kernel<BM, BN, WR, WC, KIND><<<batch * p.tail * (WR * WC), 64, 0, st>>>(C, Nn, g, ep);
     return hipGetLastError();
 }
 
 template <int BM, int BN, int WR, int WC, int BK, int NST>
-static hipError_t launch_tile(const bf16_t* A, const bf16_t* W, bf16_t* C, int M, int Nn, int K, const GemmPlan& p,
-                              const Epilogue& ep, hipStream_t st) {
+static hipError_t launch_tile(const bf16_t* A, const bf16_t* W, bf16_t* C, int batch, int tokens, int Nn, int K,
+                              const GemmPlan& p, const Epilogue& ep, hipStream_t st) {
     switch (ep.kind) {
-        case EPI_BIAS: return launch_kind<BM, BN, WR, WC, BK, NST, EPI_BIAS>(A, W, C, M, Nn, K, p, ep, st);
-        case EPI_BIAS_GELU: return launch_kind<BM, BN, WR, WC, BK, NST, EPI_BIAS_GELU>(A, W, C, M, Nn, K, p, ep, st);
-        case EPI_GATE_RESIDUAL: return launch_kind<BM, BN, WR, WC, BK, NST, EPI_GATE_RESIDUAL>(A, W, C, M, Nn, K, p, ep, st);
-        case EPI_QKV_ROPE: return launch_kind<BM, BN, WR, WC, BK, NST, EPI_QKV_ROPE>(A, W, C, M, Nn, K, p, ep, st);
-        case EPI_UNPATCHIFY: return launch_kind<BM, BN, WR, WC, BK, NST, EPI_UNPATCHIFY>(A, W, C, M, Nn, K, p, ep, st);
+        case EPI_BIAS: return launch_kind<BM, BN, WR, WC, BK, NST, EPI_BIAS>(A, W, C, batch, tokens, Nn, K, p, ep, st);
+        case EPI_BIAS_GELU: return launch_kind<BM, BN, WR, WC, BK, NST, EPI_BIAS_GELU>(A, W, C, batch, tokens, Nn, K, p, ep, st);
+        case EPI_GATE_RESIDUAL: return launch_kind<BM, BN, WR, WC, BK, NST, EPI_GATE_RESIDUAL>(A, W, C, batch, tokens, Nn, K, p, ep, st);
+        case EPI_QKV_ROPE: return launch_kind<BM, BN, WR, WC, BK, NST, EPI_QKV_ROPE>(A, W, C, batch, tokens, Nn, K, p, ep, st);
+        case EPI_UNPATCHIFY: return launch_kind<BM, BN, WR, WC, BK, NST, EPI_UNPATCHIFY>(A, W, C, batch, tokens, Nn, K, p, ep, st);
         default: return hipErrorInvalidValue;
     }
 }
 
-hipError_t launch_gemm_mfma(const bf16_t* A, const bf16_t* W, bf16_t* C, int M, int Nn, int K,
-                            const Epilogue& ep, hipStream_t st) {
-    const bool tails = (get_kernel_path() & 0xff) != 4;
-    GemmPlan p = gemm_plan(M, Nn, K, ep.split_ws != nullptr && tails);
-    if (p.ws_bytes > ep.split_ws_bytes) p = gemm_plan(M, Nn, K, false);
+hipError_t launch_gemm_mfma(const bf16_t* A, const bf16_t* W, bf16_t* C, int batch, int tokens, int Nn, int K,
+                            const Epilogue& ep, int path, hipStream_t st) {
+    const bool tails = (path & 0xff) != 4;
+    const int fv = forced_variant_of(path);
+    GemmPlan p = gemm_plan(batch, tokens, Nn, K, ep.split_ws != nullptr && tails, fv);
+    if (p.ws_bytes_per_sample * (size_t)batch > ep.split_ws_bytes) p = gemm_plan(batch, tokens, Nn, K, false, fv);
     switch (p.variant) {
-        case 1: return launch_tile<256, 256, 2, 4, 64, 2>(A, W, C, M, Nn, K, p, ep, st);   // 8 waves, 128x64 each
-        case 2: return launch_tile<128, 128, 2, 2, 64, 2>(A, W, C, M, Nn, K, p, ep, st);   // 4 waves, 64x64 each, 2 per CU
+        case 1: return launch_tile<256, 256, 2, 4, 64, 2>(A, W, C, batch, tokens, Nn, K, p, ep, st);   // 8 waves, 128x64 each
+        case 2: return launch_tile<128, 128, 2, 2, 64, 2>(A, W, C, batch, tokens, Nn, K, p, ep, st);   // 4 waves, 64x64 each, 2 per CU
+        case 3: return launch_tile<192, 256, 2, 4, 64, 2>(A, W, C, batch, tokens, Nn, K, p, ep, st);   // 8 waves, 96x64 each
+        case 4: return launch_tile<192, 128, 2, 2, 64, 2>(A, W, C, batch, tokens, Nn, K, p, ep, st);   // 4 waves, 96x64 each, 2 per CU
         // Measured and dropped: 4 waves of 128x128 outputs on the 256x256 tile (fewer LDS reads per MFMA; with the
         // 32x32x16 MFMA one wave per SIMD issued one only every ~48 cycles: 5-15 % slower; with 16x16x32 the 256
         // accumulator registers per lane make the compiler shuttle values between the two register files, 3-4

@@ -31,6 +31,20 @@ def close_fp32(got, ref, tol=1e-4):
     assert O.rel_mae(ref, got)[2] <= tol
 
 
+def worst_token(ref, got, patch):
+    """Largest per-token relative MAE of a predicted latent [B, C, F, H, W] (tokens = patches)."""
+    worst = 0.0
+    for b in range(ref.shape[0]):
+        r, g = O.patchify(ref[b], patch), O.patchify(got[b], patch)
+        per = np.abs(r - g).sum(axis=1) / np.maximum(np.abs(r).sum(axis=1), 1e-30)
+        worst = max(worst, float(per.max()))
+    return worst
+
+
+# bf16 whole-forward bound per token: the global bar is 2e-2 rel-MAE; a single token (64 output values at
+# the CogVideoX-2b shape) may lie above the average, a wrong tile of rows lies far above it (rel-MAE ~ 1)
+WORST_TOKEN_BF16 = 6e-2
+
 _CACHE = {}
 
 
@@ -76,19 +90,21 @@ def test_reduced_30_layer_forward_bf16(init):
     eps = host(B.dit_forward(d, dev(x), dev(ctx, torch.bfloat16), [500]))
     ref = O.dit_forward(cfg, W, x, ctx, [500])
     r = O.rel_mae(ref, eps)[2]
-    print(f"  rel-MAE {r:.3e}", flush=True)
+    worst = worst_token(ref, eps, cfg.patch)
+    print(f"  rel-MAE {r:.3e}, worst token {worst:.3e}", flush=True)
     assert r <= 2e-2 and np.isfinite(eps).all()
+    assert worst <= WORST_TOKEN_BF16
 
 
 def test_reduced_forward_generic_and_mfma_paths_agree():
     cfg, W, d = setup("reduced", "unit", cfg=I.CONFIGS["reduced"].with_(layers=2))
     x, ctx = dev(I.make_latent(cfg, 1)), dev(I.make_context(cfg, 1), torch.bfloat16)
     fast = host(B.dit_forward(d, x, ctx, [300]))
-    B.ps_set_kernel_path(1)
+    B.dit_set_kernel_path(d, 1)
     try:
         slow = host(B.dit_forward(d, x, ctx, [300]))
     finally:
-        B.ps_set_kernel_path(0)
+        B.dit_set_kernel_path(d, 0)
     assert O.rel_mae(slow, fast)[2] < 1e-2
 
 
@@ -119,8 +135,10 @@ def test_block_forward_bf16_whole(init):
     eps = host(B.dit_forward(d, dev(x), dev(ctx, torch.bfloat16), [500]))
     ref = O.dit_forward(cfg, W, x, ctx, [500])
     r = O.rel_mae(ref, eps)[2]
-    print(f"  rel-MAE {r:.3e}", flush=True)
+    worst = worst_token(ref, eps, cfg.patch)
+    print(f"  rel-MAE {r:.3e}, worst token {worst:.3e}", flush=True)
     assert r <= 2e-2
+    assert worst <= WORST_TOKEN_BF16
 
 
 @pytest.mark.parametrize("name", ["full", "long"])
@@ -276,8 +294,10 @@ def test_reduced_30_layer_reuse_run_bf16():
     ref = oracle_run(cfg, W, x_T, ctx, 6, 2, [2, 2])
     x0, sums, calls = gpu_run(d, dev(x_T), dev(ctx, torch.bfloat16), 6, 2, [2, 2])
     r = O.rel_mae(ref["x0"], host(x0)[0])[2]
-    print(f"  x0 rel-MAE {r:.3e}", flush=True)
+    worst = worst_token(ref["x0"][None], host(x0), cfg.patch)
+    print(f"  x0 rel-MAE {r:.3e}, worst token {worst:.3e}", flush=True)
     assert calls == 6 and r <= 2e-2
+    assert worst <= WORST_TOKEN_BF16
     # reuse changes the result but stays finite and reproducible; window 1 is the no-reuse run
     x0p, _, _ = gpu_run(d, dev(x_T), dev(ctx, torch.bfloat16), 6, 2, [1, 1, 1, 1])
     dev_r = host(B.rel_mae(x0p, x0))[2]
@@ -286,11 +306,12 @@ def test_reduced_30_layer_reuse_run_bf16():
     assert torch.equal(x0again, x0)
 
 
-def test_step_batched_round_at_full_shape_agrees_with_one_call_per_step():
+def test_step_batched_round_at_full_shape_equals_one_call_per_step_bitwise():
     """30 layers at 17776 tokens: one warm-up step and one cycle of four, as four calls and as one call of batch 4.
 
-    At this shape the batch moves the projections' and the attention's last partial round (whose tiles are summed in
-    pieces), so the two runs agree to rounding rather than bit for bit; the per-step sums agree likewise.
+    Every sample of a batch is tiled, split and summed as if it were alone (the attention's key split of its last
+    partial round and the projections' K split are planned per sample), so the batched round reproduces the
+    per-step process bit for bit, as Section 3.3 requires of BatchStep.
     """
     print("sampler_run full shape, cycle of four, batched against unbatched", flush=True)
     cfg = I.CONFIGS["full"]
@@ -301,10 +322,114 @@ def test_step_batched_round_at_full_shape_agrees_with_one_call_per_step():
     x0b, sb, cb = gpu_run(d, x_T, ctx, 5, 1, [4], batched=True)
     assert ca == 5 and cb == 2
     assert bool(torch.isfinite(x0a).all()) and bool(torch.isfinite(x0b).all())
-    r = float(host(B.rel_mae(x0b, x0a))[2])
-    print(f"  rel-MAE between the two runs {r:.3e}", flush=True)
-    assert r <= 2e-3
-    np.testing.assert_allclose(host(sb), host(sa), rtol=2e-3, atol=1e-6)
+    assert torch.equal(x0a, x0b)
+    assert torch.equal(sa, sb)
+
+
+def test_forward_batch_invariance_at_the_block_shape_bitwise():
+    """One block at 4516 tokens (attention splits its last 28 work items, fc2 its last tiles along K), batch 3 with
+    different timesteps against three single calls."""
+    cfg, W, d = setup("block", "unit")
+    x, ctx = dev(I.make_latent(cfg, 3)), dev(I.make_context(cfg, 3), torch.bfloat16)
+    t = [900, 500, 20]
+    full = B.dit_forward(d, x, ctx, t).clone()
+    for b in range(3):
+        one = B.dit_forward(d, x[b:b + 1].contiguous(), ctx[b:b + 1].contiguous(), t[b:b + 1])
+        assert torch.equal(one[0], full[b]), b
+
+
+def test_two_handles_with_different_kernel_paths_side_by_side():
+    """The kernel path belongs to the handle: a handle on the generic kernels and one on the MFMA kernels, used
+    in turn, each reproduce what they give alone; tile variants do not change a single bit."""
+    cfg = I.CONFIGS["reduced"].with_(layers=2)
+    weights = I.make_weights(cfg, 1000, "unit")
+    wd = B.weights_to_device(cfg, weights)
+    fast, slow, tiled = B.dit_create(cfg, wd), B.dit_create(cfg, wd), B.dit_create(cfg, wd)
+    B.dit_set_kernel_path(slow, 1)
+    B.dit_set_kernel_path(tiled, 0x300)
+    x, ctx = dev(I.make_latent(cfg, 2)), dev(I.make_context(cfg, 2), torch.bfloat16)
+    t = [300, 700]
+    alone_fast = B.dit_forward(fast, x, ctx, t).clone()
+    alone_slow = B.dit_forward(slow, x, ctx, t).clone()
+    for _ in range(2):
+        assert torch.equal(B.dit_forward(slow, x, ctx, t), alone_slow)
+        assert torch.equal(B.dit_forward(fast, x, ctx, t), alone_fast)
+        assert torch.equal(B.dit_forward(tiled, x, ctx, t), alone_fast)
+    assert not torch.equal(alone_fast, alone_slow)                  # different kernels, different rounding
+    assert O.rel_mae(host(alone_slow), host(alone_fast))[2] < 1e-2
+
+
+# ----------------------------------------------------------------------- a run in pieces
+@pytest.mark.parametrize("batched,mode,S,m,cyc,stops", [
+    (False, 0, 10, 1, [1, 2, 4, 2], [1, 4, 6, 9]),
+    (False, 2, 9, 2, [3, 4], [3, 4, 8]),
+    (False, 1, 7, 1, [2, 2, 2], [2, 5]),
+    (True, 0, 10, 1, [1, 2, 4, 2], [1, 2, 4, 8]),
+])
+def test_a_run_in_pieces_equals_the_whole_run_bitwise(batched, mode, S, m, cyc, stops):
+    """sampler_run_steps stopped at `stops` and continued -- the last piece from a COPY of the state in a new
+    workspace, as a restarted process would -- against sampler_run: final sample, per-step sums and trajectory."""
+    print(f"sampler_run_steps batched={batched} mode={mode} S={S} stops={stops}", flush=True)
+    cfg, W, d = setup("tiny_text", "unit")
+    x_T, ctx = dev(I.make_latent(cfg, 1)), dev(I.make_context(cfg, 1))
+    ts, a, b = B.ddim_coefficients(S)
+    sched = B.Schedule(ts, a, b, m, cyc, batched=batched, mode=mode)
+    x0, sums, calls, traj = B.sampler_run(d, sched, x_T, ctx, want_trajectory=True)
+    torch.cuda.synchronize()
+    ws = B.sampler_workspace(d, sched, DEV)
+    state = B.SamplerState()
+    sums2 = torch.zeros_like(sums)
+    traj2 = torch.zeros_like(traj)
+    out = torch.empty_like(x_T)
+    for k in stops:
+        B.sampler_run_steps(d, sched, state, k, x_T, ctx, ws, x_out=out, step_sums=sums2, trajectory=traj2)
+        torch.cuda.synchronize()
+        assert state.step == k and torch.equal(out, traj[k - 1])
+    # "another process": the struct and the state bytes copied into a fresh, poisoned workspace
+    nstate = B.sampler_state_bytes(d, sched)
+    assert 0 < nstate < ws.numel()
+    ws2 = torch.full_like(ws, 0xFF)
+    ws2[:nstate] = ws[:nstate]
+    state2 = B.SamplerState.from_buffer_copy(bytes(state))
+    del ws
+    B.sampler_run_steps(d, sched, state2, S, None, ctx, ws2, x_out=out, step_sums=sums2, trajectory=traj2)
+    torch.cuda.synchronize()
+    assert state2.step == S and state2.calls == calls
+    assert torch.equal(out, x0) and torch.equal(sums2, sums) and torch.equal(traj2, traj)
+
+
+def test_run_in_pieces_rejects_states_and_stops_that_do_not_fit():
+    cfg, W, d = setup("tiny_text", "unit")
+    x_T, ctx = dev(I.make_latent(cfg, 1)), dev(I.make_context(cfg, 1))
+    ts, a, b = B.ddim_coefficients(8)
+    sched = B.Schedule(ts, a, b, 2, [3, 3])
+    ws = B.sampler_workspace(d, sched, DEV)
+    st = B.SamplerState()
+    with pytest.raises(B.PsError) as e:
+        B.sampler_run_steps(d, sched, st, 0, x_T, ctx, ws)           # nothing to do
+    assert e.value.status == -5
+    with pytest.raises(B.PsError) as e:
+        B.sampler_run_steps(d, sched, st, 9, x_T, ctx, ws)           # past the end
+    assert e.value.status == -5
+    with pytest.raises(B.PsError) as e:
+        B.sampler_run_steps(d, sched, st, 3, None, ctx, ws)          # a fresh run needs x_T
+    assert e.value.status == -1
+    B.sampler_run_steps(d, sched, st, 4, x_T, ctx, ws)
+    assert (st.step, st.cycle, st.round) == (4, 0, 2)
+    bad = B.SamplerState.from_buffer_copy(bytes(st)); bad.round = 1
+    with pytest.raises(B.PsError) as e:
+        B.sampler_run_steps(d, sched, bad, 8, None, ctx, ws)         # round does not belong to step 4
+    assert e.value.status == -5
+    with pytest.raises(B.PsError) as e:
+        B.sampler_run_steps(d, sched, st, 3, None, ctx, ws)          # backwards
+    assert e.value.status == -5
+    batched = B.Schedule(ts, a, b, 2, [3, 3], batched=True)
+    wsb = B.sampler_workspace(d, batched, DEV)
+    with pytest.raises(B.PsError) as e:
+        B.sampler_run_steps(d, batched, B.SamplerState(), 4, x_T, ctx, wsb)   # inside a cycle
+    assert e.value.status == -5
+    B.sampler_run_steps(d, batched, B.SamplerState(), 5, x_T, ctx, wsb)
+    torch.cuda.synchronize()
 
 
 # ------------------------------------------------- trajectories, deviation curves, other schedulers

@@ -217,13 +217,60 @@ def test_attention_bf16_reference_tracking_kernel_on_ordinary_inputs(N):
     unbounded scores); on ordinary inputs it must agree with the oracle like the default path does."""
     print(f"attn3d bf16 path 3 N={N}", flush=True)
     q, k, v = I.make_qkv(2, N, 3, 64, dtype="bf16")
-    prev = B.ps_set_kernel_path(3)
-    try:
-        o = B.attn3d(dev(q, torch.bfloat16), dev(k, torch.bfloat16), dev(v, torch.bfloat16), 0.125)
-        torch.cuda.synchronize()
-    finally:
-        B.ps_set_kernel_path(prev)
+    o = B.attn3d(dev(q, torch.bfloat16), dev(k, torch.bfloat16), dev(v, torch.bfloat16), 0.125, kernel_path=3)
+    torch.cuda.synchronize()
     assert_close_bf16(host(o), O.attn3d(q, k, v, 0.125), 2e-2, max_tol=3e-2)
+
+
+@pytest.mark.parametrize("moved_heads", [(), (0, 13, 28, 29)])
+def test_attention_bf16_reference_tracking_kernel_split_items_and_merge(moved_heads):
+    """Kernel path 3 at a shape whose work items exceed the chip's workgroup slots (4516 tokens x 30 heads = 540
+    items of 256 queries on 512 slots): the last 28 items -- head 28 from query 2048 on, all of head 29 -- are each
+    computed as 8 key ranges that carry their own softmax reference, and merged with weights
+    2^(c (r_i - max r)).  Once with ordinary inputs (all references 0) and once with q and k of some heads,
+    split ones included, scaled so that the references move and differ between key ranges.  Sampled query rows
+    of every head against the oracle, most of them inside the split items."""
+    cfg = I.CONFIGS["block"]
+    N, H = cfg.tokens, cfg.heads
+    print(f"attn3d bf16 path 3 N={N} H={H} moved heads {moved_heads}", flush=True)
+    q, k, v = I.make_qkv(1, N, H, 64, dtype="bf16")
+    for h in moved_heads:
+        q[:, :, h, :] *= 6.0
+        k[:, :, h, :] *= 6.0                          # exponents ~ N(0, 52^2): far outside the +-32 window
+    # keys of one key range much larger than the others: the ranges' references differ by construction
+    if moved_heads:
+        k[:, 3 * (N // 8):4 * (N // 8), 29, :] *= 2.0
+    q, k = I.round_to_bf16(q.astype(np.float32)), I.round_to_bf16(k.astype(np.float32))
+    o = B.attn3d(dev(q, torch.bfloat16), dev(k, torch.bfloat16), dev(v, torch.bfloat16), 0.125, kernel_path=3)
+    torch.cuda.synchronize()
+    assert torch.isfinite(o).all()
+    rng = np.random.default_rng(9)
+    rows = np.unique(np.concatenate([[0, 255, 2047, 2048, 2049, 2303, 2304, N - 257, N - 2, N - 1],
+                                     rng.integers(2048, N, 30), rng.integers(0, 2048, 8)]))
+    ref = O.attn3d(q[:, rows], k, v, 0.125)
+    got = host(o[:, torch.from_numpy(rows).to(DEV)])
+    for h in range(H):
+        assert_close_bf16(got[:, :, h], ref[:, :, h], 2e-2, max_tol=4e-2)
+    # the same call without the split (path 2 keeps the bounded kernel; both must agree with the oracle alike)
+    o2 = B.attn3d(dev(q, torch.bfloat16), dev(k, torch.bfloat16), dev(v, torch.bfloat16), 0.125, kernel_path=0)
+    got2 = host(o2[:, torch.from_numpy(rows).to(DEV)])
+    for h in range(H):
+        assert_close_bf16(got2[:, :, h], ref[:, :, h], 2e-2, max_tol=4e-2)
+
+
+def test_attention_bf16_batch_invariance_at_a_shape_that_splits():
+    """4516 tokens x 30 heads splits its last 28 work items per sample; a sample's output must not depend on
+    the batch it is computed in (bitwise), on the default path and on the reference-tracking path."""
+    cfg = I.CONFIGS["block"]
+    q, k, v = I.make_qkv(3, cfg.tokens, cfg.heads, 64, dtype="bf16")
+    qd, kd, vd = (dev(a, torch.bfloat16) for a in (q, k, v))
+    for path in (0, 3):
+        print(f"attn3d bf16 batch of 3 against single calls, kernel path {path}", flush=True)
+        full = B.attn3d(qd, kd, vd, 0.125, kernel_path=path)
+        for b in range(3):
+            one = B.attn3d(qd[b:b + 1].contiguous(), kd[b:b + 1].contiguous(), vd[b:b + 1].contiguous(), 0.125,
+                           kernel_path=path)
+            assert torch.equal(one[0], full[b]), (path, b)
 
 
 def test_attention_bf16_mixed_heads_take_different_kernels():
@@ -265,15 +312,48 @@ def test_attention_invariants(dtype):
     assert np.abs(oa - ob).max() < (1e-5 if dtype == "f32" else 8e-3)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_attention_rotary_position_offset_and_token_permutation(dtype):
+    """Video tokens only, q and k rotated on the host with the 3D rotary angles (the oracle's routine): moving every
+    token by the same (frame, row, column) offset leaves the attention output unchanged, and permuting the tokens
+    together with their angles permutes the output -- here through the GPU attention (the tiny network's head
+    width for fp32, the MFMA kernel's for bf16)."""
+    td = torch.float32 if dtype == "f32" else torch.bfloat16
+    grid, H, d = (2, 8, 8), 4, (16 if dtype == "f32" else 64)
+    N = grid[0] * grid[1] * grid[2]
+    rng = np.random.default_rng(8)
+    q, k, v = (rng.standard_normal((N, H, d)) for _ in range(3))
+    prep = (lambda a: a.astype(np.float32)) if dtype == "f32" else (lambda a: I.round_to_bf16(a.astype(np.float32)))
+    v = prep(v)
+
+    def shifted(offset):
+        big = tuple(g + o for g, o in zip(grid, offset))
+        ang = O.rope3d_angles(big, d).reshape(big + (d // 2,))
+        return ang[offset[0]:, offset[1]:, offset[2]:].reshape(N, d // 2)
+
+    scale = 1.0 / math.sqrt(d)
+    run = lambda qq, kk, vv: host(B.attn3d(dev(qq[None], td), dev(kk[None], td), dev(vv[None], td), scale))[0]
+    a0 = shifted((0, 0, 0))
+    q0, k0 = prep(O.rope3d_apply(q, a0)), prep(O.rope3d_apply(k, a0))
+    base = run(q0, k0, v)
+    ref = O.attn3d(q0[None], k0[None], v[None], scale)[0]
+    tol = 1e-4 if dtype == "f32" else 2e-2
+    assert O.rel_mae(ref, base)[2] <= tol
+    a1 = shifted((3, 1, 2))
+    q1, k1 = prep(O.rope3d_apply(q, a1)), prep(O.rope3d_apply(k, a1))
+    assert np.abs(q1 - q0).max() > 0.1
+    moved = run(q1, k1, v)
+    assert O.rel_mae(base, moved)[2] <= (2e-6 if dtype == "f32" else 1.5e-2)   # bf16: q1, k1 are rounded again
+    perm = rng.permutation(N)
+    permuted = run(q0[perm], k0[perm], v[perm])
+    assert O.rel_mae(base[perm], permuted)[2] <= (2e-6 if dtype == "f32" else 8e-3)
+
+
 def test_attention_bf16_generic_and_mfma_paths_agree():
     q, k, v = I.make_qkv(1, 190, 2, 64, dtype="bf16")
     args = (dev(q, torch.bfloat16), dev(k, torch.bfloat16), dev(v, torch.bfloat16), 0.125)
     fast = host(B.attn3d(*args))
-    B.ps_set_kernel_path(1)
-    try:
-        slow = host(B.attn3d(*args))
-    finally:
-        B.ps_set_kernel_path(0)
+    slow = host(B.attn3d(*args, kernel_path=1))
     ref = O.attn3d(q, k, v, 0.125)
     assert O.rel_mae(ref, slow)[2] < 4e-3 and O.rel_mae(ref, fast)[2] < 8e-3
 
@@ -308,6 +388,24 @@ def test_attention_full_shape_sampled_rows(name, batch):
 
 
 # ------------------------------------------------------------------------------ dit_linear
+@pytest.mark.parametrize("M,Nn,K", [(777, 320, 256), (4516, 1920, 1920), (200, 64, 128)])
+def test_linear_tile_variants_give_identical_results(M, Nn, K):
+    """The tile variant decides which workgroup computes an output, never its value: every variant sums the k
+    products of an output in the same order."""
+    print(f"dit_linear tile variants M={M} N={Nn} K={K}", flush=True)
+    rng = np.random.default_rng(M)
+    a = dev(I.make_tokens(M, K, 5, "bf16"), torch.bfloat16)
+    w = dev(I.round_to_bf16((rng.standard_normal((Nn, K)) / math.sqrt(K)).astype(np.float32)), torch.bfloat16)
+    bias = dev(rng.standard_normal(Nn).astype(np.float32))
+    for act in (0, 1):
+        outs = [B.dit_linear(a, w, bias, act, kernel_path=v << 8) for v in (0, 1, 2, 3, 4)]
+        torch.cuda.synchronize()
+        for v in (1, 2, 3, 4):
+            assert torch.equal(outs[v], outs[0]), (v, act)
+    ref = host(a) @ host(w).T + host(bias)
+    assert_close_bf16(host(B.dit_linear(a, w, bias, 0, kernel_path=0x300)), ref, 5e-3, max_tol=1e-2)
+
+
 @pytest.mark.parametrize("M,Nn,K", [(1, 64, 64), (5, 66, 64), (130, 192, 128), (257, 130, 192), (300, 384, 64)])
 @pytest.mark.parametrize("act", [0, 1])
 def test_linear_small_shapes_both_dtypes(M, Nn, K, act):
@@ -328,18 +426,21 @@ def test_linear_small_shapes_both_dtypes(M, Nn, K, act):
             assert_close_bf16(out, ref, 5e-3, max_tol=1e-2)
 
 
+@pytest.mark.parametrize("variant", [0, 3, 4])
 @pytest.mark.parametrize("Nn,K,act", [(5760, 1920, 0), (1920, 1920, 0), (7680, 1920, 1), (1920, 7680, 0)])
-def test_linear_full_shapes_sampled_rows(Nn, K, act):
-    """The four projections of a block at 17776 tokens; the oracle checks 64 sampled rows."""
+def test_linear_full_shapes_sampled_rows(Nn, K, act, variant):
+    """The four projections of a block at 17776 tokens; the oracle checks 64 sampled rows.  Variant 0 is the
+    tile the library picks, 3 and 4 force the 192-row tiles (17776 = 92 * 192 + 112: a ragged last tile row)."""
     M = I.CONFIGS["full"].tokens
-    print(f"dit_linear M={M} N={Nn} K={K}", flush=True)
+    print(f"dit_linear M={M} N={Nn} K={K} variant={variant}", flush=True)
     a = I.make_tokens(M, K, 21, "bf16")
     rng = np.random.default_rng(22)
     w = I.round_to_bf16((rng.standard_normal((Nn, K)) / math.sqrt(K)).astype(np.float32))
     bias = rng.standard_normal(Nn).astype(np.float32)
-    out = B.dit_linear(dev(a, torch.bfloat16), dev(w, torch.bfloat16), dev(bias), act)
+    out = B.dit_linear(dev(a, torch.bfloat16), dev(w, torch.bfloat16), dev(bias), act, kernel_path=variant << 8)
     torch.cuda.synchronize()
-    rows = np.unique(np.concatenate([[0, 127, 128, 255, 256, M - 129, M - 1], rng.integers(0, M, 57)]))
+    rows = np.unique(np.concatenate([[0, 127, 128, 191, 192, 255, 256, M - 129, M - 113, M - 112, M - 1],
+                                     rng.integers(0, M, 57)]))
     ref = a[rows].astype(np.float64) @ w.astype(np.float64).T + bias
     if act:
         ref = O.gelu_tanh(ref)
@@ -347,11 +448,10 @@ def test_linear_full_shapes_sampled_rows(Nn, K, act):
     assert torch.isfinite(out).all()
     # the long-K shape splits its last partial round of tiles along K when given scratch (the sampled rows M-129
     # and M-1 lie in those tiles); without scratch the same product is computed unsplit
-    nb = B.lib().dit_linear_workspace_bytes(M, Nn, K, 1)
-    if K == 7680:
-        assert nb > 0
+    nb = B.lib().dit_linear_workspace_bytes(M, Nn, K, 1, variant << 8)
     if nb:
-        out2 = B.dit_linear(dev(a, torch.bfloat16), dev(w, torch.bfloat16), dev(bias), act, use_workspace=False)
+        out2 = B.dit_linear(dev(a, torch.bfloat16), dev(w, torch.bfloat16), dev(bias), act, use_workspace=False,
+                            kernel_path=variant << 8)
         torch.cuda.synchronize()
         assert_close_bf16(host(out2[torch.from_numpy(rows).to(DEV)]), ref, 5e-3, max_tol=1e-2)
         d = (out2.float() - out.float()).abs()

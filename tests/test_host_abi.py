@@ -119,6 +119,35 @@ def test_dit_create_validation():
     assert L.dit_create(None, _fake_weights(30), 30, C.byref(C.c_void_p())) == -1
 
 
+def test_kernel_path_is_a_property_of_the_handle():
+    """Two handles hold different kernel paths side by side; nothing process-wide is involved."""
+    L = B.lib()
+    cfg = I.CONFIGS["tiny"]
+    (rc1, h1), (rc2, h2) = _create(_cfg_struct(cfg)), _create(_cfg_struct(cfg))
+    assert rc1 == 0 and rc2 == 0
+    assert L.dit_get_kernel_path(h1) == 0 and L.dit_get_kernel_path(h2) == 0
+    assert L.dit_set_kernel_path(h1, 1) == 0 and L.dit_set_kernel_path(h2, 0x203) == 0
+    assert L.dit_get_kernel_path(h1) == 1 and L.dit_get_kernel_path(h2) == 0x203
+    ws = L.dit_workspace_bytes(h2, 2)
+    for bad in (-1, 5, 0x500, 0x1000, 1 << 20):
+        assert L.dit_set_kernel_path(h2, bad) == -2
+    assert L.dit_get_kernel_path(h2) == 0x203 and L.dit_workspace_bytes(h2, 2) == ws
+    assert L.dit_set_kernel_path(h2, 0) == 0 and L.dit_workspace_bytes(h2, 2) == ws   # size independent of the path
+    assert L.dit_set_kernel_path(None, 0) == -1 and L.dit_get_kernel_path(None) == -1
+    assert not hasattr(L, "ps_set_kernel_path")
+    L.dit_destroy(h1); L.dit_destroy(h2)
+
+
+def test_dit_create_rejects_shapes_no_kernel_serves():
+    cfg = I.CONFIGS["tiny"]
+    assert _create(_cfg_struct(cfg, in_channels=300))[0] == -2                    # 1200 patch values: LDS staging
+    assert _create(_cfg_struct(cfg, in_channels=256))[0] == 0
+    # bf16: a sample's widest activation must stay below 2^31 elements (32-bit offsets in the MFMA projections)
+    big = dict(hidden=2048, heads=32, head_dim=64, mlp_ratio=8, frames=33, height=128, width=128, patch=2)
+    assert _create(_cfg_struct(cfg, dtype=1, **big))[0] == -2
+    assert _create(_cfg_struct(cfg, dtype=0, **big))[0] == 0
+
+
 def test_dit_forward_validation_has_no_side_effects():
     L = B.lib()
     cfg = I.CONFIGS["tiny_text"]
@@ -143,8 +172,10 @@ def test_attn3d_validation():
     L = B.lib()
     Q, K, V, Oo, WS = 0x1000, 0x2000, 0x3000, 0x4000, 0x10000
     f = lambda **k: L.attn3d(k.get("q", Q), K, V, k.get("o", Oo), k.get("b", 1), k.get("n", 10), 2, k.get("d", 16),
-                             k.get("scale", 0.25), k.get("dt", 0), k.get("ws", None), k.get("wsb", 0), None)
+                             k.get("scale", 0.25), k.get("dt", 0), k.get("path", 0), k.get("ws", None), k.get("wsb", 0),
+                             None)
     assert f(q=None) == -1 and f(o=None) == -1
+    assert f(path=5) == -2 and f(path=-1) == -2 and f(path=0x500) == -2 and f(path=0x1000) == -2
     assert f(dt=5) == -3
     assert f(n=0) == -2 and f(b=0) == -2 and f(d=48) == -2 and f(d=128) == -2
     assert f(scale=0.0) == -2 and f(scale=float("nan")) == -2 and f(scale=-1.0) == -2
@@ -161,19 +192,23 @@ def test_dit_linear_validation_and_workspace_size():
     L = B.lib()
     A, W, BI, OUT, WS = 0x1000, 0x2000, 0x3000, 0x4000, 0x10000
     f = lambda **k: L.dit_linear(k.get("a", A), W, k.get("bias", BI), k.get("out", OUT), k.get("m", 8), k.get("n", 64),
-                                 k.get("k", 64), k.get("act", 0), k.get("dt", 1), k.get("ws", None), k.get("wsb", 0), None)
+                                 k.get("k", 64), k.get("act", 0), k.get("dt", 1), k.get("path", 0), k.get("ws", None),
+                                 k.get("wsb", 0), None)
     assert f(a=None) == -1 and f(bias=None) == -1 and f(out=None) == -1
+    assert f(path=7) == -2 and f(path=0x900) == -2
     assert f(dt=7) == -3
     assert f(m=0) == -2 and f(n=63) == -2 and f(k=60) == -2 and f(act=2) == -2
     assert f(out=A) == -2 and f(a=A + 2) == -2 and f(bias=BI + 4) == -2
     assert f(ws=WS + 16, wsb=1 << 20) == -4
     # scratch is only asked for where the K-split of the last partial round of tiles pays: 17776 x 1920 x 7680
     # leaves 37 of 2085 tiles of 128 x 128 for a 5th round on 512 workgroup slots; they are split 8 ways
-    assert L.dit_linear_workspace_bytes(17776, 1920, 7680, 1) == 37 * 8 * 128 * 128 * 4
-    assert L.dit_linear_workspace_bytes(17776, 1920, 1920, 1) == 0       # short K
-    assert L.dit_linear_workspace_bytes(17776, 7680, 1920, 1) == 0       # 256 x 256 tiles
-    assert L.dit_linear_workspace_bytes(17776, 1920, 7680, 0) == 0       # fp32 runs on the generic kernel
-    assert L.dit_linear_workspace_bytes(100, 64, 64, 1) == 0
+    assert L.dit_linear_workspace_bytes(17776, 1920, 7680, 1, 0x200) == 37 * 8 * 128 * 128 * 4
+    assert L.dit_linear_workspace_bytes(17776, 1920, 7680, 1, 0x204) == 0   # mode 4: no K-split
+    assert L.dit_linear_workspace_bytes(17776, 1920, 1920, 1, 0x200) == 0   # short K
+    assert L.dit_linear_workspace_bytes(17776, 7680, 1920, 1, 0x100) == 0   # 256 x 256 tiles
+    assert L.dit_linear_workspace_bytes(17776, 1920, 7680, 0, 0) == 0       # fp32 runs on the generic kernel
+    assert L.dit_linear_workspace_bytes(100, 64, 64, 1, 0) == 0
+    assert L.dit_linear_workspace_bytes(100, 64, 64, 1, 0x700) == 0         # unknown tile variant
 
 
 def test_sampler_step_and_rel_mae_validation():
