@@ -6,14 +6,19 @@ A "step" is one denoising step of the CogVideoX-2b-shaped run: one noise-predict
 update and relative-MAE sums, driven by the reuse-then-predict loop (window 2).  Inputs
 and weights are synthetic (seeded Gaussians) and resident in HBM before the timed region.
 
-Prints ONE JSON line: step latency (ms), the attention kernel's roofline fraction measured
-with HIP events over the timed region, and the CPU oracle timed on a bounded sample.
+Prints ONE JSON line: step latency (ms; mean of the timed region, median and min over its
+steps), the attention kernel's roofline fraction measured with HIP events over the timed
+region, per-projection and HBM-kernel figures, the clocks seen, an MFMA-only ceiling, the
+other named workloads (`workloads`), and the CPU oracle timed on a bounded sample.
 """
 import argparse
+import glob
 import json
 import math
 import os
+import statistics
 import sys
+import threading
 import time
 
 # Kernel arguments in device memory: the command processor then does not fetch them from host memory at every
@@ -26,9 +31,22 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
-# HBM bytes per launch of the dominant attention kernel at the `full` shape, from rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE scaled by a plain 1 GiB copy (profiles/attn3d_full_hbm_traffic.md): 502 MB fetched + 108 MB written
-ATTN_HBM_BYTES_PER_LAUNCH = 6.10e8
+# HBM bytes per launch of the dominant attention kernel at the `full` shape inside dit_forward come from
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a plain 1 GiB copy; the committed summary that holds them:
+ATTN_TRAFFIC_PROFILE = "profiles/dit_layer_full_hbm_traffic.md"
+ALL_WORKLOADS = ("block", "fallback_attention", "long_sweep", "run50", "step_batched")
+
+
+def attention_traffic():
+    """`traffic` of the roofline object, read from the committed profile summary (its line
+    `attn_sp_kernel<true> traffic_bytes_per_launch = N`), so the figure and its source cannot drift apart."""
+    try:
+        for line in open(os.path.join(ROOT, ATTN_TRAFFIC_PROFILE)):
+            if "traffic_bytes_per_launch" in line and "attn_sp_kernel<true>" in line:
+                return float(line.split("=")[1].split()[0])
+    except (OSError, ValueError, IndexError):
+        pass
+    return None
 
 
 def device_weights(cfg, torch, seed):
@@ -81,81 +99,324 @@ def cpu_baseline(cfg, rows=6144):
             "sample_seconds": round(dt, 2)}
 
 
-def report(kind, torch, B, I):
-    """Supplementary measurements on the other named workloads (one JSON object; not the benchmark line)."""
-    cfg = I.CONFIGS["long" if kind == "long_sweep" else "full"]
+# ------------------------------------------------------------------------------------ clocks
+class ClockSampler:
+    """Samples the GPU's engine and memory clock and its power from sysfs while a region runs."""
+
+    def __init__(self, period=0.05):
+        self.period, self.rows, self._stop, self._thread = period, [], threading.Event(), None
+        base = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))
+        self.dev = os.path.dirname(base[0]) if base else None
+
+    @staticmethod
+    def _current(path):
+        try:
+            for line in open(path):
+                if "*" in line:
+                    return float(line.split(":")[1].lower().replace("mhz", "").replace("*", "").strip())
+        except (OSError, ValueError, IndexError):
+            pass
+        return None
+
+    def _power(self):
+        for pat in ("power1_average", "power1_input"):
+            for f in glob.glob(os.path.join(self.dev, "hwmon", "hwmon*", pat)):
+                try:
+                    return float(open(f).read()) / 1e6
+                except (OSError, ValueError):
+                    pass
+        return None
+
+    def _loop(self):
+        while not self._stop.is_set():
+            self.rows.append((self._current(os.path.join(self.dev, "pp_dpm_sclk")),
+                              self._current(os.path.join(self.dev, "pp_dpm_mclk")), self._power()))
+            self._stop.wait(self.period)
+
+    def __enter__(self):
+        if self.dev:
+            self._thread = threading.Thread(target=self._loop, daemon=True)
+            self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop.set()
+        if self._thread:
+            self._thread.join(timeout=2)
+
+    def summary(self):
+        def col(i):
+            v = [r[i] for r in self.rows if r[i] is not None]
+            return {"min": min(v), "median": statistics.median(v), "max": max(v)} if v else None
+        return {"source": "sysfs pp_dpm_sclk / pp_dpm_mclk / hwmon power, sampled during the timed region",
+                "samples": len(self.rows), "sclk_mhz": col(0), "mclk_mhz": col(1), "power_w": col(2)}
+
+
+def stats_ms(v):
+    return {"mean": round(statistics.fmean(v), 4), "median": round(statistics.median(v), 4), "min": round(min(v), 4),
+            "max": round(max(v), 4), "n": len(v)}
+
+
+def event_times(torch, fn, reps, warm=2):
+    """Per-repetition milliseconds of fn() with HIP events on the stream the library launches on."""
+    for _ in range(warm):
+        fn()
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+    torch.cuda.synchronize()
+    evs[0].record()
+    for i in range(reps):
+        fn()
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    return [evs[i].elapsed_time(evs[i + 1]) for i in range(reps)]
+
+
+# ---------------------------------------------------------------------------- other workloads
+class Net:
+    """The 30-layer weights once, handles for the token counts that share them."""
+
+    def __init__(self, torch, B, I, kpath):
+        self.torch, self.B, self.I, self.kpath = torch, B, I, kpath
+        self.weights = device_weights(I.CONFIGS["full"], torch, 1003)
+        self.handles = {}
+
+    def handle(self, name):
+        if name not in self.handles:
+            cfg, full = self.I.CONFIGS[name], self.I.CONFIGS["full"]
+            assert [s for _, s in self.I.weight_shapes(cfg)] == [s for _, s in self.I.weight_shapes(full)]
+            d = self.B.dit_create(cfg, self.weights)
+            self.B.dit_set_kernel_path(d, self.kpath)
+            self.handles[name] = d
+        return self.handles[name]
+
+    def inputs(self, name, batch=1):
+        cfg = self.I.CONFIGS[name]
+        g = self.torch.Generator(device="cuda")
+        g.manual_seed(42)
+        x = self.torch.randn((batch,) + cfg.latent_shape, generator=g, device="cuda")
+        ctx = self.torch.randn((batch, cfg.text_tokens, cfg.hidden), generator=g, device="cuda").to(self.torch.bfloat16)
+        return x, ctx
+
+
+def timed_run(net, name, steps, warm, window, batched=False, mode=0):
+    """One sampler_run, wall-clock between synchronisations, attention timed with events on the library's stream."""
+    torch, B = net.torch, net.B
+    d = net.handle(name)
+    x_T, ctx = net.inputs(name)
+    ts, a, b = B.ddim_coefficients(steps)
+    cycles = [window] * ((steps - warm + window - 1) // window) if steps > warm else []
+    sched = B.Schedule(ts, a, b, warm, cycles, batched=batched, mode=mode)
+    B.dit_profile_enable(d, 2)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    x0, sums, calls = B.sampler_run(d, sched, x_T, ctx)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3
+    att_ms, att_n = B.dit_profile_read(d)["attention"]
+    B.dit_profile_enable(d, 0)
+    assert bool(torch.isfinite(x0).all())
+    return {"e2e_ms": round(ms, 1), "ms_per_step": round(ms / steps, 2), "predictor_calls": int(calls),
+            "attention_avg_ms": round(att_ms / max(att_n, 1), 4), "attention_launches": int(att_n)}, x0, sums
+
+
+def wl_block(net):
+    """One block at CogVideoX-2b width on 4290 + 226 tokens: forward and the attention kernel in isolation."""
+    torch, B, I = net.torch, net.B, net.I
+    cfg = I.CONFIGS["block"]
     N, D = cfg.tokens, cfg.hidden
-    d = B.dit_create(cfg, device_weights(cfg, torch, 1003))
-    g = torch.Generator(device="cuda"); g.manual_seed(42)
-    x_T = torch.randn((1,) + cfg.latent_shape, generator=g, device="cuda")
+    d = B.dit_create(cfg, device_weights(cfg, torch, 1002))
+    B.dit_set_kernel_path(d, net.kpath)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(42)
+    x = torch.randn((1,) + cfg.latent_shape, generator=g, device="cuda")
     ctx = torch.randn((1, cfg.text_tokens, D), generator=g, device="cuda").to(torch.bfloat16)
+    eps = torch.empty_like(x)
+    fwd = event_times(torch, lambda: B.dit_forward(d, x, ctx, [500], eps_out=eps), 10)
+    q, k, v = (torch.randn((1, N, cfg.heads, cfg.head_dim), generator=g, device="cuda").to(torch.bfloat16)
+               for _ in range(3))
+    o = torch.empty_like(q)
+    att = event_times(torch, lambda: B.attn3d(q, k, v, cfg.head_dim ** -0.5, out=o, kernel_path=net.kpath), 10)
+    flop, bflop = 4.0 * N * N * D, N * (24.0 * D * D + 4.0 * N * D)
+    tf = flop / (statistics.median(att) * 1e-3) / 1e12
+    return {"workload": f"1 block, hidden {D}, {cfg.video_tokens} video + {cfg.text_tokens} text tokens, bf16, batch 1",
+            "block_forward_ms": stats_ms(fwd), "block_flop": bflop,
+            "block_tflops_median": round(bflop / (statistics.median(fwd) * 1e-3) / 1e12, 1),
+            "attn3d_ms": stats_ms(att), "attn3d_flop": flop, "attn3d_tflops_median": round(tf, 1),
+            "attn3d_frac_of_bf16_peak": round(tf / PEAK_BF16_TFLOPS, 4),
+            "note": "block forward includes embedding, modulation and the final projection; stand-alone attn3d includes "
+                    "its pass over q and k for the norm bounds and the merge launch"}
 
-    def timed(steps, warm, window, batched=False, mode=0):
-        ts, a, b = B.ddim_coefficients(steps)
-        cycles = [window] * ((steps - warm + window - 1) // window)
-        sched = B.Schedule(ts, a, b, warm, cycles, batched=batched, mode=mode)
-        B.dit_profile_enable(d, 2)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        x0, sums, calls = B.sampler_run(d, sched, x_T, ctx)
-        torch.cuda.synchronize()
-        ms = (time.perf_counter() - t0) * 1e3
-        att_ms, att_n = B.dit_profile_read(d)["attention"]
-        B.dit_profile_enable(d, 0)
-        assert bool(torch.isfinite(x0).all())
-        return {"ms": round(ms, 1), "ms_per_step": round(ms / steps, 2), "predictor_calls": int(calls),
-                "attention_avg_ms": round(att_ms / max(att_n, 1), 4), "attention_launches": int(att_n)}, x0
 
-    def deviation(x, ref):
-        return float(B.rel_mae(x, ref)[2])
+def wl_fallback_attention(net):
+    """The attention kernel heads with unbounded scores take (softmax reference tracked), at 17776 tokens."""
+    torch, B, I = net.torch, net.B, net.I
+    cfg = I.CONFIGS["full"]
+    N, D = cfg.tokens, cfg.hidden
+    g = torch.Generator(device="cuda")
+    g.manual_seed(11)
+    q, k, v = (torch.randn((1, N, cfg.heads, cfg.head_dim), generator=g, device="cuda").to(torch.bfloat16)
+               for _ in range(3))
+    o = torch.empty_like(q)
+    out = {"workload": f"attn3d, {N} tokens, {cfg.heads} heads of {cfg.head_dim}, bf16, N(0,1) q/k/v"}
+    for key, path in (("reference_tracking_kernel", 3), ("default_path", net.kpath)):
+        t = event_times(torch, lambda: B.attn3d(q, k, v, cfg.head_dim ** -0.5, out=o, kernel_path=path), 10)
+        tf = 4.0 * N * N * D / (statistics.median(t) * 1e-3) / 1e12
+        out[key] = {"ms": stats_ms(t), "tflops_median": round(tf, 1), "frac_of_bf16_peak": round(tf / PEAK_BF16_TFLOPS, 4)}
+    return out
 
-    timed(2, 1, 2)                                            # untimed first touch
-    shape = f"{cfg.layers}-layer DiT, {cfg.video_tokens} video + {cfg.text_tokens} text tokens, bf16, batch 1"
-    if kind == "run50":
-        plain, x_plain = timed(50, 1, 1)
-        rtp, x_rtp = timed(50, 1, 2)
-        rtp_b, x_b = timed(50, 1, 2, batched=True)
-        direct, x_dir = timed(50, 1, 2, mode=1)
-        rtp["final_rel_mae_vs_no_reuse"] = deviation(x_rtp, x_plain)
-        rtp_b["final_rel_mae_vs_no_reuse"] = deviation(x_b, x_plain)
-        rtp_b["bitwise_equal_to_unbatched"] = bool(torch.equal(x_b, x_rtp))
-        direct["final_rel_mae_vs_no_reuse"] = deviation(x_dir, x_plain)
-        return {"report": "50 DDIM steps, 1 warm-up step, reuse window 2", "workload": shape, "weights": "random (std 0.02)",
-                "no_reuse": plain, "reuse_then_predict": rtp, "reuse_then_predict_step_batched": rtp_b,
-                "direct_reuse": direct}
-    if kind == "long_sweep":
-        out = {"report": "5 denoising steps, 1 warm-up step, reuse windows 2 and 3", "workload": shape}
-        for window in (2, 3):
-            r, _ = timed(5, 1, window)
-            r["attention_tflops"] = round(4.0 * N * N * D / (r["attention_avg_ms"] * 1e-3) / 1e12, 1)
-            out[f"window_{window}"] = r
-        return out
-    # step-batched round: cycles of 4 steps, one predictor call of batch 4 per cycle, over 48 reuse steps
-    one, x_one = timed(49, 1, 4)
-    bat, x_bat = timed(49, 1, 4, batched=True)
-    bat["attention_tflops"] = round(4.0 * 4 * N * N * D / (bat["attention_avg_ms"] * 1e-3) / 1e12, 1)
+
+def wl_long_sweep(net):
+    """25 frames: 33750 + 226 tokens, 5 denoising steps, reuse windows 2 and 3."""
+    cfg = net.I.CONFIGS["long"]
+    N, D = cfg.tokens, cfg.hidden
+    timed_run(net, "long", 2, 1, 2)                      # first touch
+    out = {"workload": f"{cfg.layers}-layer DiT, {cfg.video_tokens} video + {cfg.text_tokens} text tokens, bf16, "
+                       f"batch 1, 5 DDIM steps, 1 warm-up step"}
+    for window in (2, 3):
+        r, _, _ = timed_run(net, "long", 5, 1, window)
+        tf = 4.0 * N * N * D / (r["attention_avg_ms"] * 1e-3) / 1e12
+        r["attention_tflops"] = round(tf, 1)
+        r["attention_frac_of_bf16_peak"] = round(tf / PEAK_BF16_TFLOPS, 4)
+        out[f"window_{window}"] = r
+    out["forward_flop"] = cfg.layers * N * (24.0 * D * D + 4.0 * N * D)
+    return out
+
+
+def wl_run50(net):
+    """50 DDIM steps with the warm-up the paper uses for CogVideoX-2b at 50 steps (13; Section 4.1, Settings):
+    the original process (p = 1) and reuse-then-predict with p = 2, final samples compared."""
+    S, m, p = 50, 13, 2
+    plain, x_plain, _ = timed_run(net, "full", S, m, 1)
+    rtp, x_rtp, _ = timed_run(net, "full", S, m, p)
+    crit = m + -(-(S - m) // p)
+    per_call = rtp["e2e_ms"] / rtp["predictor_calls"]
+    return {"workload": "30-layer DiT, 17550 + 226 tokens, bf16, 50 DDIM steps, warm-up 13, random weights (std 0.02)",
+            "p1_no_reuse": plain, "p2_reuse_then_predict": rtp,
+            "final_rel_mae_x0_p1_vs_p2": float(net.B.rel_mae(x_plain, x_rtp)[2]),
+            "rank0_critical_path_forwards": crit, "forwards_total": S,
+            "rank0_critical_path_ms_derived": round(crit * per_call, 1),
+            "note": "one GPU evaluates the p predictor calls of a cycle one after the other, so e2e_ms is that of 50 "
+                    "forwards for both runs; with p devices rank 0 waits for 13 + ceil(37/2) = 32 of them (the derived "
+                    "figure = 32 x the measured time per call; bound 50/32 = 1.5625, Section 4.4)"}
+
+
+def wl_step_batched(net):
+    """2 warm-up steps + 48 steps in 12 cycles of 4: one predictor call per step against one call of batch 4 per
+    cycle (Section 3.3), and the fused update + relative-MAE sums over the batch of four latents."""
+    torch, B, I = net.torch, net.B, net.I
+    cfg = I.CONFIGS["full"]
+    N, D = cfg.tokens, cfg.hidden
+    one, x_one, s_one = timed_run(net, "full", 50, 2, 4)
+    bat, x_bat, s_bat = timed_run(net, "full", 50, 2, 4, batched=True)
     one["attention_tflops"] = round(4.0 * N * N * D / (one["attention_avg_ms"] * 1e-3) / 1e12, 1)
-    bat["bitwise_equal_to_unbatched"] = bool(torch.equal(x_bat, x_one))
-    return {"report": "1 warm-up step + 48 steps in cycles of 4: one call per step against one call of batch 4 per cycle",
-            "workload": shape, "one_call_per_step": one, "one_call_per_cycle_batch_4": bat}
+    # (the two warm-up calls of the batched run are single-sample launches: weight them out of the average)
+    one["ms_per_cycle"] = round(one["ms_per_step"] * 4, 2)
+    bat["ms_per_cycle"] = round((bat["e2e_ms"] - 2 * one["ms_per_step"]) / 12, 2)
+    att4 = (bat["attention_avg_ms"] * bat["attention_launches"] - 2 * 30 * one["attention_avg_ms"]) / (12 * 30)
+    bat["attention_batch4_avg_ms"] = round(att4, 4)
+    bat["attention_tflops"] = round(4.0 * 4 * N * N * D / (att4 * 1e-3) / 1e12, 1)
+    n4 = 4 * cfg.latent_elems
+    xs, es, ps = (torch.randn(n4, device="cuda") for _ in range(3))
+    upd = event_times(torch, lambda: B.sampler_step(xs, es, ps, 0.99, 0.05, x_out=xs), 20)
+    return {"workload": "30-layer DiT, 17550 + 226 tokens, bf16, 2 warm-up steps + 12 cycles of 4",
+            "one_call_per_step": one, "one_call_of_batch_4_per_cycle": bat,
+            "batched_final_sample_bitwise_equal": bool(torch.equal(x_bat, x_one)),
+            "batched_step_sums_bitwise_equal": bool(torch.equal(s_bat, s_one)),
+            "fused_update_and_sums_over_batch_of_4": {
+                "elements": n4, "bytes": 16 * n4, "us": stats_ms([t * 1e3 for t in upd]),
+                "note": "72 MB: resident in the 256 MB last-level cache and launch-bound; no HBM claim at this size"}}
+
+
+WORKLOAD_FUNCS = {"block": wl_block, "fallback_attention": wl_fallback_attention, "long_sweep": wl_long_sweep,
+                  "run50": wl_run50, "step_batched": wl_step_batched}
+
+
+# -------------------------------------------------------------------------- profiling targets
+def kernel_target(args, torch, B, I, cfg, kpath):
+    """Launch one kernel (or one layer) three times at the workload's shape:
+    rocprofv3 ... -- python3 bench.py --kernel ..."""
+    N, D = cfg.tokens, cfg.hidden
+    g = torch.Generator(device="cuda")
+    g.manual_seed(11)
+    if args.kernel == "attn3d":
+        q, k, v = (torch.randn((1, N, cfg.heads, cfg.head_dim), generator=g, device="cuda").to(torch.bfloat16)
+                   for _ in range(3))
+        o = torch.empty_like(q)
+        for _ in range(3):
+            B.attn3d(q, k, v, cfg.head_dim ** -0.5, out=o, kernel_path=kpath)
+        what = {"kernel": "attn3d", "tokens": N, "heads": cfg.heads, "flop": 4.0 * N * N * D}
+    elif args.kernel == "dit_linear":         # the four projection shapes of a layer (plain bias / GELU epilogues)
+        shapes = [(3 * D, D, 0), (D, D, 0), (4 * D, D, 1), (D, 4 * D, 0)]
+        for nn, kk, act in shapes:
+            a = torch.randn((N, kk), generator=g, device="cuda").to(torch.bfloat16)
+            w = (torch.randn((nn, kk), generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+            bias = torch.randn((nn,), generator=g, device="cuda")
+            out = torch.empty((N, nn), device="cuda", dtype=torch.bfloat16)
+            for _ in range(3):
+                B.dit_linear(a, w, bias, act, out=out, kernel_path=kpath)
+        what = {"kernel": "dit_linear", "tokens": N, "shapes": shapes}
+    elif args.kernel == "layer":              # one DiT layer inside dit_forward: every kernel of the hot path
+        c1 = cfg.with_(layers=1)
+        d = B.dit_create(c1, device_weights(c1, torch, 1003))
+        B.dit_set_kernel_path(d, kpath)
+        x = torch.randn((1,) + c1.latent_shape, generator=g, device="cuda")
+        ctx = torch.randn((1, c1.text_tokens, D), generator=g, device="cuda").to(torch.bfloat16)
+        eps = torch.empty_like(x)
+        for _ in range(3):
+            B.dit_forward(d, x, ctx, [500], eps_out=eps)
+        what = {"kernel": "layer", "tokens": N, "calls": 3, "ln_modulate_bytes": N * D * 6,
+                "attention_algorithmic_bytes": 4 * N * D * 2}
+    elif args.kernel == "copy":               # plain copy of known size: scale for FETCH_SIZE / WRITE_SIZE
+        n = 1 << 28
+        a, b = torch.randn(n, generator=g, device="cuda"), torch.empty(n, device="cuda")
+        for _ in range(3):
+            b.copy_(a)
+        what = {"kernel": "copy", "bytes_read": 4 * n, "bytes_written": 4 * n}
+    elif args.kernel == "rel_mae":
+        n = 1 << 28
+        xs, es = (torch.randn(n, generator=g, device="cuda") for _ in range(2))
+        for _ in range(3):
+            B.rel_mae(xs, es)
+        what = {"kernel": "rel_mae", "n": n, "bytes": 8 * n}
+    elif args.kernel == "mfma_probe":
+        sink = torch.zeros(4, device="cuda")
+        for _ in range(3):
+            flops = B.ps_mfma_probe(200000, sink)
+        what = {"kernel": "mfma_probe", "flop": flops}
+    else:
+        n = 1 << 28
+        xs, es, ps = (torch.randn(n, generator=g, device="cuda") for _ in range(3))
+        for _ in range(3):
+            B.sampler_step(xs, es, ps, 0.99, 0.05, x_out=xs)
+        what = {"kernel": "sampler_step", "n": n, "bytes": 16 * n}
+    torch.cuda.synchronize()
+    print(json.dumps(what))
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=6)
+    ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="full", choices=["full", "long", "block"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--kernel-path", type=lambda v: int(v, 0), default=0, help="kernel path of the handle and of the stand-alone calls (see dit_set_kernel_path)")
-    ap.add_argument("--kernel", default=None, choices=["attn3d", "dit_linear", "copy", "sampler_step"],
-                    help="profiling target: launch only this kernel 3 times at the workload's shape and exit")
-    ap.add_argument("--report", default=None, choices=["run50", "long_sweep", "step_batched"],
-                    help="supplementary report instead of the benchmark line: the 50-step run against a no-reuse "
-                         "run, the long-video window sweep, or the step-batched round")
+    ap.add_argument("--workloads", default="all",
+                    help="other named workloads reported under `workloads`: all, none, or a comma list of "
+                         + ", ".join(ALL_WORKLOADS))
+    ap.add_argument("--kernel-path", type=lambda v: int(v, 0), default=0,
+                    help="kernel path of the handle and of the stand-alone calls (see dit_set_kernel_path)")
+    ap.add_argument("--kernel", default=None,
+                    choices=["attn3d", "dit_linear", "layer", "copy", "sampler_step", "rel_mae", "mfma_probe"],
+                    help="profiling target: launch only this kernel (or one DiT layer) 3 times at the workload's "
+                         "shape and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives are built); use --gpus 1")
+    chosen = ALL_WORKLOADS if args.workloads == "all" else () if args.workloads == "none" else \
+        tuple(w for w in args.workloads.split(",") if w)
+    for w in chosen:
+        if w not in ALL_WORKLOADS:
+            sys.exit(f"bench.py: unknown workload {w!r}")
 
     import torch
     from paper_2505_14741_amd import binding as B
@@ -169,70 +430,55 @@ def main():
     N, D = cfg.tokens, cfg.hidden
     K, Wm = args.steps, args.warmup
 
-    if args.kernel:                               # counter / trace target (rocprofv3 -- python3 bench.py --kernel ...)
-        g = torch.Generator(device="cuda"); g.manual_seed(11)
-        if args.kernel == "attn3d":
-            q, k, v = (torch.randn((1, N, cfg.heads, cfg.head_dim), generator=g, device="cuda").to(torch.bfloat16)
-                       for _ in range(3))
-            o = torch.empty_like(q)
-            for _ in range(3):
-                B.attn3d(q, k, v, cfg.head_dim ** -0.5, out=o, kernel_path=kpath)
-            what = {"kernel": "attn3d", "tokens": N, "heads": cfg.heads, "flop": 4.0 * N * N * D}
-        elif args.kernel == "dit_linear":         # the four projection shapes of a layer (plain bias / GELU epilogues)
-            shapes = [(3 * D, D, 0), (D, D, 0), (4 * D, D, 1), (D, 4 * D, 0)]
-            for nn, kk, act in shapes:
-                a = torch.randn((N, kk), generator=g, device="cuda").to(torch.bfloat16)
-                w = (torch.randn((nn, kk), generator=g, device="cuda") * 0.02).to(torch.bfloat16)
-                bias = torch.randn((nn,), generator=g, device="cuda")
-                out = torch.empty((N, nn), device="cuda", dtype=torch.bfloat16)
-                for _ in range(3):
-                    B.dit_linear(a, w, bias, act, out=out, kernel_path=kpath)
-            what = {"kernel": "dit_linear", "tokens": N, "shapes": shapes}
-        elif args.kernel == "copy":               # plain copy of known size: scale for FETCH_SIZE / WRITE_SIZE
-            n = 1 << 28
-            a, b = torch.randn(n, generator=g, device="cuda"), torch.empty(n, device="cuda")
-            for _ in range(3):
-                b.copy_(a)
-            what = {"kernel": "copy", "bytes_read": 4 * n, "bytes_written": 4 * n}
-        else:
-            n = 1 << 28
-            xs, es, ps = (torch.randn(n, generator=g, device="cuda") for _ in range(3))
-            for _ in range(3):
-                B.sampler_step(xs, es, ps, 0.99, 0.05, x_out=xs)
-            what = {"kernel": "sampler_step", "n": n, "bytes": 16 * n}
-        torch.cuda.synchronize()
-        print(json.dumps(what))
+    if args.kernel:
+        kernel_target(args, torch, B, I, cfg, kpath)
         return
 
-    if args.report:
-        print(json.dumps(report(args.report, torch, B, I)))
-        return
+    net = Net(torch, B, I, kpath) if args.workload != "block" else None
+    if net is not None:
+        d = net.handle(args.workload)
+        x_T, ctx = net.inputs(args.workload)
+    else:
+        d = B.dit_create(cfg, device_weights(cfg, torch, 1003))
+        B.dit_set_kernel_path(d, kpath)
+        g = torch.Generator(device="cuda")
+        g.manual_seed(42)
+        x_T = torch.randn((1,) + cfg.latent_shape, generator=g, device="cuda")
+        ctx = torch.randn((1, cfg.text_tokens, D), generator=g, device="cuda").to(torch.bfloat16)
 
-    d = B.dit_create(cfg, device_weights(cfg, torch, 1003))
-    B.dit_set_kernel_path(d, kpath)
-    g = torch.Generator(device="cuda"); g.manual_seed(42)
-    x_T = torch.randn((1,) + cfg.latent_shape, generator=g, device="cuda")
-    ctx = torch.randn((1, cfg.text_tokens, D), generator=g, device="cuda").to(torch.bfloat16)
+    def schedule(steps):
+        ts, a, b = B.ddim_coefficients(max(steps, 2))
+        return B.Schedule(ts[:steps], a[:steps], b[:steps], 1, [2] * steps)      # 1 warm-up step, then window 2
 
     def run(steps, profile):
-        ts, a, b = B.ddim_coefficients(max(steps, 2))
-        ts, a, b = ts[:steps], a[:steps], b[:steps]
-        sched = B.Schedule(ts, a, b, 1, [2] * steps)          # 1 warm-up step, then window 2
         B.dit_profile_enable(d, profile)
-        return B.sampler_run(d, sched, x_T, ctx)
+        return B.sampler_run(d, schedule(steps), x_T, ctx)
 
     if Wm > 0:
         run(Wm, False)
+    # Timed region: K steps of one run, taken one step per call so that an event can be recorded after each.
+    # Inside the library HIP events are recorded around the attention calls only (the roofline kernel): events
+    # around every launch cost about 1.5 % of a step, so the per-class breakdown comes from a second, untimed pass.
+    sched = schedule(K)
+    ws = B.sampler_workspace(d, sched, "cuda")
+    state = B.SamplerState()
+    x0 = torch.empty_like(x_T)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
+    B.dit_profile_enable(d, 2)
     torch.cuda.synchronize()
-    # timed region: HIP events around the attention calls only (the roofline kernel); events around every launch
-    # cost about 1.5 % of a step, so the per-class breakdown comes from a second, untimed pass of the same steps
-    t0 = time.perf_counter()
-    x0, sums, calls = run(K, 2)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+    with ClockSampler() as clocks:
+        t0 = time.perf_counter()
+        evs[0].record()
+        for i in range(K):
+            B.sampler_run_steps(d, sched, state, i + 1, x_T, ctx, ws, x_out=x0 if i == K - 1 else None)
+            evs[i + 1].record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
     att_ms, att_n = B.dit_profile_read(d)["attention"]
-    assert calls == K and bool(torch.isfinite(x0).all())
+    assert state.calls == K and state.step == K and bool(torch.isfinite(x0).all())
     ms_step = wall * 1e3 / K
+    step_ms = [evs[i].elapsed_time(evs[i + 1]) for i in range(K)]
+    del ws
     run(K, 1)
     torch.cuda.synchronize()
     prof = B.dit_profile_read(d)
@@ -244,26 +490,34 @@ def main():
     for key, (nn, kk) in {"gemm_qkv": (3 * D, D), "gemm_oproj": (D, D), "gemm_fc1": (4 * D, D),
                           "gemm_fc2": (D, 4 * D)}.items():
         ms, n = prof[key]
-        gemm[key] = {"avg_ms": ms / max(n, 1), "tflops": 2.0 * N * nn * kk / (ms / max(n, 1) * 1e-3) / 1e12}
+        tf = 2.0 * N * nn * kk / (ms / max(n, 1) * 1e-3) / 1e12
+        gemm[key] = {"avg_ms": ms / max(n, 1), "tflops": tf, "frac": tf / PEAK_BF16_TFLOPS}
     gemm_ms = sum(prof[k][0] for k in gemm)
     gemm_tflops = cfg.layers * K * 24.0 * N * D * D / (gemm_ms * 1e-3) / 1e12
+    ln_ms, ln_n = prof["ln_modulate"]
+    ln_avg = ln_ms / max(ln_n, 1)
+    ln_gbs = N * D * 6.0 / (ln_avg * 1e-3) / 1e9
 
-    # scheduler update + rel-MAE sums at a stress shape that exceeds the caches (1 GiB per tensor)
+    # HBM-bound kernels at a stress shape that exceeds the caches (1 GiB per tensor)
     n_big = 1 << 28
     xs, es, ps = (torch.randn(n_big, device="cuda") for _ in range(3))
-    B.sampler_step(xs, es, ps, 0.99, 0.05, x_out=xs)
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    reps = 10
-    ev0.record()
-    for _ in range(reps):
-        B.sampler_step(xs, es, ps, 0.99, 0.05, x_out=xs)
-    ev1.record()
-    torch.cuda.synchronize()
-    ss_ms = ev0.elapsed_time(ev1) / reps
-    ss_gbs = 16.0 * n_big / (ss_ms * 1e-3) / 1e9
+    ss = event_times(torch, lambda: B.sampler_step(xs, es, ps, 0.99, 0.05, x_out=xs), 10)
+    rm = event_times(torch, lambda: B.rel_mae(xs, es), 10)
     del xs, es, ps
 
+    def hbm(times, bytes_per_elem):
+        gbs = bytes_per_elem * n_big / (statistics.median(times) * 1e-3) / 1e9
+        return {"n": n_big, "ms": stats_ms(times), "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": round(gbs / PEAK_HBM_GBS, 4), "bound": "hbm", "of": "median of 10",
+                "achieved_best": round(bytes_per_elem * n_big / (min(times) * 1e-3) / 1e9, 1)}
+
+    # what the matrix pipes sustain on this chip under load: launches of nothing but bf16 MFMAs (about 50 ms each)
+    sink = torch.zeros(4, device="cuda")
+    flops_box = []
+    probe = event_times(torch, lambda: flops_box.append(B.ps_mfma_probe(400000, sink)), 5, warm=1)
+    probe_tf = flops_box[-1] / (statistics.median(probe) * 1e-3) / 1e12
+
+    traffic = attention_traffic() if args.workload == "full" else None
     out = {
         "metric": "DiT step latency (ms) & 3D-attn TFLOP/s as % bf16 MFMA peak, CogVideoX-2b shape",
         "value": round(ms_step, 3), "unit": "ms", "n_gpus": 1, "steps": K, "warmup": Wm,
@@ -273,20 +527,33 @@ def main():
                                f"{cfg.head_dim}, {cfg.video_tokens} video + {cfg.text_tokens} text tokens, "
                                f"DDIM reuse-then-predict window 2, batch 1",
                    "tokens": N, "layers": cfg.layers, "latent": list(cfg.latent_shape)},
+        "step_ms": dict(stats_ms(step_ms), source="HIP events after each of the timed steps"),
         "roofline": {"kernel": "attn_sp_kernel", "bound": "mfma", "achieved": round(att_tflops, 1),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(att_tflops / PEAK_BF16_TFLOPS, 4),
-                     "traffic": ATTN_HBM_BYTES_PER_LAUNCH if args.workload == "full" else None, "avg_ms": round(att_avg, 4), "launches": int(att_n),
-                     "flop_per_launch": 4.0 * N * N * D},
+                     "traffic": traffic, "traffic_source": ATTN_TRAFFIC_PROFILE if traffic else None,
+                     "avg_ms": round(att_avg, 4), "launches": int(att_n), "flop_per_launch": 4.0 * N * N * D},
         "attn_pct_of_bf16_peak": round(100 * att_tflops / PEAK_BF16_TFLOPS, 2),
         "gemm": {"tflops": round(gemm_tflops, 1), "frac": round(gemm_tflops / PEAK_BF16_TFLOPS, 4),
                  "per_kernel": {k: {kk: round(vv, 4) for kk, vv in v.items()} for k, v in gemm.items()}},
         "kernel_ms_per_step": {k: round(v[0] / K, 3) for k, v in prof.items()},
         "kernel_ms_per_step_source": "second, untimed pass of the same steps with HIP events around every launch",
-        "sampler_step_stress": {"n": n_big, "ms": round(ss_ms, 4), "achieved": round(ss_gbs, 1), "peak": PEAK_HBM_GBS,
-                                "unit": "GB/s", "frac": round(ss_gbs / PEAK_HBM_GBS, 4), "bound": "hbm"},
+        "ln_modulate": {"avg_ms": round(ln_avg, 4), "bytes_per_launch": N * D * 6, "achieved": round(ln_gbs, 1),
+                        "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(ln_gbs / PEAK_HBM_GBS, 4), "bound": "hbm",
+                        "note": "fp32 residual read (just written by the preceding projection), bf16 rows written"},
+        "sampler_step_stress": hbm(ss, 16.0),
+        "rel_mae_stress": hbm(rm, 8.0),
+        "mfma_only_probe": {"tflops": round(probe_tf, 1), "frac_of_nominal_peak": round(probe_tf / PEAK_BF16_TFLOPS, 4),
+                            "ms": stats_ms(probe),
+                            "instruction": "v_mfma_f32_16x16x32_bf16 on register operands, two waves per SIMD"},
+        "clocks": clocks.summary(),
+        "timing_method": f"{Wm} untimed warm-up steps, then {K} timed steps between synchronisations (value = wall / "
+                         f"{K}); per-step and per-kernel figures from HIP events on the library's stream; stress "
+                         f"kernels and workloads: 2 warm-up + 10 repetitions, median and min",
         "paper_context": "paper reports end-to-end speedups 3.88x SVD, 2.43x CogVideoX-2b, 6.56x AudioLDM2-large "
                          "on 8x RTX 4090 (PCIe Gen3); no per-step or kernel number for this path",
     }
+    if chosen and net is not None:
+        out["workloads"] = {w: WORKLOAD_FUNCS[w](net) for w in chosen}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out))

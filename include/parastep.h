@@ -136,6 +136,13 @@ PS_API int dit_forward(dit* d, const float* x, const void* ctx, const int32_t* t
 PS_API int dit_profile_enable(dit* d, int on);
 PS_API int dit_profile_read(dit* d, double* ms_out, int64_t* launches_out);
 
+/* Measurement aid: one launch of nothing but bf16 matrix instructions (v_mfma_f32_16x16x32_bf16 on
+ * register operands, two waves per SIMD on every compute unit, `iters` x 8 instructions per wave).
+ * Timed by the caller, *flops_out (HOST) / time is the rate the matrix pipes sustain on this chip
+ * under load -- the practical ceiling next to the nominal peak.  sink: DEVICE float[1], never
+ * written in practice.  1 <= iters <= 2^24. */
+PS_API int ps_mfma_probe(int iters, float* sink, double* flops_out, void* hip_stream);
+
 /* Stand-alone full attention: for every batch and head, O = softmax(scale*Q K^T) V
  * over all `seq` tokens (no mask, Section 1's "3D attention": one token axis holding
  * text tokens and the flattened frame/row/col grid).  q, k, v, o: DEVICE

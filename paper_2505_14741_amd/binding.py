@@ -68,6 +68,7 @@ def lib():
         "dit_forward": (i32, [vp, vp, vp, C.POINTER(C.c_int32), vp, i32, vp, sz, vp]),
         "dit_profile_enable": (i32, [vp, i32]),
         "dit_profile_read": (i32, [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
+        "ps_mfma_probe": (i32, [i32, vp, C.POINTER(C.c_double), vp]),
         "attn3d_workspace_bytes": (sz, [i32, i32, i32, i32, i32]),
         "attn3d": (i32, [vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, i32, vp, sz, vp]),
         "dit_linear_workspace_bytes": (C.c_size_t, [i32, i32, i32, i32, i32]),
@@ -95,7 +96,7 @@ def lib():
     return L
 
 
-EXPORTED = ("ps_strerror", "dit_set_kernel_path", "dit_get_kernel_path", "dit_num_weights", "dit_create", "dit_destroy",
+EXPORTED = ("ps_strerror", "ps_mfma_probe", "dit_set_kernel_path", "dit_get_kernel_path", "dit_num_weights", "dit_create", "dit_destroy",
             "dit_workspace_bytes", "dit_forward", "dit_profile_enable", "dit_profile_read",
             "attn3d_workspace_bytes", "attn3d", "dit_linear_workspace_bytes", "dit_linear", "sampler_step_workspace_bytes", "sampler_step",
             "rel_mae_workspace_bytes", "rel_mae", "ddim_coefficients", "euler_discrete_coefficients",
@@ -197,6 +198,13 @@ def dit_profile_read(d: Dit):
     cnt = (C.c_int64 * 7)()
     _check(lib().dit_profile_read(d.handle, ms, cnt), "dit_profile_read")
     return {k: (ms[i], cnt[i]) for i, k in enumerate(KERNEL_CLASSES)}
+
+
+def ps_mfma_probe(iters: int, sink: torch.Tensor) -> float:
+    """Enqueue the MFMA-only launch; returns the operations it performs (time it with events)."""
+    flops = C.c_double(0.0)
+    _check(lib().ps_mfma_probe(int(iters), _ptr(sink), C.byref(flops), _stream()), "ps_mfma_probe")
+    return flops.value
 
 
 # ---------------------------------------------------------------------------- attention

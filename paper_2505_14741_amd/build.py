@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libparastep_hip.so")
-SOURCES = ["api.hip", "elementwise.hip", "gemm.hip", "gemm_mfma.hip", "attention.hip"]
+SOURCES = ["api.hip", "elementwise.hip", "gemm.hip", "gemm_mfma.hip", "attention.hip", "probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -349,6 +349,13 @@ int dit_forward(dit* d, const float* x, const void* ctx, const int32_t* t_host, 
     return forward_impl(d, x, ctx, t_host, eps_out, batch, workspace, (hipStream_t)hip_stream);
 }
 
+int ps_mfma_probe(int iters, float* sink, double* flops_out, void* hip_stream) {
+    if (!sink || !flops_out) return PS_ERR_NULL;
+    if (iters < 1 || iters > (1 << 24)) return PS_ERR_SHAPE;
+    hipError_t e = launch_mfma_probe(iters, sink, flops_out, (hipStream_t)hip_stream);
+    return e == hipSuccess ? PS_OK : PS_ERR_HIP;
+}
+
 int dit_profile_enable(dit* d, int on) {
     if (!d) return PS_ERR_NULL;
     if (on < 0 || on > 2) return PS_ERR_SHAPE;

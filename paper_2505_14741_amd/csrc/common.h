@@ -150,6 +150,9 @@ hipError_t launch_final_proj(int dtype, const float* X, const float* modf, const
                              const float* b_out, float* eps_out, int batch, int C, int F, int H,
                              int Wd, int patch, int text_tokens, int D, float eps, hipStream_t st);
 
+// measurement aid: a launch of nothing but bf16 MFMAs (see probe.hip)
+hipError_t launch_mfma_probe(int iters, float* sink, double* flops, hipStream_t st);
+
 size_t reduce_workspace_bytes(size_t n);
 hipError_t launch_sampler_step(const float* x, const float* e, const float* e_prev, float* x_out,
                                double a, double b, size_t n, float* sums4, void* ws, hipStream_t st);

@@ -496,21 +496,24 @@ def test_other_schedulers_run_matches_oracle(kind):
 
 
 def test_bench_prints_one_json_line_with_the_agreed_fields():
-    """bench.py (one step, no CPU leg) as a child process: one JSON line, the contract's keys, sane values."""
+    """bench.py (one step, no CPU leg, the two cheap extra workloads) as a child process: one JSON line, the
+    contract's keys, sane values."""
     import json
     import os
     import subprocess
     import sys
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    print("bench.py --steps 1 --warmup 1 --no-cpu-baseline", flush=True)
+    print("bench.py --steps 1 --warmup 1 --no-cpu-baseline --workloads block,fallback_attention", flush=True)
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--steps", "1", "--warmup", "1",
-                        "--no-cpu-baseline"], capture_output=True, text=True, timeout=170)
+                        "--no-cpu-baseline", "--workloads", "block,fallback_attention"],
+                       capture_output=True, text=True, timeout=170)
     assert r.returncode == 0, r.stderr[-2000:]
     lines = [l for l in r.stdout.splitlines() if l.startswith("{")]
     assert len(lines) == 1
     out = json.loads(lines[0])
     for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
-                "vs_baseline", "dtype", "data", "config", "roofline"):
+                "vs_baseline", "dtype", "data", "config", "roofline", "step_ms", "gemm", "ln_modulate",
+                "sampler_step_stress", "rel_mae_stress", "mfma_only_probe", "clocks", "workloads"):
         assert key in out, key
     assert out["n_gpus"] == 1 and out["steps"] == 1 and out["unit"] == "ms" and out["higher_is_better"] is False
     assert out["vs_baseline"] is None and out["dtype"] == "bf16" and out["data"] == "synthetic"
@@ -520,3 +523,10 @@ def test_bench_prints_one_json_line_with_the_agreed_fields():
     assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-3
     assert roof["launches"] == 30 and 0.2 < roof["frac"] < 1.0
     assert 30.0 < out["value"] < 1000.0
+    assert out["step_ms"]["n"] == 1 and abs(out["step_ms"]["mean"] - out["value"]) < 0.05 * out["value"]
+    for key in ("sampler_step_stress", "rel_mae_stress", "ln_modulate"):
+        assert out[key]["bound"] == "hbm" and 0.2 < out[key]["frac"] < 1.0, key
+    assert 0.4 < out["mfma_only_probe"]["frac_of_nominal_peak"] <= 1.0
+    assert set(out["workloads"]) == {"block", "fallback_attention"}
+    assert 0.2 < out["workloads"]["fallback_attention"]["reference_tracking_kernel"]["frac_of_bf16_peak"] < 1.0
+    assert out["workloads"]["block"]["attn3d_ms"]["n"] == 10
