@@ -190,6 +190,19 @@ PS_API int sampler_step(const float* x, const float* eps, const float* eps_prev,
                  double a, double b, size_t n, float* sums4,
                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* sampler_step for callers that cannot allocate device memory or carry a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels
+ * and results as sampler_step (bit for bit), but the partial sums of the reduction live in a
+ * file-scope device array of the library (1 MiB on every GPU the library runs on, held until the
+ * process ends) instead of a workspace; the call allocates and frees nothing.
+ * n <= SAMPLER_STEP_NOALLOC_MAX_N, larger sizes are PS_ERR_SHAPE.  The device current at the call
+ * must be the one `hip_stream` belongs to (the array's address is looked up per device, on first
+ * use).  Every call on a GPU shares that GPU's array: calls that overlap on one GPU (two streams,
+ * two threads) race on it; calls in order on one stream do not. */
+#define SAMPLER_STEP_NOALLOC_MAX_N ((size_t)1 << 31)
+PS_API int sampler_step_noalloc(const float* x, const float* eps, const float* eps_prev, float* x_out,
+                         double a, double b, size_t n, float* sums4, void* hip_stream);
+
 /* Relative MAE of Eq. (1): out3 = { sum|a-b|, sum|a|, sum|a-b| / sum|a| } (DEVICE fp32).
  * The denominator is the FIRST argument; a zero denominator yields inf or nan.
  * n may be 0 (a and b are then not looked at, NULL is accepted): { 0, 0, nan }. */

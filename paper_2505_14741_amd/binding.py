@@ -75,6 +75,7 @@ def lib():
         "dit_linear": (i32, [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, C.c_size_t, vp]),
         "sampler_step_workspace_bytes": (sz, [sz]),
         "sampler_step": (i32, [vp, vp, vp, vp, C.c_double, C.c_double, sz, vp, vp, sz, vp]),
+        "sampler_step_noalloc": (i32, [vp, vp, vp, vp, C.c_double, C.c_double, sz, vp, vp]),
         "rel_mae_workspace_bytes": (sz, [sz]),
         "rel_mae": (i32, [vp, vp, sz, vp, vp, sz, vp]),
         "ddim_coefficients": (i32, [i32, C.c_double, C.c_double, i32, C.POINTER(C.c_int32),
@@ -96,7 +97,7 @@ def lib():
     return L
 
 
-EXPORTED = ("ps_strerror", "ps_mfma_probe", "dit_set_kernel_path", "dit_get_kernel_path", "dit_num_weights", "dit_create", "dit_destroy",
+EXPORTED = ("ps_strerror", "ps_mfma_probe", "dit_set_kernel_path", "dit_get_kernel_path", "sampler_step_noalloc", "dit_num_weights", "dit_create", "dit_destroy",
             "dit_workspace_bytes", "dit_forward", "dit_profile_enable", "dit_profile_read",
             "attn3d_workspace_bytes", "attn3d", "dit_linear_workspace_bytes", "dit_linear", "sampler_step_workspace_bytes", "sampler_step",
             "rel_mae_workspace_bytes", "rel_mae", "ddim_coefficients", "euler_discrete_coefficients",
@@ -246,6 +247,14 @@ def sampler_step(x: torch.Tensor, eps: torch.Tensor, eps_prev: Optional[torch.Te
     ws = _workspace(nb, x.device)
     _check(lib().sampler_step(_ptr(x), _ptr(eps), _ptr(eps_prev), _ptr(x_out), float(a), float(b), n, _ptr(sums),
                               _ptr(ws), nb, _stream()), "sampler_step")
+    return x_out, sums
+
+
+def sampler_step_noalloc(x: torch.Tensor, eps: torch.Tensor, eps_prev: Optional[torch.Tensor], a: float, b: float,
+                         x_out: torch.Tensor, sums: Optional[torch.Tensor]):
+    """The caller supplies every buffer; neither this wrapper nor the library allocates."""
+    _check(lib().sampler_step_noalloc(_ptr(x), _ptr(eps), _ptr(eps_prev), _ptr(x_out), float(a), float(b), x.numel(),
+                                      _ptr(sums), _stream()), "sampler_step_noalloc")
     return x_out, sums
 
 

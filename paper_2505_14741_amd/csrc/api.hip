@@ -449,6 +449,17 @@ int sampler_step(const float* x, const float* eps, const float* eps_prev, float*
     return e == hipSuccess ? PS_OK : PS_ERR_HIP;
 }
 
+int sampler_step_noalloc(const float* x, const float* eps, const float* eps_prev, float* x_out, double a, double b,
+                         size_t n, float* sums4, void* hip_stream) {
+    if (n > SAMPLER_STEP_NOALLOC_MAX_N) return PS_ERR_SHAPE;
+    if (n > 0 && (!x || !eps || !x_out)) return PS_ERR_NULL;
+    if (!aligned(x, 16) || !aligned(eps, 16) || !aligned(x_out, 16) || (eps_prev && !aligned(eps_prev, 16)))
+        return PS_ERR_SHAPE;
+    if (n > 0 && (eps == x_out || (eps_prev && eps_prev == x_out))) return PS_ERR_SHAPE;
+    hipError_t e = launch_sampler_step_static(x, eps, eps_prev, x_out, a, b, n, sums4, (hipStream_t)hip_stream);
+    return e == hipSuccess ? PS_OK : PS_ERR_HIP;
+}
+
 int rel_mae(const float* a, const float* b, size_t n, float* out3, void* workspace, size_t workspace_bytes,
             void* hip_stream) {
     if (!out3 || (n > 0 && (!a || !b))) return PS_ERR_NULL;

@@ -156,6 +156,9 @@ hipError_t launch_mfma_probe(int iters, float* sink, double* flops, hipStream_t 
 size_t reduce_workspace_bytes(size_t n);
 hipError_t launch_sampler_step(const float* x, const float* e, const float* e_prev, float* x_out,
                                double a, double b, size_t n, float* sums4, void* ws, hipStream_t st);
+// the same update with its partial sums in a file-scope device array of the library (no workspace, no allocation)
+hipError_t launch_sampler_step_static(const float* x, const float* e, const float* e_prev, float* x_out,
+                                      double a, double b, size_t n, float* sums4, hipStream_t st);
 hipError_t launch_rel_mae(const float* a, const float* b, size_t n, float* out3, void* ws,
                           hipStream_t st);
 

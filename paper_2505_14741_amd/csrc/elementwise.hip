@@ -3,6 +3,8 @@
 // relative-MAE sums of paper Eq. (1), and the stand-alone relative MAE.
 #include "common.h"
 
+#include <mutex>
+
 namespace ps {
 
 static constexpr int WAVE = 64;
@@ -603,6 +605,37 @@ hipError_t launch_sampler_step(const float* x, const float* e, const float* e_pr
     if (err != hipSuccess) return err;
     if (sums4) finish_sums4_kernel<<<1, FIN_THREADS, 0, st>>>(part, blocks, sums4);
     return hipGetLastError();
+}
+
+// Partial sums of sampler_step for callers that may not allocate: a file-scope device array (1 MiB, held by
+// every GPU the library runs on until the process ends) instead of a caller-supplied workspace.  In host code the
+// array's name is only a stand-in; its device address is looked up once per device, with that device current, and
+// kept.  Nothing in it has to start at zero: stage 1 writes the partial sums of every workgroup it launches and
+// stage 2 reads exactly those.  Calls that overlap on one GPU share the array and race.
+static __device__ __align__(256) double scratch[(size_t)RED_MAX_BLOCKS * 4];
+static constexpr int SCRATCH_MAX_DEVICES = 64;
+static double* scratch_ptr[SCRATCH_MAX_DEVICES];     // device address of `scratch` on each device (nullptr: not yet asked)
+static std::mutex scratch_mutex;
+
+hipError_t launch_sampler_step_static(const float* x, const float* e, const float* e_prev, float* x_out,
+                                      double a, double b, size_t n, float* sums4, hipStream_t st) {
+    double* ptr = nullptr;
+    if (sums4) {
+        int dev = -1;
+        hipError_t err = hipGetDevice(&dev);
+        if (err != hipSuccess) return err;
+        if (dev < 0 || dev >= SCRATCH_MAX_DEVICES) return hipErrorInvalidDevice;
+        std::lock_guard<std::mutex> lock(scratch_mutex);
+        if (scratch_ptr[dev] == nullptr) {
+            void* p = nullptr;
+            err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (err != hipSuccess) return err;
+            if (p == nullptr) return hipErrorInvalidSymbol;
+            scratch_ptr[dev] = static_cast<double*>(p);
+        }
+        ptr = scratch_ptr[dev];
+    }
+    return launch_sampler_step(x, e, e_prev, x_out, a, b, n, sums4, ptr, st);
 }
 
 __global__ void __launch_bounds__(RED_THREADS)

@@ -221,6 +221,12 @@ def test_sampler_step_and_rel_mae_validation():
     assert f(x=None) == -1 and f(e=None) == -1 and f(xo=None) == -1
     assert f(xo=E) == -2 and f(xo=P) == -2 and f(x=X + 8) == -2
     assert f(ws=None) == -4 and f(wsb=need - 1) == -4 and f(ws=WS + 64) == -4
+    # the entry point without a workspace: same checks, and a size limit (the scratch array is fixed)
+    h = lambda **k: L.sampler_step_noalloc(k.get("x", X), k.get("e", E), k.get("p", P), k.get("xo", X), 1.0, 0.5,
+                                           k.get("n", 1000), None, None)
+    assert h(x=None) == -1 and h(e=None) == -1 and h(xo=None) == -1
+    assert h(xo=E) == -2 and h(xo=P) == -2 and h(x=X + 8) == -2
+    assert h(n=(1 << 31) + 1) == -2
     g = lambda **k: L.rel_mae(k.get("a", X), k.get("b", E), 1000, k.get("o", 0x5000), k.get("ws", WS),
                               k.get("wsb", need), None)
     assert g(a=None) == -1 and g(o=None) == -1 and g(ws=None) == -4 and g(a=X + 4) == -2
