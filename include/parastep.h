@@ -163,7 +163,8 @@ PS_API int attn3d(const void* q, const void* k, const void* v, void* o,
 /* The projection every DiT sub-layer uses, exposed for per-kernel parity and timing:
  * out[M, n_out] = act(a[M, k] * w[n_out, k]^T + bias), act 0 = none, 1 = tanh-GELU.
  * a, w, out DEVICE in `dtype`, row-major, 16-byte aligned; bias DEVICE fp32 [n_out],
- * 16-byte aligned.  n_out even, k % 8 == 0.
+ * 16-byte aligned.  n_out even, k % 8 == 0; bf16 shapes of the MFMA kernel (k % 64 == 0,
+ * n_out % 4 == 0, n_out >= 64) need m * n_out < 2^31.
  * workspace: DEVICE scratch, 256-byte aligned, or NULL.  With at least
  * dit_linear_workspace_bytes(...) of it, shapes whose output tiles do not fill the last round
  * of workgroups split those tiles along k (fp32 partial sums pass through the workspace and
@@ -197,7 +198,8 @@ PS_API int sampler_step(const float* x, const float* eps, const float* eps_prev,
  * process ends) instead of a workspace; the call allocates and frees nothing.
  * n <= SAMPLER_STEP_NOALLOC_MAX_N, larger sizes are PS_ERR_SHAPE.  The device current at the call
  * must be the one `hip_stream` belongs to (the array's address is looked up per device, on first
- * use).  Every call on a GPU shares that GPU's array: calls that overlap on one GPU (two streams,
+ * use with sums4 != NULL: a caller that captures its stream into a graph makes one such call on the
+ * device beforehand).  Every call on a GPU shares that GPU's array: calls that overlap on one GPU (two streams,
  * two threads) race on it; calls in order on one stream do not. */
 #define SAMPLER_STEP_NOALLOC_MAX_N ((size_t)1 << 31)
 PS_API int sampler_step_noalloc(const float* x, const float* eps, const float* eps_prev, float* x_out,

@@ -424,6 +424,11 @@ int dit_linear(const void* a, const void* w, const float* bias, void* out, int m
     if (!aligned(a, 16) || !aligned(w, 16) || !aligned(out, 16) || !aligned(bias, 16) || out == a || out == w)
         return PS_ERR_SHAPE;
     if (workspace && !aligned(workspace, 256)) return PS_ERR_WORKSPACE;
+    // a bf16 shape that belongs to the MFMA kernel but whose output exceeds its 32-bit offsets is refused, not
+    // handed to the slow generic kernel
+    if (dtype == PS_BF16 && (kernel_path & 0xff) != 1 && k % 64 == 0 && n_out % 4 == 0 && n_out >= 64 &&
+        (long)m * n_out >= (1L << 31))
+        return PS_ERR_SHAPE;
     Epilogue ep{};
     ep.kind = act ? EPI_BIAS_GELU : EPI_BIAS;
     ep.bias = bias;

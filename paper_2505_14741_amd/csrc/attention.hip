@@ -985,11 +985,16 @@ attn_sp_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const
 // many ways the rest is split along the keys.
 struct AttnPlan { int qblocks, items_ps, full_ps, tail_ps, nsplit, bq; };
 static int compute_units() {
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-        cus = 256;
-    return cus;
+    // per device, asked once (a constant of the device, not a setting)
+    static int cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+        cached[dev] = cus;
+    }
+    return cached[dev];
 }
 // kernel path 3 sends every head to the reference-tracking kernel; otherwise heads with provably bounded
 // exponents take the check-free software-pipelined kernel

@@ -646,11 +646,16 @@ bool gemm_mfma_supported(int tokens, int Nn, int K) {
 // how the rest is split.  A function of the sample's shape only (never of the batch): see gemm_mfma_kernel.
 struct GemmPlan { int variant, bm, bn, per_cu, tiles_m, tiles_n, full, tail, nsplit; size_t ws_bytes_per_sample; };
 static int gemm_compute_units() {
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-        cus = 256;
-    return cus;
+    // per device, asked once (a constant of the device, not a setting)
+    static int cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+        cached[dev] = cus;
+    }
+    return cached[dev];
 }
 
 struct TileVariant { int bm, bn, per_cu; float cost; };

@@ -200,6 +200,7 @@ def test_dit_linear_validation_and_workspace_size():
     assert f(m=0) == -2 and f(n=63) == -2 and f(k=60) == -2 and f(act=2) == -2
     assert f(out=A) == -2 and f(a=A + 2) == -2 and f(bias=BI + 4) == -2
     assert f(ws=WS + 16, wsb=1 << 20) == -4
+    assert f(m=1 << 20, n=4096) == -2                                  # 2^32 bf16 outputs: beyond the MFMA kernel's offsets
     # scratch is only asked for where the K-split of the last partial round of tiles pays: 17776 x 1920 x 7680
     # leaves 37 of 2085 tiles of 128 x 128 for a 5th round on 512 workgroup slots; they are split 8 ways
     assert L.dit_linear_workspace_bytes(17776, 1920, 7680, 1, 0x200) == 37 * 8 * 128 * 128 * 4
