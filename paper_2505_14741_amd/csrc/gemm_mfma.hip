@@ -595,9 +595,9 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
     gemm_tile<BM, BN, WR, WC, BK, NST, KIND>(A, W, C, g.tokens, Nn, K, m0, n0, k0, k1, piece, ep, lds);
 }
 
-// Sums the K-split pieces of the tail tiles (fixed order: deterministic) and applies the epilogue; one
-// single-wave workgroup per wave of gemm_mfma_kernel's layout (the few tail tiles then spread over four times
-// as many compute units: the kernel is a chain of dependent loads).
+// Sums the K-split pieces of the tail tiles (fixed order: deterministic) and applies the epilogue; one single-wave
+// workgroup per 32-row strip of each wave of gemm_mfma_kernel's layout (the few tail tiles then spread over 8 to 16
+// times as many compute units as they had workgroups: the kernel is a chain of dependent loads).
 template <int BM, int BN, int WR, int WC, int KIND>
 __global__ void __launch_bounds__(64)
 gemm_tail_kernel(bf16_t* __restrict__ C, int Nn, GemmGrid g, Epilogue ep) {
@@ -606,7 +606,7 @@ gemm_tail_kernel(bf16_t* __restrict__ C, int Nn, GemmGrid g, Epilogue ep) {
     constexpr int TM = WM / 32, TN = WN / 32;
     __shared__ __attribute__((aligned(16))) float patch[EPI_LDS_FLOATS];
     const int lane = threadIdx.x;
-    const int wave = blockIdx.x % NW, tail = blockIdx.x / NW;      // tail: over all samples
+    const int strip = blockIdx.x % TM, wave = (blockIdx.x / TM) % NW, tail = blockIdx.x / (TM * NW);   // tail: over all samples
     const int wm = wave / WC, wn = wave % WC;
     const int sample = tail / g.tail_tiles;
     const int tile = g.full_tiles + tail % g.tail_tiles;
@@ -615,26 +615,23 @@ gemm_tail_kernel(bf16_t* __restrict__ C, int Nn, GemmGrid g, Epilogue ep) {
     const int M = g.tokens, nsplit = g.nsplit;
     int m0, n0;
     tile_origin(tile, g.tiles_m, g.tiles_n, BM, BN, m0, n0);
-    f32x4_t acc[TM][TN][4];
+    f32x4_t acc[1][TN][4];
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) acc[i][j][q] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        for (int q = 0; q < 4; ++q) acc[0][j][q] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     for (int pi = 0; pi < nsplit; ++pi) {
         const float* pp = ep.split_ws + ((((long)tail * nsplit + pi) * NW + wave) * (TM * TN) * 64 + lane) * 16;
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    acc[i][j][q] += *reinterpret_cast<const f32x4_t*>(pp + (i * TN + j) * 64 * 16 + q * 4);
+            for (int q = 0; q < 4; ++q)
+                acc[0][j][q] += *reinterpret_cast<const f32x4_t*>(pp + (strip * TN + j) * 64 * 16 + q * 4);
     }
-    wave_epilogue<TM, TN, 0, KIND, true>(acc, ep, C, M, Nn, m0 + wm * WM, n0 + wn * WN, lane, patch);
+    const int wrow0 = m0 + wm * WM + strip * 32;
+    wave_epilogue<1, TN, 0, KIND, true>(acc, ep, C, M, Nn, wrow0, n0 + wn * WN, lane, patch);
     if constexpr (TN == 4)
-        wave_epilogue<TM, TN, 2, KIND, true>(acc, ep, C, M, Nn, m0 + wm * WM, n0 + wn * WN + 64, lane, patch);
+        wave_epilogue<1, TN, 2, KIND, true>(acc, ep, C, M, Nn, wrow0, n0 + wn * WN + 64, lane, patch);
 }
 
 // `tokens` rows per sample; offsets inside a sample are 32-bit element indices
@@ -744,7 +741,7 @@ static hipError_t launch_kind(const bf16_t* A, const bf16_t* W, bf16_t* C, int b
     gemm_mfma_kernel<BM, BN, WR, WC, BK, NST, KIND><<<grid, block, 0, st>>>(A, W, C, Nn, K, g, ep);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.tail == 0) return e;
-    gemm_tail_kernel<BM, BN, WR, WC, KIND><<<batch * p.tail * (WR * WC), 64, 0, st>>>(C, Nn, g, ep);
+    gemm_tail_kernel<BM, BN, WR, WC, KIND><<<batch * p.tail * (WR * WC) * (BM / WR / 32), 64, 0, st>>>(C, Nn, g, ep);
     return hipGetLastError();
 }
 
