@@ -22,10 +22,7 @@
  *  - a sample's result does not depend on the batch it is computed in: every sample of a
  *    batch is tiled and summed exactly as if it were alone (Section 3.3: the batched step
  *    must reproduce the per-step process), so dit_forward on B samples equals B calls bit
- *    for bit (one caveat: which of two softmax kernels a head takes is decided from an
- *    upper bound of its largest query and key norm that is formed per tile of rows; a head
- *    within a factor 2 of that limit may be sent to the other kernel, whose result differs
- *    in rounding);
+ *    for bit;
  *  - the library keeps no process-wide mutable state: kernels are selected per call from
  *    the shapes and from the kernel path of the handle (dit_set_kernel_path) or of the
  *    call (attn3d, dit_linear);
@@ -150,10 +147,11 @@ PS_API int ps_mfma_probe(int iters, float* sink, double* flops_out, void* hip_st
  * the inputs.  seq >= 1, scale > 0, head_dim in {16, 32, 64}; rows past the end are never
  * read, but V must be finite (masked keys multiply V by an exact 0).
  * workspace: DEVICE, 256-byte aligned, >= attn3d_workspace_bytes(...) (may be NULL when
- * that is 0); scratch only.  It is non-zero for bf16 with head_dim 64: those kernels keep the
- * largest query and key norm of every (batch, head) there (heads whose scores are provably
- * bounded take a softmax without running maximum) and the partial sums of the workgroups
- * that split their keys in the last, partial round (merged by a second kernel).
+ * that is 0); scratch only.  It is non-zero for bf16 with head_dim 64: the kernel that needs no
+ * running maximum checks its own sums and marks, per (batch, head), what it could not do there
+ * (a second kernel that tracks a softmax reference recomputes those heads), and the workgroups
+ * that split their keys in the last, partial round leave their partial sums there (merged by
+ * that second launch).
  * kernel_path: as for dit_set_kernel_path (0 = default); the workspace size does not depend on it. */
 PS_API size_t attn3d_workspace_bytes(int batch, int seq, int heads, int head_dim, int dtype);
 PS_API int attn3d(const void* q, const void* k, const void* v, void* o,

@@ -193,28 +193,24 @@ int forward_impl(dit* d, const float* x, const void* ctx, const int32_t* t_host,
     for (int l = 0; l < L; ++l) {
         const LayerW& lw = d->layers[l];
         const float* mod_l = mod + (long)l * 12 * D;
-        // the projection's epilogue leaves the per-head maxima of |q|^2 and |k|^2 the attention kernel selects on;
-        // the LayerNorm kernel in front of it clears them
-        const bool fused_bounds = c.head_dim == 64 && gemm_uses_mfma(dt, N, 3 * D, D, path);
-        int nbounds = 0;
-        float* bounds = fused_bounds ? attention_norm_bounds(dt, batch, c.heads, c.head_dim, attn_ws, path, st, false, &nbounds)
-                                     : nullptr;
+        // the attention kernels mark heads in a small flag array; the LayerNorm kernel in front of the QKV projection
+        // clears it instead of a launch of its own
+        int nflags = 0;
+        float* flags = attention_head_flags(dt, batch, c.heads, c.head_dim, attn_ws, path, st, false, &nflags);
         // h = LN(X)(1+scale_a)+shift_a
-        PS_TIMED(KC_LN, launch_ln_modulate(dt, X, Hb, M, D, c.ln_eps, mod_l, mod_bs, 0, 1, geom, st, bounds, nbounds));
+        PS_TIMED(KC_LN, launch_ln_modulate(dt, X, Hb, M, D, c.ln_eps, mod_l, mod_bs, 0, 1, geom, st, flags, nflags));
         // [q|k|v] = W_qkv h + b, rotary on video q,k
         Epilogue eq{};
         eq.kind = EPI_QKV_ROPE; eq.bias = lw.b_qkv; eq.D = D; eq.geom = geom;
         eq.rope_cs = rope; eq.head_dim = c.head_dim; eq.rope_F = c.frames; eq.rope_Hp = d->Hp; eq.rope_Wp = d->Wp;
         eq.q_scale = prescale ? scale * 1.4426950408889634f : 1.0f;
         eq.split_ws = gemm_ws; eq.split_ws_bytes = w.gemm_bytes;
-        eq.norm_bounds = bounds;
-        eq.heads = c.heads;
         PS_TIMED(KC_QKV, launch_gemm(dt, Hb, lw.W_qkv, QKV, batch, N, 3 * D, D, eq, path, st));
         // o = attention(q, k, v) -> Hb (token-major, heads concatenated)
         const char* qp = (const char*)QKV;
         PS_TIMED(KC_ATTN, launch_attention(dt, qp, qp + (size_t)D * es, qp + (size_t)2 * D * es, Hb, batch, N,
                                            c.heads, c.head_dim, scale, as, attn_ws, path, st, prescale,
-                                           eq.norm_bounds != nullptr));
+                                           flags != nullptr));
         // X += gate_a * (W_o o + b_o)
         Epilogue eo{};
         eo.kind = EPI_GATE_RESIDUAL; eo.bias = lw.b_o; eo.resid = X; eo.mod_layer = mod_l;

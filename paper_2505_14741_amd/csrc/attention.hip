@@ -177,81 +177,23 @@ __device__ __forceinline__ float sum_across_halves(float v) {
 //    of the running sums.
 // PRESCALED: q already carries the factor c = scale*log2(e) (the QKV projection applies it
 // in fp32 before rounding), so p = exp2(acc) with no multiply; otherwise p = exp2(c*acc).
-// ---- fast variant for bounded scores ------------------------------------------------------
-// attn_bound_kernel finds, per (batch, head), the largest squared norm of a query row and of a
-// key row.  By Cauchy-Schwarz every exponent c*s of that head lies within +-c*|q|max*|k|max; if
-// that is below PP_EXP_LIMIT, 2^(c s) can neither overflow nor sum to zero, so the softmax
-// needs no reference value, no maximum and no check at all, and attn_sp_kernel takes the head.
-// Heads above the limit are left to attn_mfma_kernel, which tracks a reference.
-constexpr float PP_EXP_LIMIT = 60.0f;
+// ---- fast variant without a reference --------------------------------------------------------
+// attn_sp_kernel accumulates sum_j 2^(c s_j) v_j and sum_j 2^(c s_j) as they are: the quotient is the softmax
+// whenever no term overflows and the sum does not vanish, which is the case for every head whose exponents c*s
+// stay within roughly +-100 of zero.  It does not look for maxima; it checks its result instead.  A query row
+// whose key sum l is outside [2^-40, 2^100], or whose accumulators are not finite, marks its (batch, head) in
+// a flag array; the launch of attn_mfma_kernel that follows recomputes exactly the marked heads with a tracked
+// reference and overwrites them.  (l >= 2^-40 also bounds what flushing tiny terms to zero can cost: with
+// l >= 2^-40 the largest term is at least 2^-40 / N, and the terms below the smallest normal number, 2^-126,
+// sum to less than N * 2^-126, i.e. a fraction below 2^-58 of l for any sequence this kernel accepts.)
+// The check is exact about what went wrong, where a bound on the exponents from the largest query and key
+// norms (Cauchy-Schwarz) would send every head with large norms, however harmless its scores, to the slower kernel;
+// heads that really overflow are computed twice.
+constexpr float SP_SUM_MIN = 0x1p-40f, SP_SUM_MAX = 0x1p+100f;
 
-__global__ void attn_bound_clear_kernel(float* __restrict__ bounds, int n) {
+__global__ void attn_flags_clear_kernel(unsigned* __restrict__ flags, int n) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) bounds[i] = 0.f;
-}
-
-// grid (blocks of BOUND_ROWS tokens, batch).  A workgroup walks its rows' q and k slices of ALL heads in
-// memory order (8 lanes per 128-byte head slice), keeps per-head maxima in LDS and ends with one
-// conditional atomic per head.  bounds[2*bh] = max |q|^2, bounds[2*bh+1] = max |k|^2
-constexpr int BOUND_ROWS = 32, BOUND_MAX_HEADS = 128;
-__global__ void __launch_bounds__(256)
-attn_bound_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int seq, int heads, AttnStrides s,
-                  float* __restrict__ bounds) {
-    __shared__ unsigned smax[2][BOUND_MAX_HEADS];
-    const int b = blockIdx.y, row0 = blockIdx.x * BOUND_ROWS;
-    const int rows = min(BOUND_ROWS, seq - row0);
-    for (int i = threadIdx.x; i < 2 * BOUND_MAX_HEADS; i += 256) (&smax[0][0])[i] = 0u;
-    __syncthreads();
-    const bf16_t* qb = q + b * s.q_batch + (long)row0 * s.q_tok;
-    const bf16_t* kb = k + b * s.k_batch + (long)row0 * s.k_tok;
-    const int per_row = heads * 8, total = rows * per_row;
-    for (int c0 = 0; c0 < total; c0 += 4 * 256) {
-        bf16x8_t a[4], w[4];
-        int hd[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            int c = c0 + u * 256 + threadIdx.x;
-            c = c < total ? c : total - 1;            // the tail repeats the last slice: same maxima
-            const int r = c / per_row, rem = c - r * per_row;
-            hd[u] = rem >> 3;
-            a[u] = *reinterpret_cast<const bf16x8_t*>(qb + (long)r * s.q_tok + hd[u] * s.q_head + (rem & 7) * 8);
-            w[u] = *reinterpret_cast<const bf16x8_t*>(kb + (long)r * s.k_tok + hd[u] * s.k_head + (rem & 7) * 8);
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            float nq = 0.f, nk = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                nq += (float)a[u][e] * (float)a[u][e];
-                nk += (float)w[u][e] * (float)w[u][e];
-            }
-#pragma unroll
-            for (int off = 1; off < 8; off <<= 1) {   // the 8 lanes of a (token, head)
-                nq += __shfl_xor(nq, off);
-                nk += __shfl_xor(nk, off);
-            }
-            // NaN or inf norms must disqualify the head: map them to +inf, which orders above everything;
-            // non-negative floats order like their bit patterns
-            if (!(nq < INFINITY)) nq = INFINITY;
-            if (!(nk < INFINITY)) nk = INFINITY;
-            if ((threadIdx.x & 7) == 0) {
-                atomicMax(&smax[0][hd[u]], __float_as_uint(nq));
-                atomicMax(&smax[1][hd[u]], __float_as_uint(nk));
-            }
-        }
-    }
-    __syncthreads();
-    for (int i = threadIdx.x; i < 2 * heads; i += 256) {
-        const int hh = i >> 1, which = i & 1;
-        const unsigned m = smax[which][hh];
-        unsigned* dst = reinterpret_cast<unsigned*>(bounds + 2 * (b * heads + hh) + which);
-        if (m > __builtin_nontemporal_load(dst)) atomicMax(dst, m);
-    }
-}
-
-__device__ __forceinline__ bool head_is_bounded(const float* __restrict__ bounds, int bh, float c) {
-    const float e = sqrtf(bounds[2 * bh]) * sqrtf(bounds[2 * bh + 1]) * c;
-    return e < PP_EXP_LIMIT;                 // false for NaN and inf
+    if (i < n) flags[i] = 0u;
 }
 
 static constexpr int PART_STRIDE = 68;      // floats per row of a partial result (64 + l + r, padded to 16 B)
@@ -296,7 +238,7 @@ __device__ __forceinline__ void attn_item(const AttnGrid& g, int id, int nt, int
 // g: the plan the pieces were produced under; nitems = batch * g.tail_ps
 __device__ __forceinline__ void
 attn_merge_rows(int block, const float* __restrict__ part, bf16_t* __restrict__ o, int seq, const AttnGrid& g,
-                int nitems, float cexp, int bq, const AttnStrides& s, const float* __restrict__ bounds) {
+                int nitems, float cexp, int bq, const AttnStrides& s, const unsigned* __restrict__ fail) {
     const int gid = block * 256 + threadIdx.x;
     const int d4 = gid & 15, rowid = gid >> 4;          // 16 threads per row
     const int item = rowid / bq, row = rowid % bq;      // item: over all samples
@@ -305,7 +247,7 @@ attn_merge_rows(int block, const float* __restrict__ part, bf16_t* __restrict__ 
     const int local = g.full_ps + item % g.tail_ps;
     const int h = local / g.qblocks, qb = local % g.qblocks;
     const int bh = sample * g.heads + h;
-    if (bounds != nullptr && !head_is_bounded(bounds, bh, cexp)) return;   // pieces exist for attn_sp_kernel's heads only
+    if (fail != nullptr && fail[bh] != 0u) return;      // a marked head is recomputed whole by attn_mfma_kernel
     const int b = sample;
     const int qi = qb * bq + row;
     if (qi >= seq) return;
@@ -331,8 +273,8 @@ attn_merge_rows(int block, const float* __restrict__ part, bf16_t* __restrict__ 
 
 __global__ void __launch_bounds__(256)
 attn_merge_kernel(const float* __restrict__ part, bf16_t* __restrict__ o, int seq, AttnGrid g, int nitems, float cexp,
-                  int bq, AttnStrides s, const float* __restrict__ bounds) {
-    attn_merge_rows(blockIdx.x, part, o, seq, g, nitems, cexp, bq, s, bounds);
+                  int bq, AttnStrides s, const unsigned* __restrict__ fail) {
+    attn_merge_rows(blockIdx.x, part, o, seq, g, nitems, cexp, bq, s, fail);
 }
 
 // Merge work that rides on a launch of attn_mfma_kernel: its first `blocks` workgroups merge the pieces another,
@@ -379,9 +321,9 @@ template <int QT, bool PRESCALED>   // QT: 32-query column tiles per wave
 __global__ void __launch_bounds__(256, 2)
 attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
                  bf16_t* __restrict__ o, int seq, float scale_log2e, AttnStrides s, AttnGrid grid,
-                 float* __restrict__ part, const float* __restrict__ bounds, MergeTail mt) {
+                 float* __restrict__ part, const unsigned* __restrict__ fail, MergeTail mt) {
     if ((int)blockIdx.x < mt.blocks) {                      // whole workgroup: before any barrier
-        attn_merge_rows(blockIdx.x, mt.part, o, seq, mt.g, mt.nitems, mt.cexp, mt.bq, s, bounds);
+        attn_merge_rows(blockIdx.x, mt.part, o, seq, mt.g, mt.nitems, mt.cexp, mt.bq, s, fail);
         return;
     }
     const int heads = grid.heads;
@@ -398,8 +340,8 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
     // piece of a split item leaves unnormalised sums, row sum and reference in `part` for the merge.
     int bh, qb, piece, jt0, jt1;
     attn_item(grid, blockIdx.x - mt.blocks, (seq + KV - 1) / KV, bh, qb, piece, jt0, jt1);
-    // with `bounds` given, heads whose exponents are provably small belong to attn_sp_kernel
-    if (bounds != nullptr && head_is_bounded(bounds, bh, PRESCALED ? 1.0f : scale_log2e)) return;
+    // with `fail` given, only the heads attn_sp_kernel marked are (re)computed here
+    if (fail != nullptr && fail[bh] == 0u) return;
     const int b = bh / heads, h = bh % heads;
     const int q0 = qb * BQ + wave * (QT * 32);
 
@@ -725,7 +667,7 @@ template <bool PRESCALED>
 __global__ void __launch_bounds__(256, 2)
 attn_sp_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
                bf16_t* __restrict__ o, int seq, float scale_log2e, AttnStrides s, AttnGrid grid,
-               float* __restrict__ part, const float* __restrict__ bounds) {
+               float* __restrict__ part, unsigned* __restrict__ fail) {
     constexpr int QT = 2;                        // 32-query column tiles per wave
     constexpr int KV = 64;                       // keys per tile
     constexpr int BQ = 4 * QT * 32;              // queries per workgroup
@@ -741,7 +683,6 @@ attn_sp_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const
     int bh, qb, piece, jt0, jt1;
     attn_item(grid, blockIdx.x, (seq + KV - 1) / KV, bh, qb, piece, jt0, jt1);
     const float cexp = PRESCALED ? 1.0f : scale_log2e;
-    if (!head_is_bounded(bounds, bh, cexp)) return;          // whole workgroup: before any barrier
     const int b = bh / heads, h = bh % heads;
     const int q0 = qb * BQ + wave * (QT * 32);
 
@@ -943,6 +884,23 @@ attn_sp_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const
     pv(pb, (jt1 - 1 - jt0) & (NST - 1), 1);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // drain the look-ahead loads before exit
 
+    // the result checks itself (see SP_SUM_MIN): key sums out of range or accumulators that are not finite mark the
+    // head for attn_mfma_kernel.  (A key range of a split item is held to the same limits as a whole row: a range
+    // whose keys all lie far below the row's maximum sends the head to the other kernel, which costs time only.)
+    {
+        bool bad = false;
+#pragma unroll
+        for (int t = 0; t < QT; ++t) {
+            const float l = rowsum_of(t);
+            float mag = 0.f;
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) mag += fabsf(oacc[dt][t][e]);
+            bad = bad || !(l >= SP_SUM_MIN && l <= SP_SUM_MAX) || !(mag < INFINITY);
+        }
+        if (__any(bad) && lane == 0) fail[bh] = 1u;
+    }
     if (piece >= 0) {
         // partial result of a key range, reference 0: [piece][row in block][64 sums | row sum | 0 | pad]
         float* pp = part + (long)piece * BQ * PART_STRIDE;
@@ -996,9 +954,9 @@ static int compute_units() {
     }
     return cached[dev];
 }
-// kernel path 3 sends every head to the reference-tracking kernel; otherwise heads with provably bounded
-// exponents take the check-free software-pipelined kernel
-static bool attention_bounded_path(int heads, int path) { return (path & 0xff) != 3 && heads <= BOUND_MAX_HEADS; }
+// kernel path 3 sends every head to the reference-tracking kernel; otherwise every head first takes the
+// software-pipelined kernel without a reference, which marks the heads it could not do
+static bool attention_checked_path(int path) { return (path & 0xff) != 3; }
 static AttnPlan attention_plan(int seq, int heads) {
     constexpr int KV = 64;
     AttnPlan p;
@@ -1016,64 +974,62 @@ static AttnPlan attention_plan(int seq, int heads) {
     return p;
 }
 
-static size_t bounds_bytes(int batch, int heads) { return (((size_t)batch * heads * 2 * sizeof(float)) + 255) & ~(size_t)255; }
+static size_t flags_bytes(int batch, int heads) { return (((size_t)batch * heads * sizeof(unsigned)) + 255) & ~(size_t)255; }
 
-// workspace of the bf16 head-dim-64 kernels: [2 floats per (batch, head): norm bounds | key-split pieces]
+// workspace of the bf16 head-dim-64 kernels: [one flag per (batch, head) | key-split pieces]
 size_t attention_workspace_bytes(int dtype, int batch, int seq, int heads, int head_dim) {
     if (dtype != PS_BF16 || head_dim != 64 || batch < 1 || seq < 1 || heads < 1) return 0;
     const AttnPlan p = attention_plan(seq, heads);
     const size_t need = (size_t)batch * p.tail_ps * p.nsplit * p.bq * PART_STRIDE * sizeof(float);
-    return bounds_bytes(batch, heads) + need;
+    return flags_bytes(batch, heads) + need;
 }
 
 bool attention_uses_mfma(int dtype, int head_dim, int path) {
     return dtype == PS_BF16 && head_dim == 64 && (path & 0xff) != 1;
 }
 
-float* attention_norm_bounds(int dtype, int batch, int heads, int head_dim, void* ws, int path, hipStream_t st,
-                             bool clear, int* count) {
+float* attention_head_flags(int dtype, int batch, int heads, int head_dim, void* ws, int path, hipStream_t st,
+                            bool clear, int* count) {
     if (count) *count = 0;
-    if (!ws || !attention_uses_mfma(dtype, head_dim, path) || !attention_bounded_path(heads, path)) return nullptr;
-    const int nb = batch * heads * 2;
+    if (!ws || !attention_uses_mfma(dtype, head_dim, path) || !attention_checked_path(path)) return nullptr;
+    const int nb = batch * heads;
     if (count) *count = nb;
     if (!clear) return (float*)ws;
-    attn_bound_clear_kernel<<<(nb + 255) / 256, 256, 0, st>>>((float*)ws, nb);
+    attn_flags_clear_kernel<<<(nb + 255) / 256, 256, 0, st>>>((unsigned*)ws, nb);
     return hipGetLastError() == hipSuccess ? (float*)ws : nullptr;
 }
 
 hipError_t launch_attention(int dtype, const void* q, const void* k, const void* v, void* o,
                             int batch, int seq, int heads, int head_dim, float scale,
                             const AttnStrides& s, void* ws, int path, hipStream_t st, bool q_prescaled,
-                            bool bounds_ready) {
+                            bool flags_cleared) {
     if (attention_uses_mfma(dtype, head_dim, path)) {
         if (ws == nullptr) return hipErrorInvalidValue;
         if (s.k_tok >= (1 << 24) || s.v_tok >= (1 << 24)) return hipErrorInvalidValue;   // 32-bit in-tile offsets
-        const bool bounded = attention_bounded_path(heads, path);
+        const bool checked = attention_checked_path(path);
         AttnPlan p = attention_plan(seq, heads);
         if ((path & 0xff) == 2) { p.full_ps = p.items_ps; p.tail_ps = 0; p.nsplit = 1; }
         const float c = scale * 1.4426950408889634f;
         const float cexp = q_prescaled ? 1.0f : c;
         const bf16_t *qq = (const bf16_t*)q, *kk = (const bf16_t*)k, *vv = (const bf16_t*)v;
-        float* bounds = (float*)ws;
-        float* part = (float*)((char*)ws + bounds_bytes(batch, heads));
+        unsigned* flags = (unsigned*)ws;
+        float* part = (float*)((char*)ws + flags_bytes(batch, heads));
         const int bq = p.bq;
         const AttnGrid split{p.qblocks, heads, p.full_ps, p.tail_ps, p.nsplit, batch * p.full_ps};
         const AttnGrid whole{p.qblocks, heads, p.items_ps, 0, 1, batch * p.items_ps};
         const int split_blocks = batch * (p.full_ps + p.tail_ps * p.nsplit);
         const int nitems = batch * p.tail_ps;
-        if (bounded) {
-            // norm bounds per (batch, head), then the check-free kernel for the heads they qualify and the
-            // reference-tracking kernel (unsplit) for the others; each workgroup looks its head up
-            if (!bounds_ready) {
-                const int nb = batch * heads * 2;
-                attn_bound_clear_kernel<<<(nb + 255) / 256, 256, 0, st>>>(bounds, nb);
-                attn_bound_kernel<<<dim3((seq + BOUND_ROWS - 1) / BOUND_ROWS, batch), 256, 0, st>>>(qq, kk, seq, heads, s,
-                                                                                                 bounds);
+        if (checked) {
+            // the kernel without a reference for every head (it marks the heads whose sums left the safe range),
+            // then the reference-tracking kernel (unsplit) for the marked heads; each of its workgroups looks its head up
+            if (!flags_cleared) {
+                const int nb = batch * heads;
+                attn_flags_clear_kernel<<<(nb + 255) / 256, 256, 0, st>>>(flags, nb);
             }
             if (q_prescaled)
-                attn_sp_kernel<true><<<split_blocks, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, c, s, split, part, bounds);
+                attn_sp_kernel<true><<<split_blocks, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, c, s, split, part, flags);
             else
-                attn_sp_kernel<false><<<split_blocks, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, c, s, split, part, bounds);
+                attn_sp_kernel<false><<<split_blocks, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, c, s, split, part, flags);
             // then the reference-tracking kernel (unsplit) for the other heads; the merge of attn_sp_kernel's pieces
             // rides on that launch as workgroups in front of the items
             MergeTail mt{part, 0, nitems, bq, cexp, split};
@@ -1081,10 +1037,10 @@ hipError_t launch_attention(int dtype, const void* q, const void* k, const void*
             if (nitems != 0) mt.blocks = ((int)(((long)nitems * bq * 16 + 255) / 256) + 7) & ~7;
             if (q_prescaled)
                 attn_mfma_kernel<2, true><<<whole.all_full + mt.blocks, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, c, s,
-                                                                                    whole, nullptr, bounds, mt);
+                                                                                    whole, nullptr, flags, mt);
             else
                 attn_mfma_kernel<2, false><<<whole.all_full + mt.blocks, 256, 0, st>>>(qq, kk, vv, (bf16_t*)o, seq, c, s,
-                                                                                     whole, nullptr, bounds, mt);
+                                                                                     whole, nullptr, flags, mt);
             return hipGetLastError();
         }
         // (one 32-query tile per wave, i.e. 128-query workgroups at three per CU, measured 9 % slower:

@@ -56,10 +56,6 @@ struct Epilogue {
     int rope_F, rope_Hp, rope_Wp;
     int head_dim;
     float q_scale;            // factor applied to the q columns (col < D) after the rotation
-    // EPI_QKV_ROPE, bf16 MFMA kernel, head_dim 64, optional: [batch*heads][2] running maxima of the squared norms
-    // of the stored q and k rows per (batch, head), raised with atomic max (the caller zeroes them)
-    float* norm_bounds;
-    int heads;
     // EPI_UNPATCHIFY (bf16 MFMA kernel only): columns are (c, dy, dx) of a video token's patch; rows of text
     // tokens are dropped; resid is the fp32 output latent [B, C, F, H, W]
     PatchGeom pg;
@@ -100,18 +96,17 @@ struct AttnStrides { long q_tok, q_head, q_batch, k_tok, k_head, k_batch, v_tok,
 size_t attention_workspace_bytes(int dtype, int batch, int seq, int heads, int head_dim);
 // q_prescaled: q already carries scale*log2(e) (only valid when attention_uses_mfma()).
 bool attention_uses_mfma(int dtype, int head_dim, int path);
-// bounds_ready: the per-(batch, head) norm maxima at the head of `ws` are already in place (see
-// attention_norm_bounds()), so the pass over q and k that finds them is skipped.
+// flags_cleared: the per-(batch, head) flags at the head of `ws` are already zero (see attention_head_flags()), so
+// the launch that clears them is skipped.
 hipError_t launch_attention(int dtype, const void* q, const void* k, const void* v, void* o,
                             int batch, int seq, int heads, int head_dim, float scale,
                             const AttnStrides& s, void* ws, int path, hipStream_t st, bool q_prescaled = false,
-                            bool bounds_ready = false);
-// Where a producer of q and k may leave those maxima itself: zeroes [batch*heads][2] floats at the head of `ws`
-// on the stream and returns their address; nullptr if this shape's attention does not use them.
-// the per-(batch, head) norm maxima buffer of the bounded attention path inside ws (nullptr if that path is off);
-// *count = its length in floats; clear: zero it with a launch of its own (else the caller zeroes it before use)
-float* attention_norm_bounds(int dtype, int batch, int heads, int head_dim, void* ws, int path, hipStream_t st,
-                             bool clear = true, int* count = nullptr);
+                            bool flags_cleared = false);
+// The per-(batch, head) flag array of the bf16 head-dim-64 attention inside ws (nullptr if this shape or path has
+// none); *count = its length in 4-byte words; clear: zero it with a launch of its own (else the caller zeroes it
+// before the attention call, e.g. from a kernel that runs anyway).
+float* attention_head_flags(int dtype, int batch, int heads, int head_dim, void* ws, int path, hipStream_t st,
+                            bool clear = true, int* count = nullptr);
 
 hipError_t launch_sinusoid(const int32_t* t_host, float* out, int batch, int D, hipStream_t st);
 // out[b, r] = act(W[r,:] . in[b,:] + bias[r]);  act: 0 none, 1 SiLU.  W in dtype, in/out fp32.

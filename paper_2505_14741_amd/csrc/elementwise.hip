@@ -279,7 +279,7 @@ __global__ void ln_modulate_kernel(const float* __restrict__ X, T* __restrict__ 
                                    float eps, const float* __restrict__ mod_layer, long mod_bs,
                                    int shift_chunk, int scale_chunk, TokenGeom g, float* __restrict__ zero_buf,
                                    int zero_n) {
-    // a few words some later kernel accumulates into (the norm maxima of the QKV projection) are cleared here
+    // a few words some later kernel sets (the attention kernels' per-head flags) are cleared here
     // instead of by a launch of their own
     if (blockIdx.x == 0)
         for (int i = threadIdx.x; i < zero_n; i += blockDim.x) zero_buf[i] = 0.f;

@@ -121,10 +121,6 @@ __device__ __forceinline__ void wave_epilogue(f32x4_t (&acc)[TM][TN][4], const E
         gate_v = *reinterpret_cast<const f32x4_t*>(g + ep.gate_chunk * ep.D);
         gate_t = *reinterpret_cast<const f32x4_t*>(g + (ep.gate_chunk + 6) * ep.D);
     }
-    // norm maxima for the attention kernel (q and k columns; a wave's 64 columns are one head of 64)
-    bool track_norms = false;
-    int norm_head = 0, norm_which = 0, norm_split = 0;
-    unsigned nmax1 = 0u, nmax2 = 0u;
     if constexpr (KIND == EPI_QKV_ROPE) {
         rot = col < 2 * ep.D;                            // q and k columns rotate, v columns do not
         const int pr = (colc % ep.head_dim) >> 1;        // first of the lane's two pairs
@@ -133,10 +129,6 @@ __device__ __forceinline__ void wave_epilogue(f32x4_t (&acc)[TM][TN][4], const E
         inv_wp = 1.0f / (float)ep.rope_Wp;
         inv_hp = 1.0f / (float)ep.rope_Hp;
         qs = col < ep.D ? ep.q_scale : 1.0f;
-        track_norms = ep.norm_bounds != nullptr && wcol0 < 2 * ep.D && wcol0 < Nn;
-        norm_which = wcol0 < ep.D ? 0 : 1;
-        norm_head = (wcol0 - norm_which * ep.D) / 64;
-        norm_split = (b_first + 1) * tokens;             // first row of the next sample
     }
 
     // operands the strip needs from memory besides the accumulators (one 16-byte value per
@@ -221,17 +213,6 @@ __device__ __forceinline__ void wave_epilogue(f32x4_t (&acc)[TM][TN][4], const E
                 // t = (cos0, sin0, cos1, sin1); identity for text tokens and v columns
                 x = f32x4_t{x[0] * t[0] - x[1] * t[1], x[1] * t[0] + x[0] * t[1],
                             x[2] * t[2] - x[3] * t[3], x[3] * t[2] + x[2] * t[3]} * qs;
-                if (track_norms) {
-                    // this lane's 4 columns of the row (the values are stored as bf16, which moves a norm by at
-                    // most 2^-8 relative: covered by a factor on the final maximum).  Per-lane maxima over the
-                    // rows; the sum of the 16 lanes' maxima bounds the largest row norm from above (max of sums
-                    // <= sum of maxes), which is all the consumer needs.  Maxima are taken on the bit patterns
-                    // (non-negative floats order like unsigned integers; NaN orders above inf and ends as inf).
-                    // nmax1 covers every row of the wave, nmax2 only those of the sample after the first.
-                    const unsigned ss = __float_as_uint((x[0] * x[0] + x[1] * x[1]) + (x[2] * x[2] + x[3] * x[3]));
-                    nmax1 = max(nmax1, ss);
-                    if (!one_batch) nmax2 = max(nmax2, m >= norm_split ? ss : 0u);
-                }
             }
             if (CHECK && (m >= M || !col_ok)) continue;
             if constexpr (KIND == EPI_UNPATCHIFY) {
@@ -266,35 +247,6 @@ __device__ __forceinline__ void wave_epilogue(f32x4_t (&acc)[TM][TN][4], const E
             } else {
                 *reinterpret_cast<bf16x4_t*>(reinterpret_cast<unsigned short*>(C) + off) =
                     __builtin_convertvector(x, bf16x4_t);
-            }
-        }
-    }
-    if constexpr (KIND == EPI_QKV_ROPE) {
-        if (track_norms) {
-            // one or two atomics per wave (non-negative floats order like their bit patterns); a wave whose rows
-            // reach into a third sample (fewer tokens per sample than rows per wave) marks those samples' head
-            // as unbounded instead, which only sends it to the kernel that needs no bound
-            auto reduce = [&](unsigned bits) {
-                float v = __uint_as_float(bits);
-                v = (v < INFINITY) ? v : INFINITY;       // NaN -> inf
-                v += __shfl_xor(v, 1);                   // the 16 lanes that share rows ...
-                v += __shfl_xor(v, 2);
-                v += __shfl_xor(v, 4);
-                v += __shfl_xor(v, 8);
-                v = fmaxf(v, __shfl_xor(v, 16));         // ... and the 4 row groups
-                v = fmaxf(v, __shfl_xor(v, 32));
-                return (v < INFINITY) ? v * 1.01f : INFINITY;
-            };
-            const float n1 = reduce(nmax1), n2 = reduce(nmax2);
-            if (lane == 0) {
-                float* dst = ep.norm_bounds + 2 * (b_first * ep.heads + norm_head) + norm_which;
-                atomicMax(reinterpret_cast<unsigned*>(dst), __float_as_uint(n1));
-                const int b_last = row_last / tokens;
-                if (b_last > b_first)
-                    atomicMax(reinterpret_cast<unsigned*>(dst + 2 * ep.heads),
-                              __float_as_uint(b_last > b_first + 1 ? INFINITY : n2));
-                for (int b = b_first + 2; b <= b_last; ++b)
-                    atomicMax(reinterpret_cast<unsigned*>(dst + 2 * (b - b_first) * ep.heads), __float_as_uint(INFINITY));
             }
         }
     }
@@ -540,7 +492,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, const bf
 // Every sample of a batch (rows [b * tokens, (b+1) * tokens) of the operands) is tiled on its own: a tile never
 // holds rows of two samples, and which of its tiles are summed in K pieces depends on the sample's shape alone,
 // so a sample's result does not depend on the batch it is computed in (Section 3.3: the batched step must
-// reproduce the per-step process).  A workgroup shifts the operand, output, residual, modulation and norm-maximum
+// reproduce the per-step process).  A workgroup shifts the operand, output, residual and modulation
 // pointers to its sample and from then on works on a [tokens, Nn] problem.
 //
 // The first batch * full_tiles workgroups compute one BM x BN output tile each.  The tiles beyond them -- the last,
@@ -552,14 +504,12 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, const bf
 // loads the whole W panel again.)
 struct GemmGrid { int tokens, batch, tiles_m, tiles_n, full_tiles, tail_tiles, nsplit; };
 
+template <int KIND>
 __device__ __forceinline__ void shift_to_sample(Epilogue& ep, int sample, int tokens, int Nn) {
-    if (sample == 0) return;
-    if (ep.kind == EPI_GATE_RESIDUAL) {
+    if constexpr (KIND == EPI_GATE_RESIDUAL) {
         ep.resid += (long)sample * tokens * Nn;
         ep.mod_layer += (long)sample * ep.mod_batch_stride;
-    } else if (ep.kind == EPI_QKV_ROPE) {
-        if (ep.norm_bounds) ep.norm_bounds += 2L * sample * ep.heads;
-    } else if (ep.kind == EPI_UNPATCHIFY) {
+    } else if constexpr (KIND == EPI_UNPATCHIFY) {
         ep.resid += (long)sample * ep.pg.C * ep.pg.F * ep.pg.H * ep.pg.W;
     }
 }
@@ -589,7 +539,7 @@ gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, bf1
     sample = __builtin_amdgcn_readfirstlane(sample);
     A += (long)sample * g.tokens * K;
     if (C) C += (long)sample * g.tokens * Nn;
-    shift_to_sample(ep, sample, g.tokens, Nn);
+    shift_to_sample<KIND>(ep, sample, g.tokens, Nn);
     int m0, n0;
     tile_origin(tile, g.tiles_m, g.tiles_n, BM, BN, m0, n0);
     gemm_tile<BM, BN, WR, WC, BK, NST, KIND>(A, W, C, g.tokens, Nn, K, m0, n0, k0, k1, piece, ep, lds);
@@ -611,7 +561,7 @@ gemm_tail_kernel(bf16_t* __restrict__ C, int Nn, GemmGrid g, Epilogue ep) {
     const int sample = tail / g.tail_tiles;
     const int tile = g.full_tiles + tail % g.tail_tiles;
     if (C) C += (long)sample * g.tokens * Nn;
-    shift_to_sample(ep, sample, g.tokens, Nn);
+    shift_to_sample<KIND>(ep, sample, g.tokens, Nn);
     const int M = g.tokens, nsplit = g.nsplit;
     int m0, n0;
     tile_origin(tile, g.tiles_m, g.tiles_n, BM, BN, m0, n0);

@@ -185,10 +185,13 @@ def test_attention_bf16_large_logits_and_poisoned_workspace():
 
 
 @pytest.mark.parametrize("case", ["huge_everywhere", "small_first_tile_then_huge", "all_far_below_zero",
-                                  "moderate_above_window"])
+                                  "moderate_above_window", "common_offset_plus_70", "common_offset_minus_30"])
 def test_attention_bf16_reference_shifts(case):
-    """The MFMA kernel keeps its exponent reference at 0 while it safely can; these inputs force
-    it to move: on the first tile, on a later tile (overflow of 2^(c s)), and downwards."""
+    """The kernel without a softmax reference checks its own sums and hands heads it cannot do to the kernel that
+    tracks a reference, which keeps that reference at 0 while it safely can; these inputs overflow 2^(c s)
+    everywhere, only from a later tile on, or underflow it (all handed over, the reference moves on the first tile,
+    on a later tile, downwards), or stay inside the range the first kernel accepts although every exponent is
+    far from zero (+70, -30: no hand-over, sums of 2^80 and 2^-20)."""
     N = 700
     print(f"attn3d bf16 reference case {case}", flush=True)
     q, k, v = I.make_qkv(1, N, 2, 64, dtype="bf16")
@@ -202,6 +205,12 @@ def test_attention_bf16_reference_shifts(case):
         scale = 1.0
         q, k = q * 0.125, k * 0.125
         q[..., 0], k[..., 0] = 8.0, -8.0              # every score ~ -64: exponent ~ -92
+        q, k = I.round_to_bf16(q.astype(np.float32)), I.round_to_bf16(k.astype(np.float32))
+    elif case.startswith("common_offset"):
+        scale = 1.0
+        q, k = q * 0.125, k * 0.125
+        a = 7.0 if case.endswith("plus_70") else 4.56     # s = +-a^2 + small: exponents ~ +70.7 / -30.0
+        q[..., 0], k[..., 0] = a, (a if case.endswith("plus_70") else -a)
         q, k = I.round_to_bf16(q.astype(np.float32)), I.round_to_bf16(k.astype(np.float32))
     else:
         scale = 1.0                                   # exponents ~ N(0, 11.5^2): some rows peak above 32
