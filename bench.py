@@ -244,7 +244,7 @@ def wl_block(net):
             "attn3d_ms": stats_ms(att), "attn3d_flop": flop, "attn3d_tflops_median": round(tf, 1),
             "attn3d_frac_of_bf16_peak": round(tf / PEAK_BF16_TFLOPS, 4),
             "note": "block forward includes embedding, modulation and the final projection; stand-alone attn3d includes "
-                    "its pass over q and k for the norm bounds and the merge launch"}
+                    "the launch that clears the head flags and the merge launch"}
 
 
 def wl_fallback_attention(net):
