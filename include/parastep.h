@@ -101,8 +101,8 @@ PS_API int dit_destroy(dit* d);
 /* Kernel path of a handle (0 after dit_create), used by every later call on it.  Low byte = mode:
  * 0 the fastest kernel for each shape, 1 the generic fp32-FMA kernels, 2 bf16 attention without
  * the key split of its last partial round of workgroups, 3 bf16 head-dim-64 attention always
- * through the kernel that tracks a softmax reference (no norm-bound shortcut), 4 projections whose
- * last partial round of workgroups is not divided along k.  Bits 8-11: tile variant of the bf16
+ * through the kernel that tracks a softmax reference (the one without is not tried first),
+ * 4 projections whose last partial round of workgroups is not divided along k.  Bits 8-11: tile variant of the bf16
  * MFMA projections (0 automatic, 1: 256x256, 2: 128x128, 3: 192x256, 4: 192x128); the variant
  * decides which workgroup computes an output and, for k >= 4096, which outputs of the last partial
  * round are summed in k pieces (a different rounding of those); nothing else.  Other values:

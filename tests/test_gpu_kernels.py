@@ -282,9 +282,32 @@ def test_attention_bf16_batch_invariance_at_a_shape_that_splits():
             assert torch.equal(one[0], full[b]), (path, b)
 
 
+def test_attention_bf16_marked_head_in_one_sample_of_a_batch():
+    """A head whose scores overflow in sample 1 only: that (sample, head) alone is handed to the reference-tracking
+    kernel, every sample still equals its single call bit for bit, and all agree with the oracle."""
+    N, H = 700, 3
+    q, k, v = I.make_qkv(3, N, H, 64, dtype="bf16")
+    q[1, :, 2, :] *= 16.0
+    k[1, :, 2, :] *= 16.0                            # exponents ~ N(0, 370^2) for sample 1, head 2
+    q, k = I.round_to_bf16(q), I.round_to_bf16(k)
+    qd, kd, vd = (dev(a, torch.bfloat16) for a in (q, k, v))
+    full = B.attn3d(qd, kd, vd, 0.125)
+    torch.cuda.synchronize()
+    assert torch.isfinite(full).all()
+    ref = O.attn3d(q, k, v, 0.125)
+    for b in range(3):
+        one = B.attn3d(qd[b:b + 1].contiguous(), kd[b:b + 1].contiguous(), vd[b:b + 1].contiguous(), 0.125)
+        assert torch.equal(one[0], full[b]), b
+        for h in range(H):
+            assert_close_bf16(host(full)[b, :, h], ref[b, :, h], 2e-2, max_tol=3e-2)
+    # the overflowing head really needs the other kernel: forced through it, the result is the same
+    forced = B.attn3d(qd[1:2].contiguous(), kd[1:2].contiguous(), vd[1:2].contiguous(), 0.125, kernel_path=3)
+    assert torch.equal(forced[0, :, 2], full[1, :, 2])
+
+
 def test_attention_bf16_mixed_heads_take_different_kernels():
-    """One head with huge scores (over the norm bound) next to ordinary heads: each head is done by the
-    kernel its bound selects, and both agree with the oracle."""
+    """One head with huge scores (its key sums overflow without a softmax reference) next to ordinary heads: the
+    first kernel marks that head, the reference-tracking kernel redoes it, and all agree with the oracle."""
     N = 700
     q, k, v = I.make_qkv(1, N, 3, 64, dtype="bf16")
     q[:, :, 1, :] *= 16.0

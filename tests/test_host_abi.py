@@ -180,7 +180,7 @@ def test_attn3d_validation():
     assert f(n=0) == -2 and f(b=0) == -2 and f(d=48) == -2 and f(d=128) == -2
     assert f(scale=0.0) == -2 and f(scale=float("nan")) == -2 and f(scale=-1.0) == -2
     assert f(o=Q) == -2 and f(q=Q + 2) == -2
-    # the bf16 head-dim-64 kernels keep two norm bounds per (batch, head) in the workspace (one 256-byte
+    # the bf16 head-dim-64 kernels keep one flag per (batch, head) in the workspace (one 256-byte
     # block here); a short sequence has no key-split pieces.  The other kernels need no scratch.
     assert L.attn3d_workspace_bytes(1, 100, 2, 64, 1) == 256
     assert f(dt=1, d=64, ws=None, wsb=0) == -4
