@@ -127,6 +127,14 @@ class ClockSampler:
                     pass
         return None
 
+    def _power_cap(self):
+        for f in glob.glob(os.path.join(self.dev, "hwmon", "hwmon*", "power1_cap")) if self.dev else []:
+            try:
+                return float(open(f).read()) / 1e6
+            except (OSError, ValueError):
+                pass
+        return None
+
     def _loop(self):
         while not self._stop.is_set():
             self.rows.append((self._current(os.path.join(self.dev, "pp_dpm_sclk")),
@@ -149,7 +157,8 @@ class ClockSampler:
             v = [r[i] for r in self.rows if r[i] is not None]
             return {"min": min(v), "median": statistics.median(v), "max": max(v)} if v else None
         return {"source": "sysfs pp_dpm_sclk / pp_dpm_mclk / hwmon power, sampled during the timed region",
-                "samples": len(self.rows), "sclk_mhz": col(0), "mclk_mhz": col(1), "power_w": col(2)}
+                "samples": len(self.rows), "sclk_mhz": col(0), "mclk_mhz": col(1), "power_w": col(2),
+                "power_cap_w": self._power_cap()}
 
 
 def stats_ms(v):
