@@ -16,9 +16,11 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hi
          "-Wno-unused-command-line-argument"]
 
 
-# per-file additions: the attention loop is a long straight-line mix of matrix, vector and LDS instructions, and the
-# scheduler's max-ILP strategy orders it about 1 % faster than the default (same instructions, same results)
-FILE_FLAGS = {"attention.hip": ["-mllvm", "-amdgpu-sched-strategy=max-ilp"]}
+# per-file additions: the attention loop is a long straight-line mix of matrix, vector and LDS instructions at the
+# register limit; of the compiler's scheduling strategies (same instructions, same results) iterative-minreg orders it
+# fastest: against the default 1.2 % at 17776 keys, against max-ilp 0.5 % (1 % at 33976 keys, 2 % for the kernel that
+# tracks a softmax reference); iterative-ilp is 8 % slower
+FILE_FLAGS = {"attention.hip": ["-mllvm", "-amdgpu-sched-strategy=iterative-minreg"]}
 
 
 def _compile(src: str, extra) -> str:
