@@ -647,7 +647,7 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
     }
 }
 
-// Check-free kernel for heads with bounded exponents (see attn_bound_kernel): p = 2^(c s), no reference.
+// The kernel without a softmax reference (see SP_SUM_MIN above): p = 2^(c s), the result checks itself at the end.
 // Work split and LDS layout as in attn_mfma_kernel (4 waves x 64 queries, K/V tiles of 64 keys straight into
 // an LDS ring, two workgroups per CU), but the loop is software-pipelined over 32-key half tiles.  In
 // every step a wave issues the 8 MFMAs of S^T for the NEXT half, the exp2 / pack instructions (and the row-sum MFMAs) of
@@ -656,7 +656,9 @@ attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, con
 // A wave that alternates long MFMA-only and ALU-only blocks (the other kernel) leaves the matrix pipe
 // idle during its ALU blocks even with a second wave on the SIMD, because both waves drift into phase;
 // a homogeneous stream keeps both units busy.  Measured on a register-only replica: 1.77 vs 1.37-1.43
-// PFLOP/s-equivalent.  (Workgroups of 8 such waves sharing each K/V tile, one per CU, measured 2-3 % slower.
+// PFLOP/s-equivalent.  (Workgroups of 8 such waves sharing each K/V tile, one per CU, measured 2-3 % slower; 8 waves
+// of 32 queries, four per SIMD, 6 % slower; the steps written out in a fixed order, one MFMA with two exp2 and one
+// pack per group, 3 % slower than the compiler's order.
 // The same loop on v_mfma_f32_16x16x32_bf16 -- query blocks of 16, the eight exponentials of a lane again the B
 // fragment of the second product -- measured +1.5 % at 17776 keys, -2.4 % at 33976, -2 to -7 % below 5000: dropped.)
 // Steps of iteration j (tile j = halves a, b):
