@@ -392,6 +392,56 @@ def kernel_target(args, torch, B, I, cfg, kpath):
         for _ in range(3):
             flops = B.ps_mfma_probe(200000, sink)
         what = {"kernel": "mfma_probe", "flop": flops}
+    elif args.kernel == "power":              # clock, power and energy per flop of each matrix kernel run back to back
+        def sustained(name, fn, flop, secs=1.5):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(); fn(); e1.record()
+            torch.cuda.synchronize()
+            reps = max(3, int(secs * 1e3 / e0.elapsed_time(e1)))
+            with ClockSampler(period=0.02) as cs:
+                e0.record()
+                for _ in range(reps):
+                    fn()
+                e1.record()
+                torch.cuda.synchronize()
+            ms, c = e0.elapsed_time(e1) / reps, cs.summary()
+            med = lambda k: c[k]["median"] if c[k] else None
+            row = {"kernel": name, "ms": round(ms, 4), "tflops": round(flop / ms / 1e9, 1) if flop else None,
+                   "sclk_mhz": med("sclk_mhz"), "power_w": med("power_w"), "power_cap_w": c["power_cap_w"]}
+            if flop and row["power_w"]:
+                row["pj_per_flop"] = round(row["power_w"] * ms * 1e-3 / flop * 1e12, 3)
+            return row
+        rows = []
+        q, k, v = (torch.randn((1, N, cfg.heads, cfg.head_dim), generator=g, device="cuda").to(torch.bfloat16)
+                   for _ in range(3))
+        o = torch.empty_like(q)
+        rows.append(sustained("attn3d", lambda: B.attn3d(q, k, v, cfg.head_dim ** -0.5, out=o, kernel_path=kpath),
+                              4.0 * N * N * D))
+        for nm, nn, kk, act in (("qkv", 3 * D, D, 0), ("out_proj", D, D, 0), ("fc1", 4 * D, D, 1), ("fc2", D, 4 * D, 0)):
+            a = torch.randn((N, kk), generator=g, device="cuda").to(torch.bfloat16)
+            w = (torch.randn((nn, kk), generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+            bias = torch.randn((nn,), generator=g, device="cuda")
+            out = torch.empty((N, nn), device="cuda", dtype=torch.bfloat16)
+            rows.append(sustained(f"dit_linear {nm}", lambda: B.dit_linear(a, w, bias, act, out=out, kernel_path=kpath),
+                                  2.0 * N * nn * kk))
+            rows.append(sustained(f"torch.matmul {nm} (hipBLASLt, no bias)", lambda: torch.matmul(a, w.t(), out=out),
+                                  2.0 * N * nn * kk))
+        sink = torch.zeros(4, device="cuda")
+        flops = B.ps_mfma_probe(20000, sink)
+        rows.append(sustained("ps_mfma_probe", lambda: B.ps_mfma_probe(20000, sink), flops))
+        n = 1 << 28
+        xs, es, ps = (torch.randn(n, generator=g, device="cuda") for _ in range(3))
+        rows.append(sustained("sampler_step 2^28", lambda: B.sampler_step(xs, es, ps, 0.99, 0.05, x_out=xs), 0))
+        del xs, es, ps
+        time.sleep(1.0)
+        with ClockSampler(period=0.02) as cs:
+            time.sleep(0.5)
+        c = cs.summary()
+        rows.append({"kernel": "idle", "sclk_mhz": c["sclk_mhz"]["median"] if c["sclk_mhz"] else None,
+                     "power_w": c["power_w"]["median"] if c["power_w"] else None, "power_cap_w": c["power_cap_w"]})
+        what = {"kernel": "power", "tokens": N, "rows": rows}
     else:
         n = 1 << 28
         xs, es, ps = (torch.randn(n, generator=g, device="cuda") for _ in range(3))
@@ -415,9 +465,9 @@ def main():
     ap.add_argument("--kernel-path", type=lambda v: int(v, 0), default=0,
                     help="kernel path of the handle and of the stand-alone calls (see dit_set_kernel_path)")
     ap.add_argument("--kernel", default=None,
-                    choices=["attn3d", "dit_linear", "layer", "copy", "sampler_step", "rel_mae", "mfma_probe"],
+                    choices=["attn3d", "dit_linear", "layer", "copy", "sampler_step", "rel_mae", "mfma_probe", "power"],
                     help="profiling target: launch only this kernel (or one DiT layer) 3 times at the workload's "
-                         "shape and exit")
+                         "shape and exit; power: each matrix kernel back to back for 1.5 s with clock and power sampled")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives are built); use --gpus 1")
