@@ -429,6 +429,37 @@ def test_a_run_in_pieces_equals_the_whole_run_bitwise(batched, mode, S, m, cyc, 
     assert torch.equal(out, x0) and torch.equal(sums2, sums) and torch.equal(traj2, traj)
 
 
+def test_a_run_in_pieces_at_the_full_shape_is_bitwise_the_whole_run():
+    """The benchmark times its steps one sampler_run_steps call per step: at its shape (30 layers, 17776 tokens, one
+    warm-up step, cycles of two) a run taken step by step -- the last step from a copy of the state in another
+    workspace -- gives the whole run's sample and per-step sums bit for bit."""
+    print("sampler_run_steps full shape, step by step", flush=True)
+    cfg = I.CONFIGS["full"]
+    _, W, d = setup("full", "std002")
+    x_T = dev(I.make_latent(cfg, 1))
+    ctx = dev(I.make_context(cfg, 1), torch.bfloat16)
+    S = 5
+    ts, a, b = B.ddim_coefficients(S)
+    sched = B.Schedule(ts, a, b, 1, [2, 2])
+    x0, sums, calls = B.sampler_run(d, sched, x_T, ctx)
+    torch.cuda.synchronize()
+    ws = B.sampler_workspace(d, sched, DEV)
+    state, sums2, out = B.SamplerState(), torch.zeros_like(sums), torch.empty_like(x_T)
+    for k in range(1, S):
+        B.sampler_run_steps(d, sched, state, k, x_T, ctx, ws, x_out=out, step_sums=sums2)
+    torch.cuda.synchronize()
+    nstate = B.sampler_state_bytes(d, sched)
+    ws2 = torch.full_like(ws, 0xFF)
+    ws2[:nstate] = ws[:nstate]
+    del ws
+    state2 = B.SamplerState.from_buffer_copy(bytes(state))
+    B.sampler_run_steps(d, sched, state2, S, None, ctx, ws2, x_out=out, step_sums=sums2)
+    torch.cuda.synchronize()
+    assert state2.step == S and state2.calls == calls
+    assert bool(torch.isfinite(x0).all())
+    assert torch.equal(out, x0) and torch.equal(sums2, sums)
+
+
 def test_run_in_pieces_rejects_states_and_stops_that_do_not_fit():
     cfg, W, d = setup("tiny_text", "unit")
     x_T, ctx = dev(I.make_latent(cfg, 1)), dev(I.make_context(cfg, 1))
